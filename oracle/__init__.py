@@ -1,0 +1,12 @@
+"""CPU oracle for shared-prefix decode attention -- TEST INFRASTRUCTURE ONLY.
+
+Plain, slow, fp64 numpy.  Only tests, the smoke check and the benchmark's
+cpu_baseline leg may import this package; the product path (the HIP library and
+its Python binding) never does, and this package imports nothing from it.
+
+Parity pins (tests/test_oracle_*.py): brute-force dense attention in Python
+loops, closed forms, placement/permutation invariance, split-and-merge
+exactness, a library SDPA for the single-model case, the e4m3 format table, and
+the Eq. 9 block-count / refcount invariants.  No function here is unpinned.
+"""
+from . import attention, fp8, layout  # noqa: F401

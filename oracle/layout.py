@@ -1,0 +1,136 @@
+"""Refcounted two-segment block table, reference policy (oracle side, test infrastructure).
+
+Problem statement followed: a pool of fixed-size cached KV blocks (Background,
+"Multi-Model Inference and Prefix Caching"); every decode module starts from
+the *same* base cache, C <- C_base (Method, Eq. 6), so a prompt's prefix blocks
+are stored once and referenced by all its requests, while each request owns
+the blocks of its model-specific segment (Efficiency Analysis, Eq. 9:
+Mem = O(L_shared + N * L_unique)).
+
+Canonical policy (fixed so that two builders can be compared bit for bit):
+  * the pool's free list starts in the caller-given order;
+  * prompts are served in ascending index, each taking ceil(Lp/B) blocks from the
+    head of the free list in logical order; then requests in ascending index,
+    each taking ceil(Ls/B) private blocks (a private segment always starts in a
+    fresh block; a partially filled last prefix block stays shared, read-only);
+  * a prefix block's refcount is the number of requests on that prompt, a
+    private block's is 1;
+  * release drops those references; blocks that reach zero are appended to the
+    free list in ascending block id;
+  * a batch that does not fit leaves the pool untouched.
+"""
+from __future__ import annotations
+
+from collections import deque
+from dataclasses import dataclass
+
+import numpy as np
+
+
+class LayoutError(Exception):
+    pass
+
+
+class OutOfBlocks(LayoutError):
+    pass
+
+
+class RefcountError(LayoutError):
+    pass
+
+
+class BlockPool:
+    def __init__(self, num_blocks: int, free_order=None):
+        order = list(range(num_blocks)) if free_order is None else [int(x) for x in free_order]
+        if sorted(order) != list(range(num_blocks)):
+            raise LayoutError("free_order must be a permutation of the pool")
+        self.num_blocks = num_blocks
+        self.free = deque(order)
+        self.refcount = np.zeros(num_blocks, dtype=np.int32)
+
+
+@dataclass
+class Layout:
+    block_size: int
+    prefix_len: np.ndarray          # [P]
+    suffix_len: np.ndarray          # [R]
+    req_prompt: np.ndarray          # [R]
+    req_model: np.ndarray           # [R]
+    prefix_blk_indptr: np.ndarray   # [P+1]
+    prefix_blk: np.ndarray
+    group_indptr: np.ndarray        # [P+1]  prompt -> its requests
+    group_req: np.ndarray           # [R]
+    suffix_blk_indptr: np.ndarray   # [R+1]
+    suffix_blk: np.ndarray
+    released: bool = False
+
+
+def build_layout(pool: BlockPool, block_size: int, prefix_len, req_prompt, req_model, suffix_len) -> Layout:
+    prefix_len = np.asarray(prefix_len, dtype=np.int64)
+    suffix_len = np.asarray(suffix_len, dtype=np.int64)
+    req_prompt = np.asarray(req_prompt, dtype=np.int64)
+    req_model = np.asarray(req_model, dtype=np.int64)
+    num_p, num_r = len(prefix_len), len(req_prompt)
+    if block_size <= 0 or (prefix_len < 0).any() or (suffix_len < 0).any():
+        raise LayoutError("negative length or bad block size")
+    if len(req_model) != num_r or len(suffix_len) != num_r:
+        raise LayoutError("request arrays differ in length")
+    if num_r and (req_prompt.min() < 0 or req_prompt.max() >= num_p or req_model.min() < 0):
+        raise LayoutError("request names an unknown prompt or model")
+    if len({(int(p), int(m)) for p, m in zip(req_prompt, req_model)}) != num_r:
+        raise LayoutError("duplicate (prompt, model) request")
+    members = [[] for _ in range(num_p)]
+    for r in range(num_r):
+        members[int(req_prompt[r])].append(r)
+    if any(len(m) == 0 for m in members):
+        raise LayoutError("prompt without a request")
+
+    nb_prefix = (prefix_len + block_size - 1) // block_size
+    nb_suffix = (suffix_len + block_size - 1) // block_size
+    needed = int(nb_prefix.sum() + nb_suffix.sum())
+    if needed > len(pool.free):
+        raise OutOfBlocks(f"need {needed} blocks, {len(pool.free)} free")
+
+    prefix_indptr = np.zeros(num_p + 1, np.int32)
+    prefix_blk = []
+    for p in range(num_p):
+        for _ in range(int(nb_prefix[p])):
+            blk = pool.free.popleft()
+            pool.refcount[blk] += len(members[p])
+            prefix_blk.append(blk)
+        prefix_indptr[p + 1] = len(prefix_blk)
+    suffix_indptr = np.zeros(num_r + 1, np.int32)
+    suffix_blk = []
+    for r in range(num_r):
+        for _ in range(int(nb_suffix[r])):
+            blk = pool.free.popleft()
+            pool.refcount[blk] += 1
+            suffix_blk.append(blk)
+        suffix_indptr[r + 1] = len(suffix_blk)
+    group_indptr = np.zeros(num_p + 1, np.int32)
+    group_req = []
+    for p in range(num_p):
+        group_req.extend(members[p])
+        group_indptr[p + 1] = len(group_req)
+    return Layout(block_size, prefix_len.astype(np.int32), suffix_len.astype(np.int32),
+                  req_prompt.astype(np.int32), req_model.astype(np.int32),
+                  prefix_indptr, np.asarray(prefix_blk, np.int32), group_indptr,
+                  np.asarray(group_req, np.int32), suffix_indptr, np.asarray(suffix_blk, np.int32))
+
+
+def release_layout(pool: BlockPool, lay: Layout) -> None:
+    if lay.released:
+        raise RefcountError("layout released twice")
+    drop = np.zeros(pool.num_blocks, dtype=np.int64)
+    for p in range(len(lay.prefix_len)):
+        k = int(lay.group_indptr[p + 1] - lay.group_indptr[p])
+        for blk in lay.prefix_blk[lay.prefix_blk_indptr[p]:lay.prefix_blk_indptr[p + 1]]:
+            drop[blk] += k
+    for blk in lay.suffix_blk:
+        drop[blk] += 1
+    if (pool.refcount < drop).any():
+        raise RefcountError("refcount underflow")
+    pool.refcount -= drop.astype(np.int32)
+    for blk in np.nonzero((drop > 0) & (pool.refcount == 0))[0]:
+        pool.free.append(int(blk))
+    lay.released = True

@@ -1,0 +1,291 @@
+"""Seeded generators for multi-model shared-prefix decode batches.
+
+A *workload* is one decode step of M task-specific decode modules over P
+prompts: every (prompt, model) request holds one query token, reads the
+prompt's prefix KV (produced once by the frozen prefill module, Method
+"Definitions and Formulation", Eq. 5-6) and its own private suffix KV (the
+model-specific segment of the Efficiency Analysis, Eq. 9).
+
+Nothing here computes attention or decides where blocks live: lengths, sharing
+structure, the pool's free order and the *stored bits* of Q/K/V are drawn from
+PCG64 streams keyed by (seed, tag, index), so every item can be regenerated on
+its own and in any order.  Draw tags: 1 lengths, 2 membership, 3 free order,
+4 Q, 5 prefix K/V (index = prompt), 6 suffix K/V (index = request).
+
+Storage formats: 'f32' -> float32, 'bf16' -> uint16 bit patterns (fp32 draws
+rounded to nearest-even), 'fp8_e4m3' -> uint8 OCP e4m3fn codes plus one fp32
+scale per (16-token block, KV head) for K and one for V, scale = absmax of the
+valid tokens of the tile / 448 (1 if the tile is all zero).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+STORAGE = {"f32": np.float32, "bf16": np.uint16, "fp8_e4m3": np.uint8}
+ELEM_BYTES = {"f32": 4, "bf16": 2, "fp8_e4m3": 1}
+# Values written into every slot no request may read (NaN in each format).
+POISON = {"f32": np.float32("nan"), "bf16": np.uint16(0x7FC0), "fp8_e4m3": np.uint8(0x7F)}
+
+CONFIG_NAMES = ("tiny", "b8", "long", "mixed", "fp8_70b")
+
+
+def _rng(seed: int, tag: int, index: int = 0) -> np.random.Generator:
+    return np.random.Generator(np.random.PCG64(np.random.SeedSequence([int(seed), int(tag), int(index)])))
+
+
+def bf16_bits_from_f32(x: np.ndarray) -> np.ndarray:
+    """Round finite float32 values to bfloat16 (nearest, ties to even); return the 16-bit patterns."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    r = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    return r.astype(np.uint16)
+
+
+def e4m3_encode(x: np.ndarray) -> np.ndarray:
+    """Quantise finite float32 values to OCP e4m3fn codes: nearest-even, saturating at +-448.
+
+    e4m3fn: 1 sign bit, 4 exponent bits (bias 7), 3 mantissa bits; exponent
+    field 0 is subnormal (multiples of 2^-9); no infinities.
+    """
+    x = np.asarray(x, dtype=np.float32)
+    sign = (np.signbit(x).astype(np.uint8) << np.uint8(7)).astype(np.uint8)
+    a = np.minimum(np.abs(x).astype(np.float64), 448.0)
+    sub = a < 2.0 ** -6
+    code_sub = np.rint(a * 512.0)                      # 0..8 ; 8 is the smallest normal
+    _, e = np.frexp(np.where(sub, 1.0, a))
+    big_e = e.astype(np.int64) - 1                     # a = (1.f) * 2^big_e
+    frac = np.rint((np.where(sub, 1.0, a) / np.exp2(big_e.astype(np.float64)) - 1.0) * 8.0).astype(np.int64)
+    carry = frac == 8
+    big_e = big_e + carry
+    frac = np.where(carry, 0, frac)
+    code_norm = ((big_e + 7) << 3) | frac
+    code = np.where(sub, code_sub.astype(np.int64), code_norm).astype(np.uint8)
+    return (code | sign).astype(np.uint8)
+
+
+@dataclass(frozen=True)
+class Geometry:
+    num_q_heads: int
+    num_kv_heads: int
+    head_dim: int
+    block_size: int
+    q_dtype: str          # 'f32' | 'bf16'
+    kv_dtype: str         # 'f32' | 'bf16' | 'fp8_e4m3'
+
+    @property
+    def group(self) -> int:
+        return self.num_q_heads // self.num_kv_heads
+
+    @property
+    def token_bytes(self) -> int:
+        """Bytes of K plus V for one token over all KV heads (b_tok)."""
+        return 2 * self.num_kv_heads * self.head_dim * ELEM_BYTES[self.kv_dtype]
+
+
+@dataclass
+class Segment:
+    """Stored bits of one KV segment: k, v are [L, Hkv, d]; scales [ceil(L/B), Hkv] or None."""
+    k: np.ndarray
+    v: np.ndarray
+    k_scale: Optional[np.ndarray] = None
+    v_scale: Optional[np.ndarray] = None
+
+
+@dataclass
+class Workload:
+    name: str
+    seed: int
+    geometry: Geometry
+    num_models: int
+    prefix_len: np.ndarray            # int32 [P]
+    req_prompt: np.ndarray            # int32 [R]
+    req_model: np.ndarray             # int32 [R]
+    suffix_len: np.ndarray            # int32 [R]
+    num_blocks: int                   # size of the physical pool
+    free_order: np.ndarray            # int32 [num_blocks], a permutation
+    _cache: Dict = field(default_factory=dict, repr=False)
+
+    @property
+    def num_prompts(self) -> int:
+        return int(self.prefix_len.shape[0])
+
+    @property
+    def num_requests(self) -> int:
+        return int(self.req_prompt.shape[0])
+
+    def blocks_needed(self) -> int:
+        b = self.geometry.block_size
+        return int(((self.prefix_len.astype(np.int64) + b - 1) // b).sum()
+                   + ((self.suffix_len.astype(np.int64) + b - 1) // b).sum())
+
+    # ---- stored bits -----------------------------------------------------
+    def _normal(self, tag: int, index: int, shape) -> np.ndarray:
+        return _rng(self.seed, tag, index).standard_normal(shape, dtype=np.float32)
+
+    def q_bits(self) -> np.ndarray:
+        g = self.geometry
+        x = self._normal(4, 0, (self.num_requests, g.num_q_heads, g.head_dim))
+        return x if g.q_dtype == "f32" else bf16_bits_from_f32(x)
+
+    def _segment(self, tag: int, index: int, length: int) -> Segment:
+        g = self.geometry
+        shape = (int(length), g.num_kv_heads, g.head_dim)
+        rng = _rng(self.seed, tag, index)
+        k = rng.standard_normal(shape, dtype=np.float32)
+        v = rng.standard_normal(shape, dtype=np.float32)
+        if g.kv_dtype == "f32":
+            return Segment(k, v)
+        if g.kv_dtype == "bf16":
+            return Segment(bf16_bits_from_f32(k), bf16_bits_from_f32(v))
+        kc, ks = _quantise_tiles(k, g.block_size)
+        vc, vs = _quantise_tiles(v, g.block_size)
+        return Segment(kc, vc, ks, vs)
+
+    def prefix_kv(self, prompt: int) -> Segment:
+        return self._segment(5, prompt, int(self.prefix_len[prompt]))
+
+    def suffix_kv(self, request: int) -> Segment:
+        return self._segment(6, request, int(self.suffix_len[request]))
+
+
+def _quantise_tiles(x: np.ndarray, block: int):
+    """x [L, H, d] float32 -> (codes uint8 [L, H, d], scales float32 [ceil(L/B), H])."""
+    length, heads, dim = x.shape
+    nb = (length + block - 1) // block
+    pad = np.zeros((nb * block, heads, dim), np.float32)
+    pad[:length] = x
+    tiles = pad.reshape(nb, block, heads, dim)
+    absmax = np.abs(tiles).max(axis=(1, 3)).astype(np.float32)          # [nb, H]
+    scale = np.where(absmax > 0, absmax / np.float32(448.0), np.float32(1.0)).astype(np.float32)
+    codes = e4m3_encode(tiles / scale[:, None, :, None])
+    return codes.reshape(nb * block, heads, dim)[:length].copy(), scale
+
+
+@dataclass
+class PoolData:
+    """Physical KV pool as the decode GPU holds it.
+
+    kv     : [num_blocks, Hkv, 2, B, d] storage dtype; [:, :, 0] = K, [:, :, 1] = V
+    scales : [num_blocks, Hkv, 2] float32 (fp8 only, else None)
+    Slots no request owns hold NaN patterns.
+    """
+    kv: np.ndarray
+    scales: Optional[np.ndarray]
+
+
+def fill_pool(w: Workload, prefix_blk_indptr, prefix_blk, suffix_blk_indptr, suffix_blk) -> PoolData:
+    """Scatter every segment's stored bits into the pool at the blocks a block table names.
+
+    The tables come from whichever layout builder is under test; this routine
+    only copies bits (token j of a segment goes to slot j % B of the segment's
+    block j // B).
+    """
+    g = w.geometry
+    b = g.block_size
+    kv = np.full((w.num_blocks, g.num_kv_heads, 2, b, g.head_dim), POISON[g.kv_dtype], dtype=STORAGE[g.kv_dtype])
+    scales = None
+    if g.kv_dtype == "fp8_e4m3":
+        scales = np.full((w.num_blocks, g.num_kv_heads, 2), np.nan, dtype=np.float32)
+
+    def put(seg: Segment, ids: np.ndarray):
+        length = seg.k.shape[0]
+        nfull = length // b
+        for which, arr in ((0, seg.k), (1, seg.v)):
+            if nfull:
+                full = arr[: nfull * b].reshape(nfull, b, g.num_kv_heads, g.head_dim).transpose(0, 2, 1, 3)
+                kv[ids[:nfull], :, which] = full
+            rem = length - nfull * b
+            if rem:
+                kv[ids[nfull], :, which, :rem] = arr[nfull * b:].transpose(1, 0, 2)
+        if scales is not None and length:
+            scales[ids, :, 0] = seg.k_scale
+            scales[ids, :, 1] = seg.v_scale
+
+    prefix_blk = np.asarray(prefix_blk)
+    suffix_blk = np.asarray(suffix_blk)
+    for p in range(w.num_prompts):
+        put(w.prefix_kv(p), prefix_blk[prefix_blk_indptr[p]:prefix_blk_indptr[p + 1]])
+    for r in range(w.num_requests):
+        put(w.suffix_kv(r), suffix_blk[suffix_blk_indptr[r]:suffix_blk_indptr[r + 1]])
+    return PoolData(kv, scales)
+
+
+def ideal_bytes(w: Workload) -> int:
+    """HBM bytes an ideal kernel moves: shared KV once + private KV (+ fp8 scales) + Q + O."""
+    g = w.geometry
+    total = int(w.prefix_len.astype(np.int64).sum() + w.suffix_len.astype(np.int64).sum()) * g.token_bytes
+    if g.kv_dtype == "fp8_e4m3":
+        total += w.blocks_needed() * g.num_kv_heads * 2 * 4
+    total += 2 * w.num_requests * g.num_q_heads * g.head_dim * ELEM_BYTES[g.q_dtype]
+    return total
+
+
+def make_workload(name: str, geometry: Geometry, num_models: int, prefix_len: Sequence[int],
+                  membership: Sequence[Sequence[int]], suffix_len: Sequence[int],
+                  pool_factor: float = 1.0, seed: int = 0) -> Workload:
+    """Build a workload from explicit lengths.
+
+    membership[p] lists the models that decode on prompt p (ascending); requests are
+    numbered prompt-major in that order and suffix_len follows the same numbering.
+    """
+    req_prompt: List[int] = []
+    req_model: List[int] = []
+    for p, models in enumerate(membership):
+        for m in models:
+            if not 0 <= m < num_models:
+                raise ValueError("model index out of range")
+            req_prompt.append(p)
+            req_model.append(m)
+    if len(suffix_len) != len(req_prompt) or len(membership) != len(prefix_len):
+        raise ValueError("length lists do not match the membership")
+    w = Workload(name, seed, geometry, num_models,
+                 np.asarray(prefix_len, np.int32), np.asarray(req_prompt, np.int32),
+                 np.asarray(req_model, np.int32), np.asarray(suffix_len, np.int32), 0, np.zeros(0, np.int32))
+    needed = w.blocks_needed()
+    w.num_blocks = int(np.ceil(pool_factor * needed)) if needed else 0
+    w.free_order = _rng(seed, 3).permutation(w.num_blocks).astype(np.int32)
+    return w
+
+
+def named_workload(name: str, seed: int = 0) -> Workload:
+    """The five benchmark configurations (synthetic stand-ins for multi-agent traffic).
+
+    tiny     M=2, 1 prompt, prefix 256, suffix 8, 4 q / 2 kv heads, d 64, fp32
+    b8       M=4, 32 prompts, prefix 4096, suffix U[1,512], 32/8 heads, d 128, bf16
+    long     M=8, 8 prompts, prefix 32768, suffix U[256,2048], bf16, pool 1.5x
+    mixed    M=6, 256 prompts, prefix log-uniform [512,16384], 2-6 models per prompt,
+             suffix U[1,1024], bf16
+    fp8_70b  M=4, 64 prompts, prefix 8192, suffix U[1,512], 64/8 heads, bf16 Q, e4m3 KV
+    """
+    len_rng = _rng(seed, 1)
+    mem_rng = _rng(seed, 2)
+    if name == "tiny":
+        geo = Geometry(4, 2, 64, 16, "f32", "f32")
+        return make_workload(name, geo, 2, [256], [[0, 1]], [8, 8], 1.0, seed)
+    if name == "b8":
+        geo = Geometry(32, 8, 128, 16, "bf16", "bf16")
+        m, p = 4, 32
+        return make_workload(name, geo, m, [4096] * p, [list(range(m))] * p,
+                             len_rng.integers(1, 513, size=p * m), 1.0, seed)
+    if name == "long":
+        geo = Geometry(32, 8, 128, 16, "bf16", "bf16")
+        m, p = 8, 8
+        return make_workload(name, geo, m, [32768] * p, [list(range(m))] * p,
+                             len_rng.integers(256, 2049, size=p * m), 1.5, seed)
+    if name == "mixed":
+        geo = Geometry(32, 8, 128, 16, "bf16", "bf16")
+        m, p = 6, 256
+        u = len_rng.uniform(np.log(512.0), np.log(16384.0), size=p)
+        prefix = np.clip(np.floor(np.exp(u)), 512, 16384).astype(np.int64)
+        sizes = mem_rng.integers(2, 7, size=p)
+        membership = [sorted(mem_rng.choice(m, size=int(k), replace=False).tolist()) for k in sizes]
+        nreq = int(sizes.sum())
+        return make_workload(name, geo, m, prefix, membership, len_rng.integers(1, 1025, size=nreq), 1.0, seed)
+    if name == "fp8_70b":
+        geo = Geometry(64, 8, 128, 16, "bf16", "fp8_e4m3")
+        m, p = 4, 64
+        return make_workload(name, geo, m, [8192] * p, [list(range(m))] * p,
+                             len_rng.integers(1, 513, size=p * m), 1.0, seed)
+    raise KeyError(f"unknown workload {name!r}; choose from {CONFIG_NAMES}")
