@@ -1,0 +1,157 @@
+/*
+ * prefillshare.h -- C ABI of the shared-prefix decode attention library for MI355X (gfx950).
+ *
+ * Setting (PrefillShare, arXiv 2602.12029): a frozen base module prefills a prompt once and
+ * produces the shared cache C_base (Method, Eq. 5); each of several task-specific decode modules
+ * starts from C <- C_base and appends its own keys/values while decoding (Method, Eq. 6; Background
+ * Eq. 2 and Eq. 4).  On the decode GPU a prompt's prefix KV is therefore stored once and read by
+ * every model, and each (prompt, model) request owns only its model-specific segment (Efficiency
+ * Analysis, Eq. 9: Mem = O(L_shared + N * L_unique)).  This library is the attention of one decode
+ * step of one layer for a batch of such requests: a query token per request attends over
+ * [shared prefix ; private suffix].
+ *
+ * Conventions
+ *   - Every function returns an int32 status (PS_OK or a PS_ERR_* code); nothing throws.
+ *   - "host" pointers are ordinary process memory, "device" pointers are HIP device memory on the
+ *     current device.  The caller owns all device memory (KV pool, scales, Q, O, workspace, the
+ *     uploaded table blob); the library owns only the opaque host objects it creates.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Kernels are enqueued
+ *     asynchronously and never synchronise; ps_layout_upload copies from pageable host memory and
+ *     may block the host until the copy is staged.
+ *   - q and out are [R][Hq][d] contiguous in q_dtype.  The KV pool is addressed as
+ *         elem(block, kv_head, which, slot, c) = block*kv_stride_block + kv_head*kv_stride_head
+ *                                               + which*kv_stride_kv + slot*kv_stride_tok + c
+ *     (which: 0 = K, 1 = V; strides in elements; the head_dim axis is contiguous; every stride must
+ *     be a multiple of 16 bytes).  kv_scales (fp8 only) is [num_blocks][Hkv][2] fp32: K scale, V scale.
+ *   - q head h reads KV head h / (Hq / Hkv).  There is no mask: every stored token of both segments
+ *     is attended to.  Scores are scaled by 1/sqrt(head_dim).
+ *   - A partial state of a set of tokens is (o: the softmax-weighted value average over that set,
+ *     fp32[d]; lse: natural-log sum of exp(score) over that set, fp32).  The empty set is (0, -inf).
+ */
+#ifndef PREFILLSHARE_H
+#define PREFILLSHARE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  PS_OK = 0,
+  PS_ERR_INVALID_ARG = 1, /* NULL pointer, negative size, index out of range, duplicate request   */
+  PS_ERR_SHAPE = 2,       /* geometry the kernels cannot address (Hq % Hkv, strides, alignment)    */
+  PS_ERR_OOM = 3,         /* the pool has too few free blocks; nothing was allocated              */
+  PS_ERR_REFCOUNT = 4,    /* release would drive a refcount below zero (wrong pool)               */
+  PS_ERR_UNSUPPORTED = 5, /* dtype / head_dim / block_size combination without a kernel           */
+  PS_ERR_DEVICE = 6       /* a HIP call failed; ps_last_hip_error() returns its code              */
+};
+
+enum { PS_F32 = 0, PS_BF16 = 1, PS_FP8_E4M3 = 2 /* OCP e4m3fn, KV only */ };
+
+/* kernel family used for a pass */
+enum { PS_VARIANT_AUTO = 0, PS_VARIANT_WAVE = 1 /* fp32 wavefront-reduction */, PS_VARIANT_MFMA = 2 };
+
+typedef struct ps_pool ps_pool;     /* host: free list + refcounts of the physical blocks          */
+typedef struct ps_layout ps_layout; /* host: block tables, sharing groups and split plan of a batch */
+
+typedef struct ps_geometry {
+  int32_t num_q_heads, num_kv_heads, head_dim, block_size;
+  int32_t q_dtype, kv_dtype;
+  int64_t kv_stride_block, kv_stride_head, kv_stride_kv, kv_stride_tok; /* in elements */
+} ps_geometry;
+
+typedef struct ps_plan_options {
+  int32_t prefix_chunk_tokens; /* tokens of a shared prefix handled by one workgroup; 0 = choose  */
+  int32_t suffix_chunk_tokens; /* same for private suffixes; 0 = choose                           */
+  int32_t prefix_variant;      /* PS_VARIANT_*                                                    */
+  int32_t suffix_variant;      /* PS_VARIANT_*                                                    */
+  int32_t num_cus;             /* compute units to plan for; 0 = 256                              */
+} ps_plan_options;
+
+/* ---- block pool (pool of cached KV blocks, Background "Prefix Caching") -------------------------
+ * ps_pool_create: num_blocks >= 0; free_order = host permutation of [0, num_blocks) giving the
+ * initial free-list order, or NULL for ascending.  *out receives the pool. */
+int32_t ps_pool_create(int32_t num_blocks, const int32_t* free_order, ps_pool** out);
+int32_t ps_pool_destroy(ps_pool* pool);
+int32_t ps_pool_num_free(const ps_pool* pool, int32_t* out);
+/* Copies the free list (head first) into host out[capacity]; *count receives its length. */
+int32_t ps_pool_free_list(const ps_pool* pool, int32_t* out, int32_t capacity, int32_t* count);
+/* *refcount points at the pool's own int32[num_blocks]; valid until ps_pool_destroy. */
+int32_t ps_pool_refcounts(const ps_pool* pool, const int32_t** refcount);
+
+/* ---- ps_kv_layout: the refcounted two-segment block table (Eq. 6 "C <- C_base", Eq. 9) ----------
+ * Builds the table of one decode batch.  Host inputs: prefix_len[P]; for each request its prompt
+ * index, model index and private suffix length (tokens; 0 allowed).  Policy: prompts in ascending
+ * index take ceil(Lp/B) blocks each from the head of the free list, then requests in ascending index
+ * take ceil(Ls/B) private blocks each; a prefix block's refcount rises by the number of requests on
+ * that prompt, a private block's by 1.  A partially filled last prefix block stays shared and
+ * read-only; a private segment always starts in a fresh block.  Also derives a split plan (how the
+ * segments are cut into workgroup-sized chunks) with default options.
+ * Errors: PS_ERR_INVALID_ARG (NULL, negative length, unknown prompt, duplicate (prompt, model), a
+ * prompt with no request), PS_ERR_SHAPE / PS_ERR_UNSUPPORTED (geometry), PS_ERR_OOM (pool untouched). */
+int32_t ps_kv_layout(ps_pool* pool, const ps_geometry* geometry,
+                     int32_t num_prompts, const int32_t* prefix_len,
+                     int32_t num_requests, const int32_t* req_prompt, const int32_t* req_model,
+                     const int32_t* suffix_len, ps_layout** out);
+/* Drops the batch's references (blocks reaching zero join the free-list tail in ascending id) and
+ * destroys the layout.  PS_ERR_REFCOUNT leaves pool and layout unchanged. */
+int32_t ps_layout_release(ps_pool* pool, ps_layout* layout);
+/* Host views of the tables (int32, CSR), valid until release.  Any output pointer may be NULL.
+ * prefix_blk_indptr[P+1], prefix_blk[..], group_indptr[P+1], group_req[R] (a prompt's requests,
+ * ascending), suffix_blk_indptr[R+1], suffix_blk[..]. */
+int32_t ps_layout_tables(const ps_layout* layout,
+                         const int32_t** prefix_blk_indptr, const int32_t** prefix_blk,
+                         const int32_t** group_indptr, const int32_t** group_req,
+                         const int32_t** suffix_blk_indptr, const int32_t** suffix_blk);
+
+/* ---- split plan -------------------------------------------------------------------------------
+ * Re-derives the plan with explicit options (NULL = defaults).  Invalidates earlier uploads of this
+ * layout's table blob and the sizes reported below. */
+int32_t ps_layout_replan(ps_layout* layout, const ps_plan_options* options);
+/* Plan introspection (host, valid until the next replan/release).  items is int32[num_items][8]:
+ * {first block index in the concatenated (prefix ++ suffix) block array, token begin, token end,
+ *  first index into the request list, number of requests, kv head, split index within the request's
+ *  partial states, 0 = prefix / 1 = suffix}.  slot_base is int32[R+1]: request r owns partial-state
+ * slots [slot_base[r], slot_base[r+1]), prefix splits first. */
+int32_t ps_layout_plan(const ps_layout* layout, int32_t* num_items, const int32_t** items,
+                       const int32_t** slot_base, int32_t* prefix_variant, int32_t* suffix_variant);
+
+/* Size of the int32 table blob, and its copy to device memory (at least that many bytes, 16-byte
+ * aligned) on `stream`. */
+int64_t ps_layout_device_bytes(const ps_layout* layout);
+int32_t ps_layout_upload(const ps_layout* layout, void* dev_tables, void* stream);
+/* Partial-state workspace: fp32 o[num_slots][Hq][d] followed, at lse_offset_bytes, by fp32
+ * lse[num_slots][Hq]. */
+int64_t ps_workspace_bytes(const ps_layout* layout);
+int32_t ps_workspace_layout(const ps_layout* layout, int64_t* num_slots, int64_t* lse_offset_bytes);
+
+/* ---- attention passes (device pointers; asynchronous on `stream`) ---------------------------------
+ * ps_prefix_attention: for every prompt, KV head and chunk of the prompt's shared prefix, streams the
+ * chunk's K/V blocks once and applies them to the queries of every request on that prompt and every
+ * q head of the KV head's group; writes one partial state per (request, q head, prefix split).
+ * ps_suffix_attention: the same over each request's private blocks (flash-decoding split over tokens).
+ * Both write only their own slots of `workspace`. */
+int32_t ps_prefix_attention(const ps_layout* layout, const void* dev_tables, const void* q,
+                            const void* kv_pool, const float* kv_scales, void* workspace, void* stream);
+int32_t ps_suffix_attention(const ps_layout* layout, const void* dev_tables, const void* q,
+                            const void* kv_pool, const float* kv_scales, void* workspace, void* stream);
+/* ps_merge_states: per (request, q head) combines the request's partial states,
+ * lse = log sum_i exp(lse_i), o = sum_i exp(lse_i - lse) o_i, and writes out[R][Hq][d] in q_dtype
+ * (bf16: round to nearest even) and, if out_lse != NULL, lse as fp32 [R][Hq].  A request with no
+ * tokens at all gets o = 0, lse = -inf.  `workspace` may have been filled by the two passes or by the
+ * caller in the documented format. */
+int32_t ps_merge_states(const ps_layout* layout, const void* dev_tables, const void* workspace,
+                        void* out, float* out_lse, void* stream);
+/* ps_decode_attention: the whole step -- prefix pass, suffix pass, merge -- on one stream. */
+int32_t ps_decode_attention(const ps_layout* layout, const void* dev_tables, const void* q,
+                            const void* kv_pool, const float* kv_scales, void* workspace,
+                            void* out, float* out_lse, void* stream);
+
+const char* ps_strerror(int32_t status);
+int32_t ps_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PREFILLSHARE_H */

@@ -1,0 +1,234 @@
+"""ctypes binding of libprefillshare.so: same names as include/prefillshare.h.
+
+Host arrays are numpy int32 arrays; device pointers and the stream are plain
+integers (e.g. torch.Tensor.data_ptr(), torch.cuda.current_stream().cuda_stream).
+Every wrapper raises PsError on a non-zero status.  Opaque handles are returned
+as ctypes void pointers.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+PS_OK, PS_ERR_INVALID_ARG, PS_ERR_SHAPE, PS_ERR_OOM, PS_ERR_REFCOUNT, PS_ERR_UNSUPPORTED, PS_ERR_DEVICE = range(7)
+PS_F32, PS_BF16, PS_FP8_E4M3 = 0, 1, 2
+PS_VARIANT_AUTO, PS_VARIANT_WAVE, PS_VARIANT_MFMA = 0, 1, 2
+DTYPE_CODE = {"f32": PS_F32, "bf16": PS_BF16, "fp8_e4m3": PS_FP8_E4M3}
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libprefillshare.so")
+
+EXPORTS = [
+    "ps_pool_create", "ps_pool_destroy", "ps_pool_num_free", "ps_pool_free_list", "ps_pool_refcounts",
+    "ps_kv_layout", "ps_layout_release", "ps_layout_tables", "ps_layout_replan", "ps_layout_plan",
+    "ps_layout_device_bytes", "ps_layout_upload", "ps_workspace_bytes", "ps_workspace_layout",
+    "ps_prefix_attention", "ps_suffix_attention", "ps_merge_states", "ps_decode_attention",
+    "ps_strerror", "ps_last_hip_error",
+]
+
+
+class PsError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _lib().ps_strerror(status).decode()
+        if status == PS_ERR_DEVICE:
+            msg += f" [hip error {_lib().ps_last_hip_error()}]"
+        super().__init__(f"{where}: {msg} (status {status})")
+
+
+class ps_geometry(C.Structure):
+    _fields_ = [("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("block_size", C.c_int32), ("q_dtype", C.c_int32), ("kv_dtype", C.c_int32),
+                ("kv_stride_block", C.c_int64), ("kv_stride_head", C.c_int64),
+                ("kv_stride_kv", C.c_int64), ("kv_stride_tok", C.c_int64)]
+
+
+class ps_plan_options(C.Structure):
+    _fields_ = [("prefix_chunk_tokens", C.c_int32), ("suffix_chunk_tokens", C.c_int32),
+                ("prefix_variant", C.c_int32), ("suffix_variant", C.c_int32), ("num_cus", C.c_int32)]
+
+
+_LIB = None
+_I32P = C.POINTER(C.c_int32)
+
+
+def _lib():
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2602_12029_amd.build` "
+                              "(there is no CPU fallback)")
+        lib = C.CDLL(LIB_PATH)
+        lib.ps_strerror.restype = C.c_char_p
+        lib.ps_strerror.argtypes = [C.c_int32]
+        lib.ps_layout_device_bytes.restype = C.c_int64
+        lib.ps_workspace_bytes.restype = C.c_int64
+        for name in EXPORTS:
+            getattr(lib, name)                      # fail early if a symbol is missing
+        _LIB = lib
+    return _LIB
+
+
+def _check(status: int, where: str):
+    if status != PS_OK:
+        raise PsError(status, where)
+
+
+def _i32(a):
+    arr = np.ascontiguousarray(a, dtype=np.int32)
+    return arr, arr.ctypes.data_as(_I32P)
+
+
+def _view(ptr, n) -> np.ndarray:
+    if n == 0:
+        return np.zeros(0, np.int32)
+    return np.ctypeslib.as_array(ptr, shape=(n,)).copy()
+
+
+def geometry(num_q_heads, num_kv_heads, head_dim, block_size, q_dtype, kv_dtype, strides=None) -> ps_geometry:
+    """strides = (block, head, kv, tok) in elements; default is the dense [blk][Hkv][2][B][d] pool."""
+    if strides is None:
+        tok = head_dim
+        kv = block_size * tok
+        head = 2 * kv
+        strides = (num_kv_heads * head, head, kv, tok)
+    return ps_geometry(num_q_heads, num_kv_heads, head_dim, block_size,
+                       DTYPE_CODE.get(q_dtype, q_dtype), DTYPE_CODE.get(kv_dtype, kv_dtype), *strides)
+
+
+def plan_options(prefix_chunk_tokens=0, suffix_chunk_tokens=0, prefix_variant=0, suffix_variant=0, num_cus=0):
+    return ps_plan_options(prefix_chunk_tokens, suffix_chunk_tokens, prefix_variant, suffix_variant, num_cus)
+
+
+# ---- pool ------------------------------------------------------------------------------------------
+def ps_pool_create(num_blocks: int, free_order=None):
+    out = C.c_void_p()
+    if free_order is None:
+        st = _lib().ps_pool_create(C.c_int32(num_blocks), None, C.byref(out))
+    else:
+        arr, p = _i32(free_order)
+        if arr.shape != (num_blocks,):
+            raise ValueError("free_order must have num_blocks entries")
+        st = _lib().ps_pool_create(C.c_int32(num_blocks), p, C.byref(out))
+    _check(st, "ps_pool_create")
+    return out
+
+
+def ps_pool_destroy(pool):
+    _check(_lib().ps_pool_destroy(pool), "ps_pool_destroy")
+
+
+def ps_pool_num_free(pool) -> int:
+    out = C.c_int32()
+    _check(_lib().ps_pool_num_free(pool, C.byref(out)), "ps_pool_num_free")
+    return out.value
+
+
+def ps_pool_free_list(pool) -> np.ndarray:
+    n = ps_pool_num_free(pool)
+    buf = np.zeros(max(n, 1), np.int32)
+    cnt = C.c_int32()
+    _check(_lib().ps_pool_free_list(pool, buf.ctypes.data_as(_I32P), C.c_int32(n), C.byref(cnt)), "ps_pool_free_list")
+    return buf[:cnt.value].copy()
+
+
+def ps_pool_refcounts(pool, num_blocks: int) -> np.ndarray:
+    p = _I32P()
+    _check(_lib().ps_pool_refcounts(pool, C.byref(p)), "ps_pool_refcounts")
+    return _view(p, num_blocks)
+
+
+# ---- layout ----------------------------------------------------------------------------------------
+def ps_kv_layout(pool, geo: ps_geometry, prefix_len, req_prompt, req_model, suffix_len):
+    pl, plp = _i32(prefix_len)
+    rp, rpp = _i32(req_prompt)
+    rm, rmp = _i32(req_model)
+    sl, slp = _i32(suffix_len)
+    if not (rp.shape == rm.shape == sl.shape):
+        raise ValueError("request arrays differ in length")
+    out = C.c_void_p()
+    st = _lib().ps_kv_layout(pool, C.byref(geo), C.c_int32(pl.size), plp, C.c_int32(rp.size), rpp, rmp, slp, C.byref(out))
+    _check(st, "ps_kv_layout")
+    return out
+
+
+def ps_layout_release(pool, layout):
+    _check(_lib().ps_layout_release(pool, layout), "ps_layout_release")
+
+
+def ps_layout_tables(layout, num_prompts: int, num_requests: int) -> dict:
+    ptrs = [_I32P() for _ in range(6)]
+    _check(_lib().ps_layout_tables(layout, *[C.byref(p) for p in ptrs]), "ps_layout_tables")
+    pbi = _view(ptrs[0], num_prompts + 1)
+    gi = _view(ptrs[2], num_prompts + 1)
+    sbi = _view(ptrs[4], num_requests + 1)
+    return {"prefix_blk_indptr": pbi, "prefix_blk": _view(ptrs[1], int(pbi[-1])),
+            "group_indptr": gi, "group_req": _view(ptrs[3], num_requests),
+            "suffix_blk_indptr": sbi, "suffix_blk": _view(ptrs[5], int(sbi[-1]))}
+
+
+def ps_layout_replan(layout, options: ps_plan_options | None = None):
+    st = _lib().ps_layout_replan(layout, C.byref(options) if options is not None else None)
+    _check(st, "ps_layout_replan")
+
+
+def ps_layout_plan(layout, num_requests: int) -> dict:
+    n = C.c_int32()
+    items, slots = _I32P(), _I32P()
+    pv, sv = C.c_int32(), C.c_int32()
+    _check(_lib().ps_layout_plan(layout, C.byref(n), C.byref(items), C.byref(slots), C.byref(pv), C.byref(sv)),
+           "ps_layout_plan")
+    return {"items": _view(items, n.value * 8).reshape(-1, 8), "slot_base": _view(slots, num_requests + 1),
+            "prefix_variant": pv.value, "suffix_variant": sv.value}
+
+
+def ps_layout_device_bytes(layout) -> int:
+    return int(_lib().ps_layout_device_bytes(layout))
+
+
+def ps_layout_upload(layout, dev_tables: int, stream: int = 0):
+    _check(_lib().ps_layout_upload(layout, C.c_void_p(dev_tables), C.c_void_p(stream)), "ps_layout_upload")
+
+
+def ps_workspace_bytes(layout) -> int:
+    return int(_lib().ps_workspace_bytes(layout))
+
+
+def ps_workspace_layout(layout):
+    n, off = C.c_int64(), C.c_int64()
+    _check(_lib().ps_workspace_layout(layout, C.byref(n), C.byref(off)), "ps_workspace_layout")
+    return n.value, off.value
+
+
+# ---- attention passes ------------------------------------------------------------------------------
+def _p(x):
+    return C.c_void_p(int(x) if x else None)
+
+
+def ps_prefix_attention(layout, dev_tables, q, kv_pool, kv_scales, workspace, stream=0):
+    _check(_lib().ps_prefix_attention(layout, _p(dev_tables), _p(q), _p(kv_pool), _p(kv_scales), _p(workspace),
+                                      _p(stream)), "ps_prefix_attention")
+
+
+def ps_suffix_attention(layout, dev_tables, q, kv_pool, kv_scales, workspace, stream=0):
+    _check(_lib().ps_suffix_attention(layout, _p(dev_tables), _p(q), _p(kv_pool), _p(kv_scales), _p(workspace),
+                                      _p(stream)), "ps_suffix_attention")
+
+
+def ps_merge_states(layout, dev_tables, workspace, out, out_lse=0, stream=0):
+    _check(_lib().ps_merge_states(layout, _p(dev_tables), _p(workspace), _p(out), _p(out_lse), _p(stream)),
+           "ps_merge_states")
+
+
+def ps_decode_attention(layout, dev_tables, q, kv_pool, kv_scales, workspace, out, out_lse=0, stream=0):
+    _check(_lib().ps_decode_attention(layout, _p(dev_tables), _p(q), _p(kv_pool), _p(kv_scales), _p(workspace),
+                                      _p(out), _p(out_lse), _p(stream)), "ps_decode_attention")
+
+
+def ps_strerror(status: int) -> str:
+    return _lib().ps_strerror(status).decode()
+
+
+def ps_last_hip_error() -> int:
+    return int(_lib().ps_last_hip_error())

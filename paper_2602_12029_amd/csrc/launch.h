@@ -1,0 +1,16 @@
+// Host-callable launchers of the device passes (defined in the .hip files).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "device_common.h"
+
+namespace psdev {
+
+bool wave_supported(const ps_geometry& g);
+int32_t launch_wave_attention(const AttnParams& p, const ps_geometry& g, int item_begin, int n_items, hipStream_t st);
+int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max_rows, int item_begin, int n_items,
+                              hipStream_t st);
+int32_t launch_merge(const int32_t* slot_base, const float* ws_o, const float* ws_lse, void* out, float* out_lse,
+                     int num_requests, const ps_geometry& g, hipStream_t st);
+
+}  // namespace psdev

@@ -1,0 +1,370 @@
+// Host side of the library: block pool, the refcounted two-segment block table (ps_kv_layout) and
+// the split plan.  Pure C++ -- no HIP calls -- so it is testable without a GPU.
+//
+// Sharing rule implemented here: a prompt's prefix blocks are allocated once and referenced by every
+// request on that prompt (each decode module starts from the same base cache, Method Eq. 6), and
+// only the model-specific segment is private (Efficiency Analysis Eq. 9).
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <numeric>
+#include <set>
+#include <utility>
+
+#include "ps_internal.h"
+
+namespace {
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline int64_t round_up(int64_t a, int64_t b) { return ceil_div(a, b) * b; }
+
+int32_t check_geometry(const ps_geometry& g) {
+  if (g.num_q_heads <= 0 || g.num_kv_heads <= 0 || g.head_dim <= 0 || g.block_size <= 0) return PS_ERR_SHAPE;
+  if (g.num_q_heads % g.num_kv_heads != 0) return PS_ERR_SHAPE;
+  if (g.q_dtype != PS_F32 && g.q_dtype != PS_BF16) return PS_ERR_UNSUPPORTED;
+  if (g.kv_dtype != PS_F32 && g.kv_dtype != PS_BF16 && g.kv_dtype != PS_FP8_E4M3) return PS_ERR_UNSUPPORTED;
+  const int64_t esz = g.kv_dtype == PS_F32 ? 4 : (g.kv_dtype == PS_BF16 ? 2 : 1);
+  const int64_t strides[4] = {g.kv_stride_block, g.kv_stride_head, g.kv_stride_kv, g.kv_stride_tok};
+  for (int64_t s : strides)
+    if (s <= 0 || (s * esz) % 16 != 0) return PS_ERR_SHAPE;
+  if (g.kv_stride_tok < g.head_dim) return PS_ERR_SHAPE;
+  return PS_OK;
+}
+
+}  // namespace
+
+bool ps_mfma_supported(const ps_geometry& g) {
+  return g.q_dtype == PS_BF16 && (g.kv_dtype == PS_BF16 || g.kv_dtype == PS_FP8_E4M3) && g.head_dim == 128 &&
+         g.block_size % 16 == 0 && (g.num_q_heads / g.num_kv_heads) <= 64;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Split plan: cut every segment into token chunks of (nearly) equal size, one workgroup each; a
+// request's partial states are numbered prefix chunks first, then its suffix chunks.
+int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
+  ps_plan_options opt{};
+  if (user) opt = *user;
+  if (opt.prefix_chunk_tokens < 0 || opt.suffix_chunk_tokens < 0 || opt.num_cus < 0) return PS_ERR_INVALID_ARG;
+  auto bad_variant = [](int32_t v) { return v != PS_VARIANT_AUTO && v != PS_VARIANT_WAVE && v != PS_VARIANT_MFMA; };
+  if (bad_variant(opt.prefix_variant) || bad_variant(opt.suffix_variant)) return PS_ERR_INVALID_ARG;
+  const ps_geometry& g = lay->geo;
+  const bool mfma_ok = ps_mfma_supported(g);
+  if ((opt.prefix_variant == PS_VARIANT_MFMA || opt.suffix_variant == PS_VARIANT_MFMA) && !mfma_ok)
+    return PS_ERR_UNSUPPORTED;
+  const int32_t group = g.num_q_heads / g.num_kv_heads;
+  const int32_t num_cus = opt.num_cus ? opt.num_cus : 256;
+
+  // chunk boundaries fall on block boundaries and on the 32-token MFMA tile
+  const int64_t granule = std::lcm<int64_t>(g.block_size, 32);
+  int64_t total = 0;
+  for (int32_t l : lay->prefix_len) total += l;
+  for (int32_t l : lay->suffix_len) total += l;
+  total *= g.num_kv_heads;
+  const int64_t ideal = std::max<int64_t>(1, ceil_div(total, int64_t(num_cus) * 4));
+  auto pick = [&](int32_t asked) -> int64_t {
+    if (asked > 0) return round_up(asked, granule);
+    return std::min<int64_t>(std::max<int64_t>(round_up(ideal, granule), round_up(256, granule)), round_up(4096, granule));
+  };
+  const int64_t prefix_chunk = pick(opt.prefix_chunk_tokens);
+  const int64_t suffix_chunk = pick(opt.suffix_chunk_tokens);
+  auto resolve = [&](int32_t v) { return v == PS_VARIANT_AUTO ? (mfma_ok ? PS_VARIANT_MFMA : PS_VARIANT_WAVE) : v; };
+
+  lay->opt = opt;
+  lay->prefix_variant = resolve(opt.prefix_variant);
+  lay->suffix_variant = resolve(opt.suffix_variant);
+  lay->prefix_chunk = int32_t(prefix_chunk);
+  lay->suffix_chunk = int32_t(suffix_chunk);
+
+  // equal-sized chunks of a segment of `len` tokens: returns the chunk size used
+  auto chunking = [&](int64_t len, int64_t chunk, int32_t* n) -> int64_t {
+    if (len <= 0) { *n = 0; return chunk; }
+    const int64_t count = ceil_div(len, chunk);
+    const int64_t size = round_up(ceil_div(len, count), granule);
+    *n = int32_t(ceil_div(len, size));
+    return size;
+  };
+
+  const int32_t P = lay->num_prompts, R = lay->num_requests;
+  std::vector<int32_t> nsplit_prefix(P), nsplit_suffix(R);
+  std::vector<ps_item> prefix_items, suffix_items;
+  const int32_t max_req = std::max(1, 64 / group);
+  const int32_t total_prefix_blocks = int32_t(lay->prefix_blk.size());
+  lay->max_rows_prefix = 0;
+  for (int32_t p = 0; p < P; ++p) {
+    int32_t n = 0;
+    const int64_t size = chunking(lay->prefix_len[p], prefix_chunk, &n);
+    nsplit_prefix[p] = n;
+    const int32_t g0 = lay->group_indptr[p], g1 = lay->group_indptr[p + 1];
+    for (int32_t c = 0; c < n; ++c)
+      for (int32_t h = 0; h < g.num_kv_heads; ++h)
+        for (int32_t m0 = g0; m0 < g1; m0 += max_req) {
+          ps_item it{};
+          it.blk_off = lay->prefix_blk_indptr[p];
+          it.tok_begin = int32_t(c * size);
+          it.tok_end = int32_t(std::min<int64_t>(lay->prefix_len[p], (c + 1) * size));
+          it.req_off = m0;
+          it.n_req = std::min(max_req, g1 - m0);
+          it.kv_head = h;
+          it.split_local = c;
+          it.kind = 0;
+          lay->max_rows_prefix = std::max(lay->max_rows_prefix, it.n_req * group);
+          prefix_items.push_back(it);
+        }
+  }
+  for (int32_t r = 0; r < R; ++r) {
+    int32_t n = 0;
+    const int64_t size = chunking(lay->suffix_len[r], suffix_chunk, &n);
+    nsplit_suffix[r] = n;
+    for (int32_t c = 0; c < n; ++c)
+      for (int32_t h = 0; h < g.num_kv_heads; ++h) {
+        ps_item it{};
+        it.blk_off = total_prefix_blocks + lay->suffix_blk_indptr[r];
+        it.tok_begin = int32_t(c * size);
+        it.tok_end = int32_t(std::min<int64_t>(lay->suffix_len[r], (c + 1) * size));
+        it.req_off = R + r;  // identity part of the request list
+        it.n_req = 1;
+        it.kv_head = h;
+        it.split_local = nsplit_prefix[lay->req_prompt[r]] + c;
+        it.kind = 1;
+        suffix_items.push_back(it);
+      }
+  }
+  auto by_cost = [](const ps_item& a, const ps_item& b) { return (a.tok_end - a.tok_begin) > (b.tok_end - b.tok_begin); };
+  std::stable_sort(prefix_items.begin(), prefix_items.end(), by_cost);
+  std::stable_sort(suffix_items.begin(), suffix_items.end(), by_cost);
+  lay->num_prefix_items = int32_t(prefix_items.size());
+  lay->items = std::move(prefix_items);
+  lay->items.insert(lay->items.end(), suffix_items.begin(), suffix_items.end());
+
+  lay->slot_base.assign(R + 1, 0);
+  int64_t slots = 0;
+  for (int32_t r = 0; r < R; ++r) {
+    slots += nsplit_prefix[lay->req_prompt[r]] + nsplit_suffix[r];
+    if (slots > INT32_MAX) return PS_ERR_INVALID_ARG;
+    lay->slot_base[r + 1] = int32_t(slots);
+  }
+  lay->num_slots = slots;
+
+  // device blob: [block ids: prefix ++ suffix][request list: group_req ++ identity][items][slot_base]
+  auto pad4 = [](int64_t n) { return (n + 3) / 4 * 4; };
+  lay->off_blk = 0;
+  lay->off_req = pad4(lay->off_blk + int64_t(lay->prefix_blk.size() + lay->suffix_blk.size()));
+  lay->off_items = pad4(lay->off_req + 2 * int64_t(R));
+  lay->off_slot = pad4(lay->off_items + 8 * int64_t(lay->items.size()));
+  const int64_t words = pad4(lay->off_slot + R + 1);
+  lay->blob.assign(size_t(std::max<int64_t>(words, 4)), 0);
+  int32_t* b = lay->blob.data();
+  std::copy(lay->prefix_blk.begin(), lay->prefix_blk.end(), b + lay->off_blk);
+  std::copy(lay->suffix_blk.begin(), lay->suffix_blk.end(), b + lay->off_blk + lay->prefix_blk.size());
+  std::copy(lay->group_req.begin(), lay->group_req.end(), b + lay->off_req);
+  for (int32_t r = 0; r < R; ++r) b[lay->off_req + R + r] = r;
+  if (!lay->items.empty()) std::memcpy(b + lay->off_items, lay->items.data(), lay->items.size() * sizeof(ps_item));
+  std::copy(lay->slot_base.begin(), lay->slot_base.end(), b + lay->off_slot);
+  return PS_OK;
+}
+
+// ---------------------------------------------------------------------------------------------------
+extern "C" {
+
+int32_t ps_pool_create(int32_t num_blocks, const int32_t* free_order, ps_pool** out) {
+  if (!out || num_blocks < 0) return PS_ERR_INVALID_ARG;
+  ps_pool* p = new (std::nothrow) ps_pool();
+  if (!p) return PS_ERR_OOM;
+  p->num_blocks = num_blocks;
+  p->refcount.assign(size_t(num_blocks), 0);
+  if (free_order) {
+    std::vector<char> seen(size_t(num_blocks), 0);
+    for (int32_t i = 0; i < num_blocks; ++i) {
+      const int32_t b = free_order[i];
+      if (b < 0 || b >= num_blocks || seen[size_t(b)]) { delete p; return PS_ERR_INVALID_ARG; }
+      seen[size_t(b)] = 1;
+      p->free_list.push_back(b);
+    }
+  } else {
+    for (int32_t i = 0; i < num_blocks; ++i) p->free_list.push_back(i);
+  }
+  *out = p;
+  return PS_OK;
+}
+
+int32_t ps_pool_destroy(ps_pool* pool) {
+  delete pool;
+  return PS_OK;
+}
+
+int32_t ps_pool_num_free(const ps_pool* pool, int32_t* out) {
+  if (!pool || !out) return PS_ERR_INVALID_ARG;
+  *out = int32_t(pool->free_list.size());
+  return PS_OK;
+}
+
+int32_t ps_pool_free_list(const ps_pool* pool, int32_t* out, int32_t capacity, int32_t* count) {
+  if (!pool || !count || capacity < 0 || (capacity > 0 && !out)) return PS_ERR_INVALID_ARG;
+  *count = int32_t(pool->free_list.size());
+  if (capacity < *count) return PS_ERR_INVALID_ARG;
+  std::copy(pool->free_list.begin(), pool->free_list.end(), out);
+  return PS_OK;
+}
+
+int32_t ps_pool_refcounts(const ps_pool* pool, const int32_t** refcount) {
+  if (!pool || !refcount) return PS_ERR_INVALID_ARG;
+  *refcount = pool->refcount.data();
+  return PS_OK;
+}
+
+int32_t ps_kv_layout(ps_pool* pool, const ps_geometry* geometry, int32_t num_prompts, const int32_t* prefix_len,
+                     int32_t num_requests, const int32_t* req_prompt, const int32_t* req_model,
+                     const int32_t* suffix_len, ps_layout** out) {
+  if (!pool || !geometry || !out || num_prompts < 0 || num_requests < 0) return PS_ERR_INVALID_ARG;
+  if ((num_prompts && !prefix_len) || (num_requests && (!req_prompt || !req_model || !suffix_len)))
+    return PS_ERR_INVALID_ARG;
+  if (int32_t st = check_geometry(*geometry)) return st;
+  const int32_t B = geometry->block_size;
+
+  std::vector<int32_t> members_count(size_t(num_prompts), 0);
+  std::set<std::pair<int32_t, int32_t>> seen;
+  for (int32_t r = 0; r < num_requests; ++r) {
+    if (req_prompt[r] < 0 || req_prompt[r] >= num_prompts || req_model[r] < 0 || suffix_len[r] < 0)
+      return PS_ERR_INVALID_ARG;
+    if (!seen.insert({req_prompt[r], req_model[r]}).second) return PS_ERR_INVALID_ARG;
+    ++members_count[size_t(req_prompt[r])];
+  }
+  int64_t needed = 0;
+  for (int32_t p = 0; p < num_prompts; ++p) {
+    if (prefix_len[p] < 0 || members_count[size_t(p)] == 0) return PS_ERR_INVALID_ARG;
+    needed += ceil_div(prefix_len[p], B);
+  }
+  for (int32_t r = 0; r < num_requests; ++r) needed += ceil_div(suffix_len[r], B);
+  if (needed > int64_t(pool->free_list.size())) return PS_ERR_OOM;
+
+  ps_layout* lay = new (std::nothrow) ps_layout();
+  if (!lay) return PS_ERR_OOM;
+  lay->geo = *geometry;
+  lay->num_prompts = num_prompts;
+  lay->num_requests = num_requests;
+  lay->prefix_len.assign(prefix_len, prefix_len + num_prompts);
+  lay->suffix_len.assign(suffix_len, suffix_len + num_requests);
+  lay->req_prompt.assign(req_prompt, req_prompt + num_requests);
+  lay->req_model.assign(req_model, req_model + num_requests);
+
+  // sharing groups: a prompt's requests in ascending request index
+  lay->group_indptr.assign(size_t(num_prompts) + 1, 0);
+  for (int32_t p = 0; p < num_prompts; ++p) lay->group_indptr[size_t(p) + 1] = lay->group_indptr[size_t(p)] + members_count[size_t(p)];
+  lay->group_req.assign(size_t(num_requests), 0);
+  {
+    std::vector<int32_t> cursor(lay->group_indptr.begin(), lay->group_indptr.end() - 1);
+    for (int32_t r = 0; r < num_requests; ++r) lay->group_req[size_t(cursor[size_t(req_prompt[r])]++)] = r;
+  }
+
+  auto take = [&](int32_t refs) {
+    const int32_t blk = pool->free_list.front();
+    pool->free_list.pop_front();
+    pool->refcount[size_t(blk)] += refs;
+    return blk;
+  };
+  lay->prefix_blk_indptr.assign(size_t(num_prompts) + 1, 0);
+  for (int32_t p = 0; p < num_prompts; ++p) {
+    const int64_t n = ceil_div(prefix_len[p], B);
+    for (int64_t i = 0; i < n; ++i) lay->prefix_blk.push_back(take(members_count[size_t(p)]));
+    lay->prefix_blk_indptr[size_t(p) + 1] = int32_t(lay->prefix_blk.size());
+  }
+  lay->suffix_blk_indptr.assign(size_t(num_requests) + 1, 0);
+  for (int32_t r = 0; r < num_requests; ++r) {
+    const int64_t n = ceil_div(suffix_len[r], B);
+    for (int64_t i = 0; i < n; ++i) lay->suffix_blk.push_back(take(1));
+    lay->suffix_blk_indptr[size_t(r) + 1] = int32_t(lay->suffix_blk.size());
+  }
+
+  if (int32_t st = ps_plan_build(lay, nullptr)) {
+    // cannot fail with default options, but never leave references behind
+    ps_layout_release(pool, lay);
+    return st;
+  }
+  *out = lay;
+  return PS_OK;
+}
+
+int32_t ps_layout_release(ps_pool* pool, ps_layout* lay) {
+  if (!pool || !lay) return PS_ERR_INVALID_ARG;
+  std::vector<int64_t> drop(size_t(pool->num_blocks), 0);
+  for (int32_t p = 0; p < lay->num_prompts; ++p) {
+    const int32_t k = lay->group_indptr[size_t(p) + 1] - lay->group_indptr[size_t(p)];
+    for (int32_t i = lay->prefix_blk_indptr[size_t(p)]; i < lay->prefix_blk_indptr[size_t(p) + 1]; ++i) {
+      const int32_t b = lay->prefix_blk[size_t(i)];
+      if (b < 0 || b >= pool->num_blocks) return PS_ERR_REFCOUNT;
+      drop[size_t(b)] += k;
+    }
+  }
+  for (int32_t b : lay->suffix_blk) {
+    if (b < 0 || b >= pool->num_blocks) return PS_ERR_REFCOUNT;
+    drop[size_t(b)] += 1;
+  }
+  for (int32_t b = 0; b < pool->num_blocks; ++b)
+    if (pool->refcount[size_t(b)] < drop[size_t(b)]) return PS_ERR_REFCOUNT;
+  for (int32_t b = 0; b < pool->num_blocks; ++b) {
+    if (!drop[size_t(b)]) continue;
+    pool->refcount[size_t(b)] -= int32_t(drop[size_t(b)]);
+    if (pool->refcount[size_t(b)] == 0) pool->free_list.push_back(b);
+  }
+  delete lay;
+  return PS_OK;
+}
+
+int32_t ps_layout_tables(const ps_layout* lay, const int32_t** prefix_blk_indptr, const int32_t** prefix_blk,
+                         const int32_t** group_indptr, const int32_t** group_req,
+                         const int32_t** suffix_blk_indptr, const int32_t** suffix_blk) {
+  if (!lay) return PS_ERR_INVALID_ARG;
+  if (prefix_blk_indptr) *prefix_blk_indptr = lay->prefix_blk_indptr.data();
+  if (prefix_blk) *prefix_blk = lay->prefix_blk.data();
+  if (group_indptr) *group_indptr = lay->group_indptr.data();
+  if (group_req) *group_req = lay->group_req.data();
+  if (suffix_blk_indptr) *suffix_blk_indptr = lay->suffix_blk_indptr.data();
+  if (suffix_blk) *suffix_blk = lay->suffix_blk.data();
+  return PS_OK;
+}
+
+int32_t ps_layout_replan(ps_layout* lay, const ps_plan_options* options) {
+  if (!lay) return PS_ERR_INVALID_ARG;
+  return ps_plan_build(lay, options);
+}
+
+int32_t ps_layout_plan(const ps_layout* lay, int32_t* num_items, const int32_t** items, const int32_t** slot_base,
+                       int32_t* prefix_variant, int32_t* suffix_variant) {
+  if (!lay) return PS_ERR_INVALID_ARG;
+  if (num_items) *num_items = int32_t(lay->items.size());
+  if (items) *items = reinterpret_cast<const int32_t*>(lay->items.data());
+  if (slot_base) *slot_base = lay->slot_base.data();
+  if (prefix_variant) *prefix_variant = lay->prefix_variant;
+  if (suffix_variant) *suffix_variant = lay->suffix_variant;
+  return PS_OK;
+}
+
+int64_t ps_layout_device_bytes(const ps_layout* lay) { return lay ? int64_t(lay->blob.size()) * 4 : -1; }
+
+int64_t ps_workspace_bytes(const ps_layout* lay) {
+  if (!lay) return -1;
+  const int64_t rows = lay->num_slots * lay->geo.num_q_heads;
+  return std::max<int64_t>(16, rows * (lay->geo.head_dim + 1) * 4);
+}
+
+int32_t ps_workspace_layout(const ps_layout* lay, int64_t* num_slots, int64_t* lse_offset_bytes) {
+  if (!lay) return PS_ERR_INVALID_ARG;
+  if (num_slots) *num_slots = lay->num_slots;
+  if (lse_offset_bytes) *lse_offset_bytes = lay->num_slots * lay->geo.num_q_heads * int64_t(lay->geo.head_dim) * 4;
+  return PS_OK;
+}
+
+const char* ps_strerror(int32_t status) {
+  switch (status) {
+    case PS_OK: return "ok";
+    case PS_ERR_INVALID_ARG: return "invalid argument";
+    case PS_ERR_SHAPE: return "geometry cannot be addressed (head counts, strides or alignment)";
+    case PS_ERR_OOM: return "not enough free KV blocks (or host memory); nothing was allocated";
+    case PS_ERR_REFCOUNT: return "refcount underflow or double release";
+    case PS_ERR_UNSUPPORTED: return "no kernel for this dtype / head_dim / block_size combination";
+    case PS_ERR_DEVICE: return "HIP call failed (see ps_last_hip_error)";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

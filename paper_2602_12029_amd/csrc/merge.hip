@@ -1,0 +1,71 @@
+// Log-sum-exp merge of partial attention states.
+//
+// For each (request, q head) the partial states (o_i, lse_i) of its prefix and suffix splits are
+// combined as lse = log sum_i exp(lse_i), o = sum_i exp(lse_i - lse) o_i -- exact by softmax algebra
+// over the concatenated cache [C_base ; own tokens] (Background Eq. 2).  One thread owns four
+// consecutive head-dim elements of one row.
+#include "device_common.h"
+#include "launch.h"
+
+namespace psdev {
+
+template <int QT>
+__global__ __launch_bounds__(256) void merge_states_kernel(const int32_t* __restrict__ slot_base,
+                                                           const float* __restrict__ ws_o,
+                                                           const float* __restrict__ ws_lse, void* __restrict__ out,
+                                                           float* __restrict__ out_lse, int num_rows, int num_q_heads,
+                                                           int head_dim) {
+  const int per_row = head_dim >> 2;
+  const int64_t gid = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+  const int64_t row = gid / per_row;
+  if (row >= num_rows) return;
+  const int c4 = int(gid % per_row);
+  const int r = int(row / num_q_heads);
+  const int h = int(row % num_q_heads);
+  const int s0 = slot_base[r], s1 = slot_base[r + 1];
+  const float neg_inf = -__builtin_inff();
+
+  float mx = neg_inf;
+  for (int s = s0; s < s1; ++s) mx = fmaxf(mx, ws_lse[int64_t(s) * num_q_heads + h]);
+  float total = 0.f;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  if (mx != neg_inf) {
+    for (int s = s0; s < s1; ++s) {
+      const float lse = ws_lse[int64_t(s) * num_q_heads + h];
+      const float w = (lse == neg_inf) ? 0.f : fast_exp2((lse - mx) * kLog2e);
+      total += w;
+      const f32x4 o = *reinterpret_cast<const f32x4*>(ws_o + (int64_t(s) * num_q_heads + h) * head_dim + 4 * c4);
+      acc += w * o;
+    }
+    acc *= 1.f / total;
+  }
+  if constexpr (QT == PS_F32) {
+    *reinterpret_cast<f32x4*>(static_cast<float*>(out) + row * head_dim + 4 * c4) = acc;
+  } else {
+    bf16x2 lo, hi;
+    lo.x = (__bf16)acc.x; lo.y = (__bf16)acc.y; hi.x = (__bf16)acc.z; hi.y = (__bf16)acc.w;
+    uint2 packed;
+    packed.x = __builtin_bit_cast(uint32_t, lo);
+    packed.y = __builtin_bit_cast(uint32_t, hi);
+    *reinterpret_cast<uint2*>(static_cast<uint16_t*>(out) + row * head_dim + 4 * c4) = packed;
+  }
+  if (out_lse && c4 == 0) out_lse[row] = (mx != neg_inf) ? mx + __builtin_amdgcn_logf(total) * kLn2 : neg_inf;
+}
+
+int32_t launch_merge(const int32_t* slot_base, const float* ws_o, const float* ws_lse, void* out, float* out_lse,
+                     int num_requests, const ps_geometry& g, hipStream_t st) {
+  const int64_t rows = int64_t(num_requests) * g.num_q_heads;
+  if (rows == 0) return PS_OK;
+  if (g.head_dim % 4 != 0) return PS_ERR_UNSUPPORTED;
+  const int64_t threads = rows * (g.head_dim / 4);
+  const dim3 grid(unsigned((threads + 255) / 256)), block(256);
+  if (g.q_dtype == PS_F32)
+    hipLaunchKernelGGL((merge_states_kernel<PS_F32>), grid, block, 0, st, slot_base, ws_o, ws_lse, out, out_lse,
+                       int(rows), g.num_q_heads, g.head_dim);
+  else
+    hipLaunchKernelGGL((merge_states_kernel<PS_BF16>), grid, block, 0, st, slot_base, ws_o, ws_lse, out, out_lse,
+                       int(rows), g.num_q_heads, g.head_dim);
+  return PS_OK;
+}
+
+}  // namespace psdev

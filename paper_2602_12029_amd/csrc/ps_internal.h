@@ -1,0 +1,52 @@
+// Internal host-side structures shared by the layout/planner and the launch code.
+#pragma once
+#include <cstdint>
+#include <deque>
+#include <vector>
+
+#include "prefillshare.h"
+
+struct ps_pool {
+  int32_t num_blocks = 0;
+  std::deque<int32_t> free_list;
+  std::vector<int32_t> refcount;
+};
+
+// One unit of attention work: a token range of one KV segment for one KV head, applied to the
+// query rows of n_req requests (all G q heads of the head's group each).
+struct ps_item {
+  int32_t blk_off;      // index of the segment's first block in the concatenated block array
+  int32_t tok_begin;
+  int32_t tok_end;
+  int32_t req_off;      // index of the first request in the request list
+  int32_t n_req;
+  int32_t kv_head;
+  int32_t split_local;  // partial-state slot of request r is slot_base[r] + split_local
+  int32_t kind;         // 0 prefix, 1 suffix
+};
+static_assert(sizeof(ps_item) == 32, "ps_item is 8 int32");
+
+struct ps_layout {
+  ps_geometry geo{};
+  int32_t num_prompts = 0, num_requests = 0;
+  std::vector<int32_t> prefix_len, suffix_len, req_prompt, req_model;
+  std::vector<int32_t> prefix_blk_indptr, prefix_blk, group_indptr, group_req, suffix_blk_indptr, suffix_blk;
+
+  // split plan
+  ps_plan_options opt{};
+  int32_t prefix_variant = PS_VARIANT_WAVE, suffix_variant = PS_VARIANT_WAVE;
+  int32_t prefix_chunk = 0, suffix_chunk = 0;
+  int32_t max_rows_prefix = 0;       // largest n_req * G over prefix items
+  std::vector<ps_item> items;        // prefix items first, then suffix items
+  int32_t num_prefix_items = 0;
+  std::vector<int32_t> slot_base;    // [R+1]
+  int64_t num_slots = 0;
+
+  // device table blob (int32 words) and section offsets in words
+  std::vector<int32_t> blob;
+  int64_t off_blk = 0, off_req = 0, off_items = 0, off_slot = 0;
+};
+
+// layout.cpp
+int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* opt);
+bool ps_mfma_supported(const ps_geometry& g);

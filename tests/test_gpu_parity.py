@@ -1,0 +1,185 @@
+"""GPU parity: the HIP path through the C ABI against the fp64 oracle, element by element.
+
+Bars: block tables bit-exact (checked when a case is set up); fp32 inputs max-abs and relative RMS
+<= 1e-5; bf16 / fp8 inputs max-abs <= 1e-2 and relative RMS <= 5e-3 (fp32 accumulation).
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from helpers import errors, oracle_decode
+from oracle import attention as oa
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": (1e-5, 1e-5), "bf16": (1e-2, 5e-3), "fp8_e4m3": (1e-2, 5e-3)}
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from gpu_helpers import GpuCase
+    return GpuCase
+
+
+def _check(case, requests=None, label=""):
+    from paper_2602_12029_amd.runtime import from_device
+    w = case.w
+    ref_o, ref_lse = oracle_decode(w, case.olay, case.data, requests)
+    torch.cuda.synchronize()
+    got_o = from_device(case.batch.out)
+    got_lse = from_device(case.batch.lse)
+    if requests is not None:
+        got_o, got_lse = got_o[list(requests)], got_lse[list(requests)]
+    max_abs, rel_rms, worst = errors(got_o, ref_o)
+    tol_abs, tol_rms = TOL[w.geometry.kv_dtype]
+    print(f"[{label or w.name}] max_abs={max_abs:.3e} rel_rms={rel_rms:.3e} worst_req_rel_rms={worst:.3e}", flush=True)
+    assert np.isfinite(got_o).all()
+    assert max_abs <= tol_abs and rel_rms <= tol_rms
+    finite = np.isfinite(ref_lse)
+    assert np.array_equal(np.isneginf(got_lse), np.isneginf(ref_lse))
+    assert np.abs(got_lse[finite] - ref_lse[finite]).max(initial=0.0) <= (1e-4 if w.geometry.kv_dtype == "f32" else 2e-3)
+    return max_abs, rel_rms
+
+
+def _variants(w):
+    g = w.geometry
+    return ["wave", "mfma"] if (g.q_dtype == "bf16" and g.kv_dtype != "f32" and g.head_dim == 128) else ["wave"]
+
+
+def test_tiny_fp32_default_and_split(gpu):
+    case = gpu(wl.named_workload("tiny"))
+    case.poison_workspace()
+    case.batch.decode_attention()
+    _check(case, label="tiny default plan")
+    for pc, sc in ((32, 32), (64, 32), (96, 4096)):
+        case.replan(pc, sc)
+        case.poison_workspace()
+        case.batch.decode_attention()
+        _check(case, label=f"tiny chunks {pc}/{sc}")
+    case.close()
+
+
+def test_separate_passes_and_partial_states(gpu):
+    """ps_prefix_attention / ps_suffix_attention partial states, merged per segment, match the oracle's segment states."""
+    from paper_2602_12029_amd import binding as B
+    w = wl.named_workload("tiny", seed=2)
+    case = gpu(w)
+    case.replan(64, 32)
+    case.poison_workspace()
+    case.batch.prefix_attention()
+    case.batch.suffix_attention()
+    case.batch.merge_states()
+    _check(case, label="tiny three calls")
+    o_ws, lse_ws = [x.cpu().double().numpy() for x in case.batch.workspace_views()]
+    assert np.isfinite(o_ws).all()                                   # every slot was written
+    plan = B.ps_layout_plan(case.layout, w.num_requests)
+    g = w.geometry
+    (op, lp), (os_, ls) = oa.segment_states(case.q_bits, g.q_dtype, case.data.kv, case.data.scales, g.kv_dtype, case.olay)
+    for r in range(w.num_requests):
+        s0, s1 = plan["slot_base"][r], plan["slot_base"][r + 1]
+        n_pre = 4                                                    # 256 tokens in chunks of 64
+        mo, ml = oa.merge_states(o_ws[s0:s0 + n_pre], lse_ws[s0:s0 + n_pre])
+        assert np.abs(mo - op[r]).max() < 1e-5 and np.abs(ml - lp[r]).max() < 1e-5
+        mo, ml = oa.merge_states(o_ws[s0 + n_pre:s1], lse_ws[s0 + n_pre:s1])
+        assert np.abs(mo - os_[r]).max() < 1e-5 and np.abs(ml - ls[r]).max() < 1e-5
+    case.close()
+
+
+def test_merge_states_alone_on_caller_built_workspace(gpu):
+    w = wl.named_workload("tiny", seed=3)
+    case = gpu(w)
+    case.replan(32, 32)
+    o_ws, lse_ws = case.batch.workspace_views()
+    gen = torch.Generator().manual_seed(5)
+    o_host = torch.randn(o_ws.shape, generator=gen)
+    lse_host = torch.randn(lse_ws.shape, generator=gen) * 3
+    lse_host[1] = float("-inf")                                      # an empty partial state
+    o_host[1] = 0
+    o_ws.copy_(o_host)
+    lse_ws.copy_(lse_host)
+    case.batch.merge_states()
+    torch.cuda.synchronize()
+    from paper_2602_12029_amd import binding as B
+    plan = B.ps_layout_plan(case.layout, w.num_requests)
+    got_o, got_lse = case.batch.out.cpu().double().numpy(), case.batch.lse.cpu().double().numpy()
+    for r in range(w.num_requests):
+        s0, s1 = plan["slot_base"][r], plan["slot_base"][r + 1]
+        ro, rl = oa.merge_states(o_host[s0:s1].double().numpy(), lse_host[s0:s1].double().numpy())
+        assert np.abs(got_o[r] - ro).max() < 1e-5 and np.abs(got_lse[r] - rl).max() < 1e-5
+    case.close()
+
+
+RAGGED = [
+    # name, geometry, models, prefix_len, membership, suffix_len
+    ("ragged_f32", wl.Geometry(4, 2, 64, 16, "f32", "f32"), 3, [1, 130, 517], [[0], [0, 2], [0, 1, 2]],
+     [0, 33, 1, 16, 0, 250]),
+    ("ragged_bf16", wl.Geometry(32, 8, 128, 16, "bf16", "bf16"), 4, [700, 31, 1025], [[0, 1, 2, 3], [1], [0, 3]],
+     [5, 0, 129, 64, 17, 1, 300]),
+    ("ragged_fp8", wl.Geometry(64, 8, 128, 16, "bf16", "fp8_e4m3"), 4, [515, 48], [[0, 1, 2, 3], [2, 3]],
+     [1, 47, 0, 200, 16, 33]),
+    ("block32_bf16", wl.Geometry(8, 2, 128, 32, "bf16", "bf16"), 2, [333, 64], [[0, 1], [1]], [40, 0, 97]),
+    ("d64_bf16", wl.Geometry(8, 2, 64, 16, "bf16", "bf16"), 2, [200], [[0, 1]], [9, 70]),
+    ("d256_f32", wl.Geometry(4, 1, 256, 16, "f32", "f32"), 2, [100], [[0, 1]], [3, 40]),
+    ("many_models", wl.Geometry(32, 2, 128, 16, "bf16", "bf16"), 10, [300], [list(range(10))], list(range(1, 11))),
+]
+
+
+@pytest.mark.parametrize("spec", RAGGED, ids=[s[0] for s in RAGGED])
+def test_ragged_shapes(gpu, spec):
+    name, geo, models, prefix, membership, suffix = spec
+    w = wl.make_workload(name, geo, models, prefix, membership, suffix, pool_factor=1.5, seed=17)
+    case = gpu(w)
+    for variant in _variants(w):
+        for pc, sc in ((0, 0), (64, 32), (256, 96)):
+            case.replan(pc, sc, variant, variant)
+            case.poison_workspace()
+            case.batch.decode_attention()
+            _check(case, label=f"{name} {variant} chunks {pc}/{sc}")
+    case.close()
+
+
+def test_request_without_tokens_gives_zero_and_neg_inf(gpu):
+    geo = wl.Geometry(4, 2, 64, 16, "f32", "f32")
+    w = wl.make_workload("empty", geo, 2, [0, 40], [[0], [0, 1]], [0, 0, 3], seed=19)
+    case = gpu(w)
+    case.poison_workspace()
+    case.batch.decode_attention()
+    torch.cuda.synchronize()
+    assert not case.batch.out[0].any() and torch.isneginf(case.batch.lse[0]).all()
+    _check(case)
+    case.close()
+
+
+@pytest.mark.parametrize("name", ["b8", "fp8_70b"])
+def test_full_size_all_outputs(gpu, name):
+    """Full benchmark configurations, default plan (the launch configuration bench.py times), every output."""
+    w = wl.named_workload(name)
+    case = gpu(w)
+    case.poison_workspace()
+    case.batch.decode_attention()
+    _check(case)
+    first = case.batch.out.clone()
+    case.batch.decode_attention()                       # no float atomics anywhere: bitwise repeatable
+    torch.cuda.synchronize()
+    assert torch.equal(first.view(torch.int16), case.batch.out.view(torch.int16))
+    case.close()
+
+
+@pytest.mark.parametrize("name", ["long", "mixed"])
+def test_full_size_sampled_outputs(gpu, name):
+    """The two largest configurations: the oracle computes a seeded sample of requests one by one."""
+    w = wl.named_workload(name)
+    case = gpu(w)
+    case.poison_workspace()
+    case.batch.decode_attention()
+    torch.cuda.synchronize()
+    assert torch.isfinite(case.batch.out.float()).all()
+    sample = sorted(np.random.default_rng(7).choice(w.num_requests, size=12, replace=False).tolist())
+    # include the longest and the shortest prefix
+    by_len = np.argsort(w.prefix_len[w.req_prompt])
+    sample = sorted(set(sample) | {int(by_len[0]), int(by_len[-1])})
+    _check(case, requests=sample)
+    case.close()

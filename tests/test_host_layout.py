@@ -1,0 +1,196 @@
+"""Host side of the C-ABI library (no GPU): exported symbols, bit-exact block tables, plan invariants, errors."""
+import json
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workloads as wl
+from oracle import layout as ol
+from paper_2602_12029_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "prefillshare.h")).read()
+    declared = set(re.findall(r"\b(ps_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    lib = B._lib()
+    for name in declared:
+        assert hasattr(lib, name)
+    assert B.ps_strerror(B.PS_ERR_OOM).startswith("not enough")
+
+
+def _both(w, geo=None):
+    g = w.geometry
+    geo = geo or B.geometry(g.num_q_heads, g.num_kv_heads, g.head_dim, g.block_size, g.q_dtype, g.kv_dtype)
+    pool = B.ps_pool_create(w.num_blocks, w.free_order)
+    lay = B.ps_kv_layout(pool, geo, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
+    opool = ol.BlockPool(w.num_blocks, w.free_order)
+    olay = ol.build_layout(opool, g.block_size, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
+    return pool, lay, opool, olay
+
+
+@pytest.mark.parametrize("name", ["tiny", "b8", "long", "mixed", "fp8_70b"])
+def test_tables_bit_exact_against_oracle_policy(name):
+    w = wl.named_workload(name)
+    pool, lay, opool, olay = _both(w)
+    t = B.ps_layout_tables(lay, w.num_prompts, w.num_requests)
+    for key in ("prefix_blk_indptr", "prefix_blk", "group_indptr", "group_req", "suffix_blk_indptr", "suffix_blk"):
+        assert np.array_equal(t[key], getattr(olay, key)), key
+    assert np.array_equal(B.ps_pool_refcounts(pool, w.num_blocks), opool.refcount)
+    assert np.array_equal(B.ps_pool_free_list(pool), np.array(opool.free, np.int32))
+    B.ps_layout_release(pool, lay)
+    ol.release_layout(opool, olay)
+    assert np.array_equal(B.ps_pool_refcounts(pool, w.num_blocks), opool.refcount)
+    assert np.array_equal(B.ps_pool_free_list(pool), np.array(opool.free, np.int32))
+    B.ps_pool_destroy(pool)
+
+
+def test_hand_worked_instance():
+    g = json.load(open(os.path.join(ROOT, "tests", "golden", "layout_small.json")))
+    geo = B.geometry(4, 2, 64, g["block_size"], "f32", "f32")
+    pool = B.ps_pool_create(g["num_blocks"], g["free_order"])
+    lay = B.ps_kv_layout(pool, geo, g["prefix_len"], g["req_prompt"], g["req_model"], g["suffix_len"])
+    t = B.ps_layout_tables(lay, 2, 3)
+    for key, val in g["expect"].items():
+        if key in t:
+            assert t[key].tolist() == val, key
+    assert B.ps_pool_refcounts(pool, 8).tolist() == g["expect"]["refcount"]
+    assert B.ps_pool_free_list(pool).tolist() == g["expect"]["free_after_build"]
+    B.ps_layout_release(pool, lay)
+    assert B.ps_pool_free_list(pool).tolist() == g["expect"]["free_after_release"]
+    B.ps_pool_destroy(pool)
+
+
+def test_random_batches_against_oracle_policy():
+    rng = np.random.default_rng(21)
+    for trial in range(30):
+        bsz = int(rng.choice([1, 4, 16, 48]))
+        num_p = int(rng.integers(1, 6))
+        num_m = int(rng.integers(1, 5))
+        membership = [sorted(rng.choice(num_m, size=int(rng.integers(1, num_m + 1)), replace=False).tolist())
+                      for _ in range(num_p)]
+        nreq = sum(len(m) for m in membership)
+        geo = wl.Geometry(4, 2, 64, bsz, "f32", "f32")
+        w = wl.make_workload("r", geo, num_m, rng.integers(0, 200, num_p), membership, rng.integers(0, 70, nreq),
+                             pool_factor=float(rng.uniform(1.0, 2.0)), seed=trial)
+        pool, lay, opool, olay = _both(w)
+        t = B.ps_layout_tables(lay, w.num_prompts, w.num_requests)
+        for key in t:
+            assert np.array_equal(t[key], getattr(olay, key)), (trial, key)
+        assert np.array_equal(B.ps_pool_refcounts(pool, w.num_blocks), opool.refcount)
+        B.ps_layout_release(pool, lay)
+        ol.release_layout(opool, olay)
+        assert np.array_equal(B.ps_pool_free_list(pool), np.array(opool.free, np.int32))
+        B.ps_pool_destroy(pool)
+
+
+def _check_plan(w, lay, plan):
+    """Chunks tile every segment exactly once per KV head and request; slots are consistent."""
+    g = w.geometry
+    items, slot_base = plan["items"], plan["slot_base"]
+    t = B.ps_layout_tables(lay, w.num_prompts, w.num_requests)
+    nprefix_blk = int(t["prefix_blk_indptr"][-1])
+    req_list = np.concatenate([t["group_req"], np.arange(w.num_requests, dtype=np.int32)])
+    cover = {}                                             # (request, kv head) -> list of (kind, begin, end, slot)
+    for blk_off, t0, t1, req_off, n_req, head, split, kind in items.tolist():
+        assert t1 > t0 >= 0 and n_req >= 1 and 0 <= head < g.num_kv_heads
+        assert t0 % g.block_size == 0
+        for r in req_list[req_off:req_off + n_req].tolist():
+            if kind == 0:
+                p = int(w.req_prompt[r])
+                assert blk_off == t["prefix_blk_indptr"][p] and t1 <= w.prefix_len[p]
+            else:
+                assert blk_off == nprefix_blk + t["suffix_blk_indptr"][r] and t1 <= w.suffix_len[r] and n_req == 1
+            cover.setdefault((r, head), []).append((kind, t0, t1, split))
+    for r in range(w.num_requests):
+        nslots = int(slot_base[r + 1] - slot_base[r])
+        for head in range(g.num_kv_heads):
+            chunks = sorted(cover.get((r, head), []), key=lambda c: c[3])
+            assert [c[3] for c in chunks] == list(range(nslots))           # every slot written exactly once
+            for kind, length in ((0, int(w.prefix_len[w.req_prompt[r]])), (1, int(w.suffix_len[r]))):
+                spans = sorted((c[1], c[2]) for c in chunks if c[0] == kind)
+                pos = 0
+                for a, b in spans:
+                    assert a == pos
+                    pos = b
+                assert pos == length
+            kinds = [c[0] for c in chunks]
+            assert kinds == sorted(kinds)                                   # prefix splits first
+
+
+@pytest.mark.parametrize("name", ["tiny", "b8", "mixed"])
+def test_default_plan_invariants(name):
+    w = wl.named_workload(name)
+    pool, lay, _, _ = _both(w)
+    _check_plan(w, lay, B.ps_layout_plan(lay, w.num_requests))
+    B.ps_layout_release(pool, lay)
+    B.ps_pool_destroy(pool)
+
+
+def test_replan_invariants_ragged_and_empty_segments():
+    geo = wl.Geometry(8, 2, 64, 16, "f32", "f32")
+    w = wl.make_workload("rag", geo, 3, [0, 1, 333, 1000], [[0], [1, 2], [0, 1, 2], [2]], [0, 5, 0, 77, 300, 1, 16],
+                         seed=3)
+    pool, lay, _, _ = _both(w)
+    for pc, sc in ((0, 0), (32, 32), (64, 16), (1000, 1), (4096, 4096)):
+        B.ps_layout_replan(lay, B.plan_options(pc, sc))
+        plan = B.ps_layout_plan(lay, w.num_requests)
+        _check_plan(w, lay, plan)
+    # request 0 has no tokens at all: it owns no slot
+    plan = B.ps_layout_plan(lay, w.num_requests)
+    assert plan["slot_base"][1] == plan["slot_base"][0]
+    slots, off = B.ps_workspace_layout(lay)
+    assert slots == plan["slot_base"][-1] and off == slots * 8 * 64 * 4
+    assert B.ps_workspace_bytes(lay) == slots * 8 * 65 * 4
+    B.ps_layout_release(pool, lay)
+    B.ps_pool_destroy(pool)
+
+
+def test_many_models_split_into_row_chunks():
+    geo = wl.Geometry(32, 2, 64, 16, "f32", "f32")           # group of 16: at most 4 requests per item
+    w = wl.make_workload("many", geo, 10, [64], [list(range(10))], [1] * 10, seed=4)
+    pool, lay, _, _ = _both(w)
+    plan = B.ps_layout_plan(lay, w.num_requests)
+    _check_plan(w, lay, plan)
+    prefix = plan["items"][plan["items"][:, 7] == 0]
+    assert sorted(prefix[prefix[:, 5] == 0][:, 4].tolist()) == [2, 4, 4]
+    B.ps_layout_release(pool, lay)
+    B.ps_pool_destroy(pool)
+
+
+def test_error_paths():
+    geo = B.geometry(4, 2, 64, 16, "f32", "f32")
+    pool = B.ps_pool_create(3, [2, 0, 1])
+
+    def status(fn, *a):
+        with pytest.raises(B.PsError) as e:
+            fn(*a)
+        return e.value.status
+
+    assert status(B.ps_kv_layout, pool, geo, [33], [0], [0], [1]) == B.PS_ERR_OOM
+    assert B.ps_pool_free_list(pool).tolist() == [2, 0, 1] and not B.ps_pool_refcounts(pool, 3).any()
+    assert status(B.ps_kv_layout, pool, geo, [16], [0, 0], [1, 1], [1, 1]) == B.PS_ERR_INVALID_ARG
+    assert status(B.ps_kv_layout, pool, geo, [16, 16], [0], [0], [1]) == B.PS_ERR_INVALID_ARG
+    assert status(B.ps_kv_layout, pool, geo, [16], [1], [0], [1]) == B.PS_ERR_INVALID_ARG
+    assert status(B.ps_kv_layout, pool, geo, [-1], [0], [0], [1]) == B.PS_ERR_INVALID_ARG
+    assert status(B.ps_kv_layout, pool, B.geometry(6, 4, 64, 16, "f32", "f32"), [16], [0], [0], [1]) == B.PS_ERR_SHAPE
+    assert status(B.ps_kv_layout, pool, B.geometry(4, 2, 64, 16, "f32", 7), [16], [0], [0], [1]) == B.PS_ERR_UNSUPPORTED
+    assert status(B.ps_kv_layout, pool, B.geometry(4, 2, 64, 16, "f32", "bf16", (2048, 1024, 512, 33)),
+                  [16], [0], [0], [1]) == B.PS_ERR_SHAPE
+    assert status(B.ps_pool_create, 3, [0, 0, 1]) == B.PS_ERR_INVALID_ARG
+    assert B.ps_pool_free_list(pool).tolist() == [2, 0, 1]
+    # releasing against a pool that does not hold the references is refused and changes nothing
+    lay = B.ps_kv_layout(pool, geo, [16], [0], [0], [1])
+    other = B.ps_pool_create(3)
+    assert status(B.ps_layout_release, other, lay) == B.PS_ERR_REFCOUNT
+    assert not B.ps_pool_refcounts(other, 3).any()
+    # forcing the MFMA variant on fp32 inputs is refused
+    assert status(B.ps_layout_replan, lay, B.plan_options(prefix_variant=B.PS_VARIANT_MFMA)) == B.PS_ERR_UNSUPPORTED
+    B.ps_layout_release(pool, lay)
+    assert B.ps_pool_num_free(pool) == 3
+    B.ps_pool_destroy(other)
+    B.ps_pool_destroy(pool)
