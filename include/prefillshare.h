@@ -136,6 +136,10 @@ int32_t ps_prefix_attention(const ps_layout* layout, const void* dev_tables, con
                             const void* kv_pool, const float* kv_scales, void* workspace, void* stream);
 int32_t ps_suffix_attention(const ps_layout* layout, const void* dev_tables, const void* q,
                             const void* kv_pool, const float* kv_scales, void* workspace, void* stream);
+/* ps_prefix_suffix_attention: both passes; where they run the same kernel family the two work lists go
+ * out as one launch (this is the attention part of ps_decode_attention). */
+int32_t ps_prefix_suffix_attention(const ps_layout* layout, const void* dev_tables, const void* q,
+                                   const void* kv_pool, const float* kv_scales, void* workspace, void* stream);
 /* ps_merge_states: per (request, q head) combines the request's partial states,
  * lse = log sum_i exp(lse_i), o = sum_i exp(lse_i - lse) o_i, and writes out[R][Hq][d] in q_dtype
  * (bf16: round to nearest even) and, if out_lse != NULL, lse as fp32 [R][Hq].  A request with no
@@ -143,7 +147,8 @@ int32_t ps_suffix_attention(const ps_layout* layout, const void* dev_tables, con
  * caller in the documented format. */
 int32_t ps_merge_states(const ps_layout* layout, const void* dev_tables, const void* workspace,
                         void* out, float* out_lse, void* stream);
-/* ps_decode_attention: the whole step -- prefix pass, suffix pass, merge -- on one stream. */
+/* ps_decode_attention: the whole step -- ps_prefix_suffix_attention, then ps_merge_states -- on one
+ * stream. */
 int32_t ps_decode_attention(const ps_layout* layout, const void* dev_tables, const void* q,
                             const void* kv_pool, const float* kv_scales, void* workspace,
                             void* out, float* out_lse, void* stream);

@@ -23,7 +23,7 @@ EXPORTS = [
     "ps_pool_create", "ps_pool_destroy", "ps_pool_num_free", "ps_pool_free_list", "ps_pool_refcounts",
     "ps_kv_layout", "ps_layout_release", "ps_layout_tables", "ps_layout_replan", "ps_layout_plan",
     "ps_layout_device_bytes", "ps_layout_upload", "ps_workspace_bytes", "ps_workspace_layout",
-    "ps_prefix_attention", "ps_suffix_attention", "ps_merge_states", "ps_decode_attention",
+    "ps_prefix_attention", "ps_suffix_attention", "ps_prefix_suffix_attention", "ps_merge_states", "ps_decode_attention",
     "ps_strerror", "ps_last_hip_error",
 ]
 
@@ -214,6 +214,11 @@ def ps_prefix_attention(layout, dev_tables, q, kv_pool, kv_scales, workspace, st
 def ps_suffix_attention(layout, dev_tables, q, kv_pool, kv_scales, workspace, stream=0):
     _check(_lib().ps_suffix_attention(layout, _p(dev_tables), _p(q), _p(kv_pool), _p(kv_scales), _p(workspace),
                                       _p(stream)), "ps_suffix_attention")
+
+
+def ps_prefix_suffix_attention(layout, dev_tables, q, kv_pool, kv_scales, workspace, stream=0):
+    _check(_lib().ps_prefix_suffix_attention(layout, _p(dev_tables), _p(q), _p(kv_pool), _p(kv_scales),
+                                             _p(workspace), _p(stream)), "ps_prefix_suffix_attention")
 
 
 def ps_merge_states(layout, dev_tables, workspace, out, out_lse=0, stream=0):

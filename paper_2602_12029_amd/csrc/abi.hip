@@ -46,10 +46,17 @@ int32_t launch_range(const ps_layout* lay, const psdev::AttnParams& p, int varia
                      hipStream_t st) {
   if (count <= 0) return PS_OK;
   int32_t rc;
-  if (variant == PS_VARIANT_MFMA)
-    rc = psdev::launch_mfma_attention(p, lay->geo, 64, begin, count, st);
-  else
+  if (variant == PS_VARIANT_MFMA) {
+    // widest row group in the range decides how many 16-row tiles the kernel carries
+    const int group = lay->geo.num_q_heads / lay->geo.num_kv_heads;
+    int max_rows = 0;
+    if (begin < lay->num_prefix_items) max_rows = lay->max_rows_prefix;
+    if (begin + count > lay->num_prefix_items) max_rows = max_rows > group ? max_rows : group;
+    rc = psdev::launch_mfma_attention(p, lay->geo, max_rows, begin, count, st);
+  } else
+  {
     rc = psdev::launch_wave_attention(p, lay->geo, begin, count, st);
+  }
   if (rc != PS_OK) return rc;
   return check_hip(hipGetLastError());
 }
@@ -100,24 +107,23 @@ int32_t ps_merge_states(const ps_layout* lay, const void* dev_tables, const void
   return check_hip(hipGetLastError());
 }
 
-int32_t ps_decode_attention(const ps_layout* lay, const void* dev_tables, const void* q, const void* kv_pool,
-                            const float* kv_scales, void* workspace, void* out, float* out_lse, void* stream) {
+int32_t ps_prefix_suffix_attention(const ps_layout* lay, const void* dev_tables, const void* q, const void* kv_pool,
+                                   const float* kv_scales, void* workspace, void* stream) {
   if (int32_t st = check_pass_args(lay, dev_tables, q, kv_pool, kv_scales, workspace)) return st;
-  if (lay->num_requests && !out) return PS_ERR_INVALID_ARG;
   const psdev::AttnParams p = make_params(lay, dev_tables, q, kv_pool, kv_scales, workspace);
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int n_all = int(lay->items.size());
-  if (lay->prefix_variant == lay->suffix_variant) {
-    // both passes run the same kernel: one launch over the whole work list
-    if (int32_t rc = launch_range(lay, p, lay->prefix_variant, 0, n_all, st)) return rc;
-  } else {
-    if (int32_t rc = launch_range(lay, p, lay->prefix_variant, 0, lay->num_prefix_items, st)) return rc;
-    if (int32_t rc = launch_range(lay, p, lay->suffix_variant, lay->num_prefix_items, n_all - lay->num_prefix_items, st))
-      return rc;
-  }
-  if (int32_t rc = psdev::launch_merge(p.slot_base, p.ws_o, p.ws_lse, out, out_lse, lay->num_requests, lay->geo, st))
-    return rc;
-  return check_hip(hipGetLastError());
+  if (lay->prefix_variant == lay->suffix_variant)  // same kernel: one launch over the whole work list
+    return launch_range(lay, p, lay->prefix_variant, 0, n_all, st);
+  if (int32_t rc = launch_range(lay, p, lay->prefix_variant, 0, lay->num_prefix_items, st)) return rc;
+  return launch_range(lay, p, lay->suffix_variant, lay->num_prefix_items, n_all - lay->num_prefix_items, st);
+}
+
+int32_t ps_decode_attention(const ps_layout* lay, const void* dev_tables, const void* q, const void* kv_pool,
+                            const float* kv_scales, void* workspace, void* out, float* out_lse, void* stream) {
+  if (lay && lay->num_requests && !out) return PS_ERR_INVALID_ARG;
+  if (int32_t rc = ps_prefix_suffix_attention(lay, dev_tables, q, kv_pool, kv_scales, workspace, stream)) return rc;
+  return ps_merge_states(lay, dev_tables, workspace, out, out_lse, stream);
 }
 
 }  // extern "C"

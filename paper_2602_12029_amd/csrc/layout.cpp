@@ -34,7 +34,7 @@ int32_t check_geometry(const ps_geometry& g) {
 }  // namespace
 
 bool ps_mfma_supported(const ps_geometry& g) {
-  return false && g.q_dtype == PS_BF16 && (g.kv_dtype == PS_BF16 || g.kv_dtype == PS_FP8_E4M3) && g.head_dim == 128 &&
+  return g.q_dtype == PS_BF16 && (g.kv_dtype == PS_BF16 || g.kv_dtype == PS_FP8_E4M3) && g.head_dim == 128 &&
          g.block_size % 16 == 0 && (g.num_q_heads / g.num_kv_heads) <= 64;
 }
 

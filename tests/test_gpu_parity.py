@@ -46,7 +46,7 @@ def _check(case, requests=None, label=""):
 
 def _variants(w):
     g = w.geometry
-    return ["wave"] if False and (g.q_dtype == "bf16" and g.kv_dtype != "f32" and g.head_dim == 128) else ["wave"]
+    return ["wave", "mfma"] if (g.q_dtype == "bf16" and g.kv_dtype != "f32" and g.head_dim == 128) else ["wave"]
 
 
 def test_tiny_fp32_default_and_split(gpu):
