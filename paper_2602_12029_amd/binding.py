@@ -59,6 +59,9 @@ def _lib():
         if not os.path.exists(LIB_PATH):
             raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2602_12029_amd.build` "
                               "(there is no CPU fallback)")
+        # The caller's device memory and streams come from PyTorch, so the library has to bind to the
+        # HIP runtime PyTorch ships: importing torch first makes the loader resolve libamdhip64 to it.
+        import torch  # noqa: F401
         lib = C.CDLL(LIB_PATH)
         lib.ps_strerror.restype = C.c_char_p
         lib.ps_strerror.argtypes = [C.c_int32]

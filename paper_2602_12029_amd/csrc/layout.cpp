@@ -60,7 +60,8 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   for (int32_t l : lay->prefix_len) total += l;
   for (int32_t l : lay->suffix_len) total += l;
   total *= g.num_kv_heads;
-  const int64_t ideal = std::max<int64_t>(1, ceil_div(total, int64_t(num_cus) * 4));
+  // two workgroups per compute unit are resident; aim for about one full-size chunk per resident slot
+  const int64_t ideal = std::max<int64_t>(1, ceil_div(total, int64_t(num_cus) * 2));
   auto pick = [&](int32_t asked) -> int64_t {
     if (asked > 0) return round_up(asked, granule);
     return std::min<int64_t>(std::max<int64_t>(round_up(ideal, granule), round_up(256, granule)), round_up(4096, granule));

@@ -79,6 +79,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
   __shared__ float sm_o[kWaves][16][kLdsRow];
   __shared__ float sm_m[kWaves][16];
   __shared__ float sm_l[kWaves][16];
+  __shared__ __attribute__((aligned(16))) uint16_t sm_q[NT][16][kD + 8];  // rows padded by 16 B against bank conflicts
 
   const ps_item it = p.items[item_begin + blockIdx.x];
   const int lane = threadIdx.x & 63;
@@ -91,22 +92,24 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
   const float neg_inf = -__builtin_inff();
   const int sub_per_blk = p.block_size >> 4;  // 16-token sub-blocks per physical block
 
-  // ---- query rows as B operands ------------------------------------------------------------------
-  bf16x8 qb[NT][4];
+  // ---- query rows, staged in LDS and re-read as B operands for every tile ------------------------------
+  // (keeping them in registers would cost 16 VGPRs per row tile for the whole kernel)
+  {
+    const int r = threadIdx.x >> 4, c = threadIdx.x & 15;  // one 16-byte piece per thread and row tile
 #pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    const int row = 16 * t + n;
-    uint4 raw[4] = {};
-    if (row < rows) {
-      const int req = p.req_list[it.req_off + row / G];
-      const int h = it.kv_head * G + row % G;
-      const uint16_t* qrow = static_cast<const uint16_t*>(p.q) + (int64_t(req) * p.num_q_heads + h) * kD;
-#pragma unroll
-      for (int s = 0; s < 4; ++s) raw[s] = *reinterpret_cast<const uint4*>(qrow + q_chunk_elem<KVT>(s, kg));
+    for (int t = 0; t < NT; ++t) {
+      const int row = 16 * t + r;
+      uint4 piece = uint4{0, 0, 0, 0};
+      if (row < rows) {
+        const int req = p.req_list[it.req_off + row / G];
+        const int h = it.kv_head * G + row % G;
+        piece = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(p.q) +
+                                                (int64_t(req) * p.num_q_heads + h) * kD + 8 * c);
+      }
+      *reinterpret_cast<uint4*>(&sm_q[t][r][8 * c]) = piece;
     }
-#pragma unroll
-    for (int s = 0; s < 4; ++s) qb[t][s] = as_bf16x8(raw[s]);
   }
+  __syncthreads();
 
   // ---- per-wave tile schedule ----------------------------------------------------------------------
   const int span = it.tok_end - it.tok_begin;
@@ -229,30 +232,22 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
         if (tok >= it.tok_end) vr[i] = uint4{0, 0, 0, 0};
       }
     }
-    // transpose inside the lane: vt[c] = column c of the 8 token rows
-    bf16x8 vt[8];
-#pragma unroll
-    for (int c = 0; c < 8; ++c) {
-      uint32_t w[4];
-#pragma unroll
-      for (int i2 = 0; i2 < 4; ++i2) {
-        const uint32_t* r0 = reinterpret_cast<const uint32_t*>(&vr[2 * i2]);
-        const uint32_t* r1 = reinterpret_cast<const uint32_t*>(&vr[2 * i2 + 1]);
-        const uint32_t a = r0[c >> 1], b = r1[c >> 1];
-        w[i2] = (c & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
-      }
-      vt[c] = as_bf16x8(uint4{w[0], w[1], w[2], w[3]});
-    }
-
+    // scores and probabilities of every row tile first ...
+    bf16x8 pb[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
+      pb[t] = bf16x8{};
       if (t < nt_used) {
+        bf16x8 qb[4];
+#pragma unroll
+        for (int st = 0; st < 4; ++st)
+          qb[st] = as_bf16x8(*reinterpret_cast<const uint4*>(&sm_q[t][n][q_chunk_elem<KVT>(st, kg)]));
         f32x4 s[2];
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
           s[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-          for (int st = 0; st < 4; ++st) s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[b][st], qb[t][st], s[b], 0, 0, 0);
+          for (int st = 0; st < 4; ++st) s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[b][st], qb[st], s[b], 0, 0, 0);
           s[b] *= sc_k[b];  // scores in log2 units
         }
         if (!full) {
@@ -274,24 +269,34 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
           for (int c = 0; c < 8; ++c) acc[t][c] *= alpha;
           m_run[t] = m_new;
         }
-        float pw[2][4];
         float lsum = 0.f;
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            pw[b][j] = fast_exp2(s[b][j] - m_new);
-            lsum += pw[b][j];
+            const float pw = fast_exp2(s[b][j] - m_new);
+            lsum += pw;
+            pb[t][4 * b + j] = (__bf16)(pw * sc_v[b]);
           }
         l_run[t] += lsum;
-        bf16x8 pb;
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) pb[4 * b + j] = (__bf16)(pw[b][j] * sc_v[b]);
-#pragma unroll
-        for (int c = 0; c < 8; ++c) acc[t][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt[c], pb, acc[t][c], 0, 0, 0);
       }
+    }
+    // ... then O^T += V^T P^T, one 16-column group of V at a time, transposed inside the lane:
+    // vt = column c of this lane's 8 token rows
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+      uint32_t w[4];
+#pragma unroll
+      for (int i2 = 0; i2 < 4; ++i2) {
+        const uint32_t* r0 = reinterpret_cast<const uint32_t*>(&vr[2 * i2]);
+        const uint32_t* r1 = reinterpret_cast<const uint32_t*>(&vr[2 * i2 + 1]);
+        const uint32_t a = r0[c >> 1], b = r1[c >> 1];
+        w[i2] = (c & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
+      }
+      const bf16x8 vt = as_bf16x8(uint4{w[0], w[1], w[2], w[3]});
+#pragma unroll
+      for (int t = 0; t < NT; ++t)
+        if (t < nt_used) acc[t][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, pb[t], acc[t][c], 0, 0, 0);
     }
   };
 
@@ -391,14 +396,15 @@ int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max
   do {                                         \
     if (cfg == 1) PS_LAUNCH(NT, KVT, 3, 1);    \
     else if (cfg == 2) PS_LAUNCH(NT, KVT, 4, 1); \
-    else PS_LAUNCH(NT, KVT, 2, 1);             \
+    else if (cfg == 4) PS_LAUNCH(NT, KVT, 2, 1); \
+    else PS_LAUNCH(NT, KVT, 2, 2);             \
   } while (0)
   if (g.kv_dtype == PS_BF16) {
-    if (nt == 1) { if (cfg == 3) PS_LAUNCH(1, PS_BF16, 2, 2); else PS_BY_CFG(1, PS_BF16); }
-    else if (nt == 2) PS_BY_CFG(2, PS_BF16);
+    if (nt == 1) PS_BY_CFG(1, PS_BF16);
+    else if (nt == 2) { if (cfg == 0) PS_LAUNCH(2, PS_BF16, 3, 1); else PS_BY_CFG(2, PS_BF16); }
     else PS_LAUNCH(4, PS_BF16, 2, 1);
   } else {
-    if (nt == 1) { if (cfg == 3) PS_LAUNCH(1, PS_FP8_E4M3, 2, 2); else PS_BY_CFG(1, PS_FP8_E4M3); }
+    if (nt == 1) PS_BY_CFG(1, PS_FP8_E4M3);
     else if (nt == 2) PS_BY_CFG(2, PS_FP8_E4M3);
     else PS_LAUNCH(4, PS_FP8_E4M3, 2, 1);
   }
