@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--suffix-variant", default="auto")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target wall time of the oracle sample; 0 = skip")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events in the timed loop")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB read + 1 GiB write elementwise kernel (reference for HBM byte counters)")
     return ap.parse_args()
 
 
@@ -134,6 +136,14 @@ def main():
     def attention(kv):      # the dominant kernel(s): prefix + suffix work list
         B.ps_prefix_suffix_attention(layout, tp, qp, kv.data_ptr(), sc, wp, stream)
 
+    if args.calibrate_copy:      # known traffic: reads 2^30 bytes, writes 2^30 bytes per launch
+        src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+
     for i in range(args.warmup):
         batch.decode_attention(with_lse=False, kv=copies[i % len(copies)])
     torch.cuda.synchronize()
@@ -163,6 +173,13 @@ def main():
         k_ms = float(np.mean([ev.elapsed_ms(i) for i in range(args.steps)]))
         roofline.update(achieved=attn_bytes / (k_ms * 1e-3) / 1e9, kernel_ms=k_ms, algorithmic_bytes=attn_bytes)
         roofline["frac"] = roofline["achieved"] / PEAK_HBM_GBS
+
+    # HBM bytes per launch from the committed rocprofv3 counter summary of this workload, if there is one
+    summary = os.path.join(ROOT, "profiles", f"attention_kernel_{args.workload}.md")
+    if os.path.exists(summary):
+        for text in open(summary):
+            if text.startswith("traffic_bytes_per_launch:"):
+                roofline["traffic"] = float(text.split(":")[1])
 
     value = ideal / (ms_per_step * 1e-3) / 1e9
     line = {
