@@ -42,20 +42,25 @@ psdev::AttnParams make_params(const ps_layout* lay, const void* dev_tables, cons
   return p;
 }
 
-int32_t launch_range(const ps_layout* lay, const psdev::AttnParams& p, int variant, int begin, int count,
-                     hipStream_t st) {
-  if (count <= 0) return PS_OK;
+enum class WorkSet { kPrefix, kSuffix, kAll };
+
+// Launches one set of work items with the kernel family the plan chose for it.
+int32_t launch_set(const ps_layout* lay, const psdev::AttnParams& p, const void* dev_tables, WorkSet set,
+                   hipStream_t st) {
+  const int n_all = int(lay->items.size());
+  const int begin = set == WorkSet::kSuffix ? lay->num_prefix_items : 0;
+  const int end = set == WorkSet::kPrefix ? lay->num_prefix_items : n_all;
+  if (end <= begin) return PS_OK;
+  const int variant = set == WorkSet::kSuffix ? lay->suffix_variant : lay->prefix_variant;
   int32_t rc;
   if (variant == PS_VARIANT_MFMA) {
-    // widest row group in the range decides how many 16-row tiles the kernel carries
-    const int group = lay->geo.num_q_heads / lay->geo.num_kv_heads;
-    int max_rows = 0;
-    if (begin < lay->num_prefix_items) max_rows = lay->max_rows_prefix;
-    if (begin + count > lay->num_prefix_items) max_rows = max_rows > group ? max_rows : group;
-    rc = psdev::launch_mfma_attention(p, lay->geo, max_rows, begin, count, st);
-  } else
-  {
-    rc = psdev::launch_wave_attention(p, lay->geo, begin, count, st);
+    const ps_layout::schedule& s = set == WorkSet::kPrefix ? lay->sched_prefix
+                                   : set == WorkSet::kSuffix ? lay->sched_suffix : lay->sched_all;
+    const int32_t* t = static_cast<const int32_t*>(dev_tables);
+    rc = psdev::launch_mfma_attention(p, lay->geo, s.max_rows, s.occ, reinterpret_cast<const ps_item*>(t + s.off_items),
+                                      t + s.off_indptr, s.num_wg, st);
+  } else {
+    rc = psdev::launch_wave_attention(p, lay->geo, begin, end - begin, st);
   }
   if (rc != PS_OK) return rc;
   return check_hip(hipGetLastError());
@@ -85,15 +90,14 @@ int32_t ps_prefix_attention(const ps_layout* lay, const void* dev_tables, const 
                             const float* kv_scales, void* workspace, void* stream) {
   if (int32_t st = check_pass_args(lay, dev_tables, q, kv_pool, kv_scales, workspace)) return st;
   const psdev::AttnParams p = make_params(lay, dev_tables, q, kv_pool, kv_scales, workspace);
-  return launch_range(lay, p, lay->prefix_variant, 0, lay->num_prefix_items, static_cast<hipStream_t>(stream));
+  return launch_set(lay, p, dev_tables, WorkSet::kPrefix, static_cast<hipStream_t>(stream));
 }
 
 int32_t ps_suffix_attention(const ps_layout* lay, const void* dev_tables, const void* q, const void* kv_pool,
                             const float* kv_scales, void* workspace, void* stream) {
   if (int32_t st = check_pass_args(lay, dev_tables, q, kv_pool, kv_scales, workspace)) return st;
   const psdev::AttnParams p = make_params(lay, dev_tables, q, kv_pool, kv_scales, workspace);
-  return launch_range(lay, p, lay->suffix_variant, lay->num_prefix_items,
-                      int(lay->items.size()) - lay->num_prefix_items, static_cast<hipStream_t>(stream));
+  return launch_set(lay, p, dev_tables, WorkSet::kSuffix, static_cast<hipStream_t>(stream));
 }
 
 int32_t ps_merge_states(const ps_layout* lay, const void* dev_tables, const void* workspace, void* out,
@@ -112,11 +116,10 @@ int32_t ps_prefix_suffix_attention(const ps_layout* lay, const void* dev_tables,
   if (int32_t st = check_pass_args(lay, dev_tables, q, kv_pool, kv_scales, workspace)) return st;
   const psdev::AttnParams p = make_params(lay, dev_tables, q, kv_pool, kv_scales, workspace);
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int n_all = int(lay->items.size());
   if (lay->prefix_variant == lay->suffix_variant)  // same kernel: one launch over the whole work list
-    return launch_range(lay, p, lay->prefix_variant, 0, n_all, st);
-  if (int32_t rc = launch_range(lay, p, lay->prefix_variant, 0, lay->num_prefix_items, st)) return rc;
-  return launch_range(lay, p, lay->suffix_variant, lay->num_prefix_items, n_all - lay->num_prefix_items, st);
+    return launch_set(lay, p, dev_tables, WorkSet::kAll, st);
+  if (int32_t rc = launch_set(lay, p, dev_tables, WorkSet::kPrefix, st)) return rc;
+  return launch_set(lay, p, dev_tables, WorkSet::kSuffix, st);
 }
 
 int32_t ps_decode_attention(const ps_layout* lay, const void* dev_tables, const void* q, const void* kv_pool,

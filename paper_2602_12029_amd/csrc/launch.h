@@ -8,8 +8,9 @@ namespace psdev {
 
 bool wave_supported(const ps_geometry& g);
 int32_t launch_wave_attention(const AttnParams& p, const ps_geometry& g, int item_begin, int n_items, hipStream_t st);
-int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max_rows, int item_begin, int n_items,
-                              hipStream_t st);
+// Persistent launch: workgroup w walks wg_items[wg_indptr[w] .. wg_indptr[w+1]).
+int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max_rows, int occ, const ps_item* wg_items,
+                              const int32_t* wg_indptr, int num_wg, hipStream_t st);
 int32_t launch_merge(const int32_t* slot_base, const float* ws_o, const float* ws_lse, void* out, float* out_lse,
                      int num_requests, const ps_geometry& g, hipStream_t st);
 

@@ -5,6 +5,7 @@
 // request on that prompt (each decode module starts from the same base cache, Method Eq. 6), and
 // only the model-specific segment is private (Efficiency Analysis Eq. 9).
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <numeric>
@@ -66,9 +67,12 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
     if (asked > 0) return round_up(asked, granule);
     return std::min<int64_t>(std::max<int64_t>(round_up(ideal, granule), round_up(256, granule)), round_up(4096, granule));
   };
-  const int64_t prefix_chunk = pick(opt.prefix_chunk_tokens);
-  const int64_t suffix_chunk = pick(opt.suffix_chunk_tokens);
   auto resolve = [&](int32_t v) { return v == PS_VARIANT_AUTO ? (mfma_ok ? PS_VARIANT_MFMA : PS_VARIANT_WAVE) : v; };
+  const int64_t mfma_cap = std::max<int64_t>(granule, kPsMfmaMaxChunk / granule * granule);
+  int64_t prefix_chunk = pick(opt.prefix_chunk_tokens);
+  int64_t suffix_chunk = pick(opt.suffix_chunk_tokens);
+  if (resolve(opt.prefix_variant) == PS_VARIANT_MFMA) prefix_chunk = std::min(prefix_chunk, mfma_cap);
+  if (resolve(opt.suffix_variant) == PS_VARIANT_MFMA) suffix_chunk = std::min(suffix_chunk, mfma_cap);
 
   lay->opt = opt;
   lay->prefix_variant = resolve(opt.prefix_variant);
@@ -146,15 +150,74 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   }
   lay->num_slots = slots;
 
-  // device blob: [block ids: prefix ++ suffix][request list: group_req ++ identity][items][slot_base]
+  // Schedules for the persistent MFMA kernel: longest-processing-time-first packing of a set of items
+  // onto the resident workgroups (cost = tokens + a fixed per-item charge), each list longest first.
+  struct packed { std::vector<ps_item> items; std::vector<int32_t> indptr; int32_t max_rows = 0, occ = 1; };
+  auto pack = [&](int begin, int end) {
+    packed out;
+    const int count = end - begin;
+    for (int i = begin; i < end; ++i) out.max_rows = std::max(out.max_rows, lay->items[size_t(i)].n_req * group);
+    out.occ = ps_mfma_occupancy(out.max_rows, g.kv_dtype);
+    const int num_wg = std::max(1, std::min(count, num_cus * out.occ));
+    std::vector<int> order(size_t(count), 0);
+    std::iota(order.begin(), order.end(), begin);
+    auto cost = [&](int i) { return int64_t(lay->items[size_t(i)].tok_end - lay->items[size_t(i)].tok_begin) + 64; };
+    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return cost(a) > cost(b); });
+    std::vector<std::vector<int>> lists{size_t(num_wg)};
+    std::set<std::pair<int64_t, int>> load;  // (assigned cost, workgroup)
+    for (int w = 0; w < num_wg; ++w) load.insert({0, w});
+    for (int i : order) {
+      auto least = *load.begin();
+      load.erase(load.begin());
+      lists[size_t(least.second)].push_back(i);
+      load.insert({least.first + cost(i), least.second});
+    }
+    out.indptr.push_back(0);
+    for (const auto& l : lists) {
+      for (int i : l) out.items.push_back(lay->items[size_t(i)]);
+      out.indptr.push_back(int32_t(out.items.size()));
+    }
+    if (count == 0) out.indptr.assign(1, 0);
+    return out;
+  };
+  const int n_items = int(lay->items.size());
+  const bool pre_mfma = lay->prefix_variant == PS_VARIANT_MFMA, suf_mfma = lay->suffix_variant == PS_VARIANT_MFMA;
+  packed pk_prefix, pk_suffix, pk_all;
+  if (pre_mfma) pk_prefix = pack(0, lay->num_prefix_items);
+  if (suf_mfma) pk_suffix = pack(lay->num_prefix_items, n_items);
+  if (pre_mfma && suf_mfma) pk_all = pack(0, n_items);
+
+  // device blob: [block ids: prefix ++ suffix][request list: group_req ++ identity][items][slot_base][schedules]
   auto pad4 = [](int64_t n) { return (n + 3) / 4 * 4; };
   lay->off_blk = 0;
   lay->off_req = pad4(lay->off_blk + int64_t(lay->prefix_blk.size() + lay->suffix_blk.size()));
   lay->off_items = pad4(lay->off_req + 2 * int64_t(R));
   lay->off_slot = pad4(lay->off_items + 8 * int64_t(lay->items.size()));
-  const int64_t words = pad4(lay->off_slot + R + 1);
+  int64_t words = pad4(lay->off_slot + R + 1);
+  auto place = [&](ps_layout::schedule& s, const packed& pk) {
+    s = ps_layout::schedule{};
+    if (pk.items.empty()) return;
+    s.num_wg = int32_t(pk.indptr.size()) - 1;
+    s.max_rows = pk.max_rows;
+    s.occ = pk.occ;
+    s.off_items = words;
+    words = pad4(words + 8 * int64_t(pk.items.size()));
+    s.off_indptr = words;
+    words = pad4(words + int64_t(pk.indptr.size()));
+  };
+  place(lay->sched_prefix, pk_prefix);
+  place(lay->sched_suffix, pk_suffix);
+  place(lay->sched_all, pk_all);
   lay->blob.assign(size_t(std::max<int64_t>(words, 4)), 0);
   int32_t* b = lay->blob.data();
+  auto fill = [&](const ps_layout::schedule& s, const packed& pk) {
+    if (pk.items.empty()) return;
+    std::memcpy(b + s.off_items, pk.items.data(), pk.items.size() * sizeof(ps_item));
+    std::copy(pk.indptr.begin(), pk.indptr.end(), b + s.off_indptr);
+  };
+  fill(lay->sched_prefix, pk_prefix);
+  fill(lay->sched_suffix, pk_suffix);
+  fill(lay->sched_all, pk_all);
   std::copy(lay->prefix_blk.begin(), lay->prefix_blk.end(), b + lay->off_blk);
   std::copy(lay->suffix_blk.begin(), lay->suffix_blk.end(), b + lay->off_blk + lay->prefix_blk.size());
   std::copy(lay->group_req.begin(), lay->group_req.end(), b + lay->off_req);

@@ -1,9 +1,10 @@
-// Grouped-query attention over a KV token range on the gfx950 matrix cores (bf16 Q, bf16 or e4m3 KV).
+// Grouped-query attention over KV token ranges on the gfx950 matrix cores (bf16 Q, bf16 or e4m3 KV).
 //
-// One workgroup (4 waves) handles one work item: a token range of one KV segment and one KV head,
-// applied to every query row that reads it (all requests sharing the prefix x the G q heads of the
-// KV head's group; a private suffix has just the G rows of its request).  Each K/V byte of the
-// range is loaded from HBM exactly once, straight into the MFMA operand registers of one wave.
+// Persistent kernel: every workgroup (4 waves) walks its own list of work items, fixed by the host
+// plan.  A work item is a token range of one KV segment and one KV head, applied to every query row
+// that reads it (all requests sharing the prefix x the G q heads of the KV head's group; a private
+// suffix has just the G rows of its request).  Each K/V byte of the range is loaded from HBM exactly
+// once, straight into the MFMA operand registers of one wave.
 //
 // Per wave, per tile of 32 tokens (two 16-token blocks a, b), with rows padded to 16-row tiles:
 //   S^T[token, row] = K[token, :] . Q[row, :]        v_mfma_f32_16x16x32_bf16, A = K, B = Q^T
@@ -13,9 +14,16 @@
 // layout PV needs, so probabilities never leave their lane.  K rows are fetched 16 bytes per lane in
 // the A layout (the contraction index is permuted consistently in K and Q); V is fetched row-wise
 // (one 16-lane group covers a full token row) and transposed inside each lane with 16-bit picks.
-// Waves take tiles round-robin, keep private (max, sum, O) state and are merged through LDS at the
-// end into one normalised partial state per (request, q head).
-#include <cstdlib>
+//
+// Streaming: a wave owns a ring of NB tile buffers in VGPRs; the loads of the tile NB - 1 slots ahead
+// are issued before the math of the current one.  Every slot issues the same 16 buffer loads -- a slot
+// without a tile uses a zero-sized buffer descriptor, which returns zeros without touching memory -- so
+// the inner loop has no branch around a memory instruction and the outstanding-load counter the
+// compiler waits on is exact (a conditional load anywhere in the loop makes it wait for *all* loads,
+// including the prefetch).  The ring runs across item boundaries: the last NB - 1 slots of an item
+// fetch the first tiles of the workgroup's next item, whose block ids and query rows were fetched
+// one item earlier, so the cross-wave merge and partial-state store at the end of an item overlap
+// with loads in flight.
 #include <type_traits>
 
 #include "device_common.h"
@@ -27,23 +35,28 @@ namespace {
 
 constexpr int kD = 128;
 constexpr int kWaves = 4;
-constexpr int kTile = 32;        // tokens per wave iteration
-constexpr int kLdsRow = kD + 4;  // padded row of the merge buffer
+constexpr int kTile = 32;         // tokens per tile buffer
+constexpr int kLdsRow = kD + 4;   // padded row of the merge buffer (floats)
+constexpr int kQRow = kD + 8;     // padded query row (bf16), 16 bytes of padding against bank conflicts
+constexpr int kHdrRing = 128;     // item headers staged in LDS (circular, refilled in halves)
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
 template <int KVT>
-struct TileRegs;                 // raw K/V of one 32-token tile as loaded
+struct TileRegs;                  // raw K/V of one 32-token tile as loaded
 template <>
 struct TileRegs<PS_BF16> {
-  uint4 k[2][4];                 // [block][k-step]: 8 bf16 of token (lane%16), d-chunk 4*step + lane/16
-  uint4 v[8];                    // token i of this lane's 8 tokens, d columns 8*(lane%16)..+7
+  u32x4 k[2][4];                  // [block][k-step]: 8 bf16 of token (lane%16), d-chunk 4*step + lane/16
+  u32x4 v[8];                     // token i of this lane's 8 tokens, d columns 8*(lane%16)..+7
 };
 template <>
 struct TileRegs<PS_FP8_E4M3> {
-  uint4 k[2][2];                 // [block][half]: 16 codes of token (lane%16), d 64*half + 16*(lane/16)..+15
-  uint2 v[8];                    // 8 codes: token i, d columns 8*(lane%16)..+7
+  u32x4 k[2][2];                  // [block][half]: 16 codes of token (lane%16), d 64*half + 16*(lane/16)..+15
+  u32x2 v[8];                     // 8 codes: token i, d columns 8*(lane%16)..+7
 };
 
-__device__ __forceinline__ bf16x8 as_bf16x8(uint4 v) { return __builtin_bit_cast(bf16x8, v); }
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
 // two e4m3 codes (bytes 2*half, 2*half+1 of w) -> two bf16 in one register (exact)
 __device__ __forceinline__ uint32_t e4m3x2_to_bf16x2(uint32_t w, bool hi) {
@@ -54,8 +67,8 @@ __device__ __forceinline__ uint32_t e4m3x2_to_bf16x2(uint32_t w, bool hi) {
   return __builtin_bit_cast(uint32_t, b);
 }
 
-__device__ __forceinline__ uint4 e4m3x8_to_bf16x8(uint32_t lo, uint32_t hi) {
-  uint4 r;
+__device__ __forceinline__ u32x4 e4m3x8_to_bf16x8(uint32_t lo, uint32_t hi) {
+  u32x4 r;
   r.x = e4m3x2_to_bf16x2(lo, false);
   r.y = e4m3x2_to_bf16x2(lo, true);
   r.z = e4m3x2_to_bf16x2(hi, false);
@@ -70,136 +83,182 @@ __device__ __forceinline__ int q_chunk_elem(int step, int kg) {
   return 64 * (step >> 1) + 16 * kg + 8 * (step & 1);
 }
 
+// Wave-uniform view of one work item for one wave.
+struct ItemCtx {
+  int blk_off, tok_begin, tok_end, req_off, n_req, kv_head, split_local;
+  int rows, nt_used, my_tiles, sub0, sub_end;
+};
+
+// Per-lane metadata of an item: block ids (and e4m3 scales) of this wave's tiles.
+struct ItemMeta {
+  int ids;
+  float ksc, vsc;
+};
+
+template <int NT>
+struct QIndex { int idx[NT]; };   // global q row (request * Hq + head) this thread fetches per row tile, -1 = padding
+template <int NT>
+struct QRegs { u32x4 piece[NT]; };
+
 }  // namespace
 
-// NT: 16-row tiles carried; NB: tile buffers in registers (NB - 1 tiles of loads in flight ahead of the
-// math); OCC: waves per SIMD the register budget is sized for.
+// NT: 16-row tiles carried; NB: tile buffers in the register ring; OCC: waves per SIMD the register
+// budget is sized for.
 template <int NT, int KVT, int NB, int OCC>
-__global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, int item_begin) {
+__global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, const ps_item* __restrict__ wg_items,
+                                                                  const int32_t* __restrict__ wg_indptr) {
   __shared__ float sm_o[kWaves][16][kLdsRow];
   __shared__ float sm_m[kWaves][16];
   __shared__ float sm_l[kWaves][16];
-  __shared__ __attribute__((aligned(16))) uint16_t sm_q[NT][16][kD + 8];  // rows padded by 16 B against bank conflicts
+  __shared__ __attribute__((aligned(16))) uint16_t sm_q[NT][16][kQRow];
+  __shared__ __attribute__((aligned(16))) int32_t sm_hdr[kHdrRing][8];
 
-  const ps_item it = p.items[item_begin + blockIdx.x];
+  const int j_first = wg_indptr[blockIdx.x], j_last = wg_indptr[blockIdx.x + 1];
+  if (j_first >= j_last) return;
+
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
   const int n = lane & 15;   // query row within a row tile / token within a block / d-chunk, by role
   const int kg = lane >> 4;
   const int G = p.group;
-  const int rows = it.n_req * G;
-  const int nt_used = (rows + 15) >> 4;
   const float neg_inf = -__builtin_inff();
   const int sub_per_blk = p.block_size >> 4;  // 16-token sub-blocks per physical block
+  constexpr int kEsz = KVT == PS_BF16 ? 2 : 1;
+  const int tok_bytes = int(p.s_tok) * kEsz;
+  const int kv_bytes = int(p.s_kv) * kEsz;    // K -> V distance inside a (block, head)
+  // per-lane byte offsets inside a 16-token sub-block
+  const int k_lane_off = n * tok_bytes + kg * 16;
+  const int v_lane_off = 4 * kg * tok_bytes + n * (8 * kEsz);
 
-  // ---- query rows, staged in LDS and re-read as B operands for every tile ------------------------------
-  // (keeping them in registers would cost 16 VGPRs per row tile for the whole kernel)
-  {
-    const int r = threadIdx.x >> 4, c = threadIdx.x & 15;  // one 16-byte piece per thread and row tile
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-      const int row = 16 * t + r;
-      uint4 piece = uint4{0, 0, 0, 0};
-      if (row < rows) {
-        const int req = p.req_list[it.req_off + row / G];
-        const int h = it.kv_head * G + row % G;
-        piece = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(p.q) +
-                                                (int64_t(req) * p.num_q_heads + h) * kD + 8 * c);
-      }
-      *reinterpret_cast<uint4*>(&sm_q[t][r][8 * c]) = piece;
-    }
-  }
-  __syncthreads();
-
-  // ---- per-wave tile schedule ----------------------------------------------------------------------
-  const int span = it.tok_end - it.tok_begin;
-  const int tiles_total = (span + kTile - 1) / kTile;
-  const int my_tiles = tiles_total > wave ? (tiles_total - wave + kWaves - 1) / kWaves : 0;
-  const int sub0 = it.tok_begin >> 4;  // first 16-token sub-block of the item within its segment
-  const int sub_end = (it.tok_end + 15) >> 4;
-
-  // block ids (and fp8 scales) of the next 32 tiles of this wave: lane 2j+h <- sub-block h of tile j
-  int ids = 0;
-  float ksc = 1.f, vsc = 1.f;
-  auto fetch_ids = [&](int tile_first) {
-    const int k = tile_first + (lane >> 1);
-    const int sub = sub0 + 2 * (wave + kWaves * k) + (lane & 1);
-    ids = 0;
-    ksc = 1.f;
-    vsc = 1.f;
-    if (k < my_tiles && sub < sub_end) {
-      ids = p.blk[it.blk_off + sub / sub_per_blk];
-      if constexpr (KVT == PS_FP8_E4M3) {
-        const float* sc = p.scales + (int64_t(ids) * p.num_kv_heads + it.kv_head) * 2;
-        ksc = sc[0];
-        vsc = sc[1];
-      }
-    }
+  // ---- item headers: staged in LDS (circular) so that looking two items ahead costs no memory round trip ----
+  auto stage_headers = [&](int first, int count) {   // items [first, first + count) -> their ring slots
+    const int32_t* src = reinterpret_cast<const int32_t*>(wg_items + first);
+    for (int i = threadIdx.x; i < count * 8; i += 256)
+      sm_hdr[((first - j_first) + (i >> 3)) % kHdrRing][i & 7] = src[i];
+  };
+  auto item_ctx = [&](int j) {
+    const int32_t* h = sm_hdr[(j - j_first) % kHdrRing];
+    ItemCtx c;
+    c.blk_off = __builtin_amdgcn_readfirstlane(h[0]);
+    c.tok_begin = __builtin_amdgcn_readfirstlane(h[1]);
+    c.tok_end = __builtin_amdgcn_readfirstlane(h[2]);
+    c.req_off = __builtin_amdgcn_readfirstlane(h[3]);
+    c.n_req = __builtin_amdgcn_readfirstlane(h[4]);
+    c.kv_head = __builtin_amdgcn_readfirstlane(h[5]);
+    c.split_local = __builtin_amdgcn_readfirstlane(h[6]);
+    c.rows = c.n_req * G;
+    c.nt_used = (c.rows + 15) >> 4;
+    const int tiles_total = (c.tok_end - c.tok_begin + kTile - 1) / kTile;
+    c.my_tiles = tiles_total > wave ? (tiles_total - wave + kWaves - 1) / kWaves : 0;
+    c.sub0 = c.tok_begin >> 4;
+    c.sub_end = (c.tok_end + 15) >> 4;
+    return c;
   };
 
-  const int64_t head_off = int64_t(it.kv_head) * p.s_head;
-  using Elem = typename std::conditional<KVT == PS_BF16, uint16_t, uint8_t>::type;
-  const Elem* kv = static_cast<const Elem*>(p.kv);
+  // block ids (and scales) of this wave's tiles of an item: lane 2k+h <- 16-token block h of tile k
+  auto fetch_meta = [&](const ItemCtx& c) {
+    ItemMeta m{0, 1.f, 1.f};
+    const int k = lane >> 1;
+    const int sub = c.sub0 + 2 * (wave + kWaves * k) + (lane & 1);
+    if (k < c.my_tiles && sub < c.sub_end) {
+      m.ids = p.blk[c.blk_off + sub / sub_per_blk];
+      if constexpr (KVT == PS_FP8_E4M3) {
+        const float* sc = p.scales + (int64_t(m.ids) * p.num_kv_heads + c.kv_head) * 2;
+        m.ksc = sc[0];
+        m.vsc = sc[1];
+      }
+    }
+    return m;
+  };
 
-  auto load_tile = [&](TileRegs<KVT>& tr, int k) {
-    const int kl = k & 31;
+  // query rows: one 16-byte piece per thread and row tile (row = thread / 16, piece = thread % 16)
+  auto q_row_index = [&](const ItemCtx& c) {
+    QIndex<NT> r;
+    const int rr = threadIdx.x >> 4;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      const int row = 16 * t + rr;
+      r.idx[t] = -1;
+      if (row < c.rows) r.idx[t] = p.req_list[c.req_off + row / G] * p.num_q_heads + c.kv_head * G + row % G;
+    }
+    return r;
+  };
+  auto load_q = [&](const QIndex<NT>& rows_idx) {
+    QRegs<NT> q;
+    const int cpiece = threadIdx.x & 15;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      q.piece[t] = u32x4{0, 0, 0, 0};
+      if (rows_idx.idx[t] >= 0)
+        q.piece[t] = *reinterpret_cast<const u32x4*>(static_cast<const uint16_t*>(p.q) +
+                                                     int64_t(rows_idx.idx[t]) * kD + 8 * cpiece);
+    }
+    return q;
+  };
+  auto store_q = [&](const QRegs<NT>& q) {
+    const int rr = threadIdx.x >> 4, cpiece = threadIdx.x & 15;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) *reinterpret_cast<u32x4*>(&sm_q[t][rr][8 * cpiece]) = q.piece[t];
+  };
+
+  // ---- tile loads: buffer loads, block base in SGPRs, two loop-invariant VGPR offsets ---------------------
+  // `live` false (or a 16-token block past the segment end) gives a zero-sized descriptor: zeros, no traffic.
+  const int64_t kv_base = reinterpret_cast<int64_t>(p.kv);
+  auto load_tile = [&](TileRegs<KVT>& tr, int sub0, int sub_end, int kv_head, int id_a, int id_b, int k, bool live) {
     const int sub_a = sub0 + 2 * (wave + kWaves * k);
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
       const int sub = sub_a + b;
-      if (sub < sub_end) {
-        const int id = __builtin_amdgcn_readlane(ids, 2 * kl + b);
-        const Elem* base = kv + int64_t(id) * p.s_block + head_off + int64_t((sub % sub_per_blk) << 4) * p.s_tok;
-        const Elem* krow = base + int64_t(n) * p.s_tok;
-        const Elem* vbase = base + p.s_kv + int64_t(4 * kg) * p.s_tok + 8 * n;
-        if constexpr (KVT == PS_BF16) {
+      const bool valid = live && sub < sub_end;
+      const int id = b ? id_b : id_a;
+      const int64_t off = (int64_t(id) * p.s_block + int64_t(kv_head) * p.s_head +
+                           int64_t((sub % sub_per_blk) << 4) * p.s_tok) * kEsz;
+      const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+          reinterpret_cast<void*>(valid ? kv_base + off : kv_base), 0, valid ? 0x7fffffff : 0, 0x00020000);
+      if constexpr (KVT == PS_BF16) {
 #pragma unroll
-          for (int s = 0; s < 4; ++s) tr.k[b][s] = *reinterpret_cast<const uint4*>(krow + 32 * s + 8 * kg);
+        for (int s = 0; s < 4; ++s) tr.k[b][s] = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off + 64 * s, 0, 0);
 #pragma unroll
-          for (int i = 0; i < 4; ++i) tr.v[4 * b + i] = *reinterpret_cast<const uint4*>(vbase + int64_t(i) * p.s_tok);
-        } else {
-#pragma unroll
-          for (int s = 0; s < 2; ++s) tr.k[b][s] = *reinterpret_cast<const uint4*>(krow + 64 * s + 16 * kg);
-#pragma unroll
-          for (int i = 0; i < 4; ++i) tr.v[4 * b + i] = *reinterpret_cast<const uint2*>(vbase + int64_t(i) * p.s_tok);
-        }
+        for (int i = 0; i < 4; ++i)
+          tr.v[4 * b + i] = __builtin_amdgcn_raw_buffer_load_b128(rs, v_lane_off, kv_bytes + i * tok_bytes, 0);
       } else {
-        if constexpr (KVT == PS_BF16) {
 #pragma unroll
-          for (int s = 0; s < 4; ++s) tr.k[b][s] = uint4{0, 0, 0, 0};
+        for (int s = 0; s < 2; ++s) tr.k[b][s] = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off + 64 * s, 0, 0);
 #pragma unroll
-          for (int i = 0; i < 4; ++i) tr.v[4 * b + i] = uint4{0, 0, 0, 0};
-        } else {
-#pragma unroll
-          for (int s = 0; s < 2; ++s) tr.k[b][s] = uint4{0, 0, 0, 0};
-#pragma unroll
-          for (int i = 0; i < 4; ++i) tr.v[4 * b + i] = uint2{0, 0};
-        }
+        for (int i = 0; i < 4; ++i)
+          tr.v[4 * b + i] = __builtin_amdgcn_raw_buffer_load_b64(rs, v_lane_off, kv_bytes + i * tok_bytes, 0);
       }
     }
   };
+  // tile k of an item of this wave (k may lie past the item's tiles: then nothing is fetched)
+  auto load_item_tile = [&](TileRegs<KVT>& tr, const ItemCtx& c, const ItemMeta& m, int k, bool live) {
+    const int idx = (2 * k) & 63;
+    load_tile(tr, c.sub0, c.sub_end, c.kv_head, __builtin_amdgcn_readlane(m.ids, idx),
+              __builtin_amdgcn_readlane(m.ids, idx + 1), k, live && k < c.my_tiles);
+  };
 
-  // ---- running state ---------------------------------------------------------------------------------
+  // ---- running state of the current item -------------------------------------------------------------------
   float m_run[NT], l_run[NT];
   f32x4 acc[NT][8];
+  auto reset_state = [&]() {
 #pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    m_run[t] = neg_inf;
-    l_run[t] = 0.f;
+    for (int t = 0; t < NT; ++t) {
+      m_run[t] = neg_inf;
+      l_run[t] = 0.f;
 #pragma unroll
-    for (int c = 0; c < 8; ++c) acc[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
+      for (int c = 0; c < 8; ++c) acc[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+  };
 
-  auto compute_tile = [&](TileRegs<KVT>& tr, int k) {
-    const int kl = k & 31;
-    const int tok0 = it.tok_begin + kTile * (wave + kWaves * k);  // first token of the tile
-    const bool full = tok0 + kTile <= it.tok_end;
+  auto compute_tile = [&](TileRegs<KVT>& tr, const ItemCtx& c, const ItemMeta& meta, int k) {
+    const int tok0 = c.tok_begin + kTile * (wave + kWaves * k);  // first token of the tile
+    const bool full = tok0 + kTile <= c.tok_end;
     float sc_k[2] = {p.scale_log2, p.scale_log2}, sc_v[2] = {1.f, 1.f};
     if constexpr (KVT == PS_FP8_E4M3) {
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
-        sc_k[b] *= __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ksc), 2 * kl + b));
-        sc_v[b] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(vsc), 2 * kl + b));
+        sc_k[b] *= __int_as_float(__builtin_amdgcn_readlane(__float_as_int(meta.ksc), 2 * k + b));
+        sc_v[b] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(meta.vsc), 2 * k + b));
       }
     }
 
@@ -218,30 +277,16 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
         }
       }
     }
-    // V rows of this lane's 8 tokens as bf16, invalid tokens zeroed (their slots may hold anything)
-    uint4 vr[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      if constexpr (KVT == PS_BF16) vr[i] = tr.v[i];
-      else vr[i] = e4m3x8_to_bf16x8(tr.v[i].x, tr.v[i].y);
-    }
-    if (!full) {
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int tok = tok0 + 16 * (i >> 2) + 4 * kg + (i & 3);
-        if (tok >= it.tok_end) vr[i] = uint4{0, 0, 0, 0};
-      }
-    }
     // scores and probabilities of every row tile first ...
     bf16x8 pb[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       pb[t] = bf16x8{};
-      if (t < nt_used) {
+      if (t < c.nt_used) {
         bf16x8 qb[4];
 #pragma unroll
         for (int st = 0; st < 4; ++st)
-          qb[st] = as_bf16x8(*reinterpret_cast<const uint4*>(&sm_q[t][n][q_chunk_elem<KVT>(st, kg)]));
+          qb[st] = as_bf16x8(*reinterpret_cast<const u32x4*>(&sm_q[t][n][q_chunk_elem<KVT>(st, kg)]));
         f32x4 s[2];
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
@@ -255,7 +300,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
           for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-              if (tok0 + 16 * b + 4 * kg + j >= it.tok_end) s[b][j] = neg_inf;
+              if (tok0 + 16 * b + 4 * kg + j >= c.tok_end) s[b][j] = neg_inf;
         }
         float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
                          fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
@@ -266,7 +311,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
           const float alpha = fast_exp2(m_run[t] - m_new);
           l_run[t] *= alpha;
 #pragma unroll
-          for (int c = 0; c < 8; ++c) acc[t][c] *= alpha;
+          for (int cc = 0; cc < 8; ++cc) acc[t][cc] *= alpha;
           m_run[t] = m_new;
         }
         float lsum = 0.f;
@@ -281,134 +326,193 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
         l_run[t] += lsum;
       }
     }
-    // ... then O^T += V^T P^T, one 16-column group of V at a time, transposed inside the lane:
-    // vt = column c of this lane's 8 token rows
+    // V rows of this lane's 8 tokens as bf16, invalid tokens zeroed (their slots may hold anything)
+    u32x4 vr[8];
 #pragma unroll
-    for (int c = 0; c < 8; ++c) {
+    for (int i = 0; i < 8; ++i) {
+      if constexpr (KVT == PS_BF16) vr[i] = tr.v[i];
+      else vr[i] = e4m3x8_to_bf16x8(tr.v[i].x, tr.v[i].y);
+    }
+    if (!full) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int tok = tok0 + 16 * (i >> 2) + 4 * kg + (i & 3);
+        if (tok >= c.tok_end) vr[i] = u32x4{0, 0, 0, 0};
+      }
+    }
+    // ... then O^T += V^T P^T, one 16-column group of V at a time, transposed inside the lane:
+    // vt = column cc of this lane's 8 token rows
+#pragma unroll
+    for (int cc = 0; cc < 8; ++cc) {
       uint32_t w[4];
 #pragma unroll
       for (int i2 = 0; i2 < 4; ++i2) {
-        const uint32_t* r0 = reinterpret_cast<const uint32_t*>(&vr[2 * i2]);
-        const uint32_t* r1 = reinterpret_cast<const uint32_t*>(&vr[2 * i2 + 1]);
-        const uint32_t a = r0[c >> 1], b = r1[c >> 1];
-        w[i2] = (c & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
+        const uint32_t a = vr[2 * i2][cc >> 1], b = vr[2 * i2 + 1][cc >> 1];
+        w[i2] = (cc & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
       }
-      const bf16x8 vt = as_bf16x8(uint4{w[0], w[1], w[2], w[3]});
+      const bf16x8 vt = as_bf16x8(u32x4{w[0], w[1], w[2], w[3]});
 #pragma unroll
       for (int t = 0; t < NT; ++t)
-        if (t < nt_used) acc[t][c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, pb[t], acc[t][c], 0, 0, 0);
+        if (t < c.nt_used) acc[t][cc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, pb[t], acc[t][cc], 0, 0, 0);
     }
   };
 
-  // ---- stream the tiles, NB - 1 tiles of loads in flight ahead of the math ---------------------------
-  TileRegs<KVT> buf[NB];
-  for (int k0 = 0; k0 < my_tiles; k0 += 32) {
-    fetch_ids(k0);
-    const int k1 = min(my_tiles, k0 + 32);
+  // merge the four waves of the item and write one partial state per row
+  auto epilogue = [&](const ItemCtx& c) {
 #pragma unroll
-    for (int u = 0; u < NB - 1; ++u)
-      if (k0 + u < k1) load_tile(buf[u], k0 + u);
-    for (int k = k0; k < k1; k += NB) {
+    for (int t = 0; t < NT; ++t) {
+      if (t < c.nt_used) {
+        float l = l_run[t];
+        l += lane_xor(l, 16);
+        l += lane_xor(l, 32);
+        if (kg == 0) {
+          sm_m[wave][n] = m_run[t];
+          sm_l[wave][n] = l;
+        }
+        // lane (n, kg), acc[cc][j] = O[row n][32 kg + 8 j + cc]
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          *reinterpret_cast<f32x4*>(&sm_o[wave][n][32 * kg + 8 * j]) =
+              f32x4{acc[t][0][j], acc[t][1][j], acc[t][2][j], acc[t][3][j]};
+          *reinterpret_cast<f32x4*>(&sm_o[wave][n][32 * kg + 8 * j + 4]) =
+              f32x4{acc[t][4][j], acc[t][5][j], acc[t][6][j], acc[t][7][j]};
+        }
+        __syncthreads();
+        const int r = threadIdx.x >> 4;  // row of the tile
+        const int c0 = (threadIdx.x & 15) * 8;
+        const int row = 16 * t + r;
+        if (row < c.rows) {
+          float mw[kWaves], mn = neg_inf;
+#pragma unroll
+          for (int w = 0; w < kWaves; ++w) {
+            mw[w] = sm_m[w][r];
+            mn = fmaxf(mn, mw[w]);
+          }
+          float coef[kWaves], lsum = 0.f;
+#pragma unroll
+          for (int w = 0; w < kWaves; ++w) {
+            coef[w] = (mw[w] == neg_inf) ? 0.f : fast_exp2(mw[w] - mn);
+            lsum += coef[w] * sm_l[w][r];
+          }
+          const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
+          f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int w = 0; w < kWaves; ++w) {
+            if (coef[w] != 0.f) {
+              o0 += coef[w] * *reinterpret_cast<const f32x4*>(&sm_o[w][r][c0]);
+              o1 += coef[w] * *reinterpret_cast<const f32x4*>(&sm_o[w][r][c0 + 4]);
+            }
+          }
+          const int req = p.req_list[c.req_off + row / G];
+          const int h = c.kv_head * G + row % G;
+          const int64_t slot = int64_t(p.slot_base[req]) + c.split_local;
+          float* o = p.ws_o + (slot * p.num_q_heads + h) * kD + c0;
+          *reinterpret_cast<f32x4*>(o) = o0 * inv;
+          *reinterpret_cast<f32x4*>(o + 4) = o1 * inv;
+          if ((threadIdx.x & 15) == 0)
+            p.ws_lse[slot * p.num_q_heads + h] = lsum > 0.f ? (mn + __builtin_amdgcn_logf(lsum)) * kLn2 : neg_inf;
+        }
+        __syncthreads();
+      }
+    }
+  };
+
+  // ---- walk the item list ------------------------------------------------------------------------------------
+  // Software pipeline over items: `cur` streams; `nxt` has its block ids and query-row indices in registers
+  // (fetched one iteration ago); the item after that gets its fetches issued now.
+  stage_headers(j_first, min(kHdrRing, j_last - j_first));
+  __syncthreads();
+  ItemCtx cur = item_ctx(j_first);
+  ItemMeta meta = fetch_meta(cur);
+  // first tiles go out as soon as the block ids are here; the query rows follow while they fly
+  TileRegs<KVT> buf[NB];
+#pragma unroll
+  for (int u = 0; u < NB - 1; ++u) load_item_tile(buf[u], cur, meta, u, true);
+  store_q(load_q(q_row_index(cur)));
+  bool has_next = j_first + 1 < j_last;
+  ItemCtx nxt = cur;
+  ItemMeta meta_nxt{0, 1.f, 1.f};
+  QIndex<NT> q_idx_nxt{};
+  if (has_next) {
+    nxt = item_ctx(j_first + 1);
+    meta_nxt = fetch_meta(nxt);
+    q_idx_nxt = q_row_index(nxt);
+  }
+  __syncthreads();
+
+  for (int j = j_first; j < j_last; ++j) {
+    // query rows of the next item (their indices arrived long ago), fetches for the item after it
+    QRegs<NT> q_nxt{};
+    if (has_next) q_nxt = load_q(q_idx_nxt);
+    const bool has_nn = j + 2 < j_last;
+    ItemCtx nn = nxt;
+    ItemMeta meta_nn{0, 1.f, 1.f};
+    QIndex<NT> q_idx_nn{};
+    if (has_nn) {
+      nn = item_ctx(j + 2);
+      meta_nn = fetch_meta(nn);
+      q_idx_nn = q_row_index(nn);
+    }
+
+    reset_state();
+    // every item occupies at least one full turn of the ring, so its last NB - 1 slots always exist to
+    // fetch ahead into the next item
+    const int slots = max(NB, (cur.my_tiles + NB - 1) / NB * NB);
+    for (int s0 = 0; s0 < slots; s0 += NB) {
 #pragma unroll
       for (int u = 0; u < NB; ++u) {
-        const int kk = k + u;
-        if (kk < k1) {
-          if (kk + NB - 1 < k1) load_tile(buf[(u + NB - 1) % NB], kk + NB - 1);
-          compute_tile(buf[u], kk);
-        }
+        const int ahead = s0 + u + NB - 1;              // slot whose loads go out now
+        const bool in_next = ahead >= slots;
+        const int ka = in_next ? ahead - slots : ahead;
+        const int idx = (2 * ka) & 63;
+        const int id_a = in_next ? __builtin_amdgcn_readlane(meta_nxt.ids, idx) : __builtin_amdgcn_readlane(meta.ids, idx);
+        const int id_b = in_next ? __builtin_amdgcn_readlane(meta_nxt.ids, idx + 1)
+                                 : __builtin_amdgcn_readlane(meta.ids, idx + 1);
+        const bool live = in_next ? (has_next && ka < nxt.my_tiles) : (ka < cur.my_tiles);
+        load_tile(buf[(u + NB - 1) % NB], in_next ? nxt.sub0 : cur.sub0, in_next ? nxt.sub_end : cur.sub_end,
+                  in_next ? nxt.kv_head : cur.kv_head, id_a, id_b, ka, live);
+        if (s0 + u < cur.my_tiles) compute_tile(buf[u], cur, meta, s0 + u);
       }
     }
-  }
 
-  // ---- merge the four waves and write one partial state per row ----------------------------------------
-#pragma unroll
-  for (int t = 0; t < NT; ++t) {
-    if (t < nt_used) {
-      float l = l_run[t];
-      l += lane_xor(l, 16);
-      l += lane_xor(l, 32);
-      if (kg == 0) {
-        sm_m[wave][n] = m_run[t];
-        sm_l[wave][n] = l;
-      }
-      // lane (n, kg), acc[c][j] = O[row n][32 kg + 8 j + c]
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        *reinterpret_cast<f32x4*>(&sm_o[wave][n][32 * kg + 8 * j]) =
-            f32x4{acc[t][0][j], acc[t][1][j], acc[t][2][j], acc[t][3][j]};
-        *reinterpret_cast<f32x4*>(&sm_o[wave][n][32 * kg + 8 * j + 4]) =
-            f32x4{acc[t][4][j], acc[t][5][j], acc[t][6][j], acc[t][7][j]};
-      }
+    epilogue(cur);   // ends with a barrier: sm_q and the consumed half of the header ring are free
+
+    if (has_next) store_q(q_nxt);
+    const int li = j + 1 - j_first;                     // items consumed so far
+    if ((li % (kHdrRing / 2)) == 0) {                   // refill the half of the header ring just used up
+      const int first = j_first + li + kHdrRing / 2;
+      if (first < j_last) stage_headers(first, min(kHdrRing / 2, j_last - first));
     }
     __syncthreads();
-    if (t < nt_used) {
-      const int r = threadIdx.x >> 4;  // row of the tile
-      const int c0 = (threadIdx.x & 15) * 8;
-      const int row = 16 * t + r;
-      if (row < rows) {
-        float mw[kWaves], mn = neg_inf;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-          mw[w] = sm_m[w][r];
-          mn = fmaxf(mn, mw[w]);
-        }
-        float coef[kWaves], lsum = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-          coef[w] = (mw[w] == neg_inf) ? 0.f : fast_exp2(mw[w] - mn);
-          lsum += coef[w] * sm_l[w][r];
-        }
-        const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
-        f32x4 o0 = {0.f, 0.f, 0.f, 0.f}, o1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-          if (coef[w] != 0.f) {
-            o0 += coef[w] * *reinterpret_cast<const f32x4*>(&sm_o[w][r][c0]);
-            o1 += coef[w] * *reinterpret_cast<const f32x4*>(&sm_o[w][r][c0 + 4]);
-          }
-        }
-        const int req = p.req_list[it.req_off + row / G];
-        const int h = it.kv_head * G + row % G;
-        const int64_t slot = int64_t(p.slot_base[req]) + it.split_local;
-        float* o = p.ws_o + (slot * p.num_q_heads + h) * kD + c0;
-        *reinterpret_cast<f32x4*>(o) = o0 * inv;
-        *reinterpret_cast<f32x4*>(o + 4) = o1 * inv;
-        if ((threadIdx.x & 15) == 0)
-          p.ws_lse[slot * p.num_q_heads + h] = lsum > 0.f ? (mn + __builtin_amdgcn_logf(lsum)) * kLn2 : neg_inf;
-      }
-    }
-    __syncthreads();
+    cur = nxt;
+    meta = meta_nxt;
+    has_next = has_nn;
+    nxt = nn;
+    meta_nxt = meta_nn;
+    q_idx_nxt = q_idx_nn;
   }
 }
 
-int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max_rows, int item_begin, int n_items,
-                              hipStream_t st) {
-  if (n_items <= 0) return PS_OK;
+int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max_rows, int occ, const ps_item* wg_items,
+                              const int32_t* wg_indptr, int num_wg, hipStream_t st) {
+  if (num_wg <= 0) return PS_OK;
   if (g.head_dim != kD || g.q_dtype != PS_BF16 || g.block_size % 16 != 0 || max_rows > 64) return PS_ERR_UNSUPPORTED;
   if (g.kv_dtype != PS_BF16 && g.kv_dtype != PS_FP8_E4M3) return PS_ERR_UNSUPPORTED;
-  const dim3 grid(n_items), block(256);
+  const dim3 grid(num_wg), block(256);
   const int nt = max_rows <= 16 ? 1 : (max_rows <= 32 ? 2 : 4);
-  int cfg = 0;
-  if (const char* e = getenv("PS_MFMA_CFG")) cfg = atoi(e);
 #define PS_LAUNCH(NT, KVT, NB, OCC) \
-  hipLaunchKernelGGL((mfma_attention_kernel<NT, KVT, NB, OCC>), grid, block, 0, st, p, item_begin)
-#define PS_BY_CFG(NT, KVT)                     \
-  do {                                         \
-    if (cfg == 1) PS_LAUNCH(NT, KVT, 3, 1);    \
-    else if (cfg == 2) PS_LAUNCH(NT, KVT, 4, 1); \
-    else if (cfg == 4) PS_LAUNCH(NT, KVT, 2, 1); \
-    else PS_LAUNCH(NT, KVT, 2, 2);             \
-  } while (0)
+  hipLaunchKernelGGL((mfma_attention_kernel<NT, KVT, NB, OCC>), grid, block, 0, st, p, wg_items, wg_indptr)
+  // two tile buffers per wave everywhere (deeper rings measured no faster); `occ` is the residency the
+  // plan sized the grid for (ps_mfma_occupancy)
   if (g.kv_dtype == PS_BF16) {
-    if (nt == 1) PS_BY_CFG(1, PS_BF16);
-    else if (nt == 2) { if (cfg == 0) PS_LAUNCH(2, PS_BF16, 3, 1); else PS_BY_CFG(2, PS_BF16); }
+    if (nt == 1) { if (occ == 2) PS_LAUNCH(1, PS_BF16, 2, 2); else PS_LAUNCH(1, PS_BF16, 2, 1); }
+    else if (nt == 2) PS_LAUNCH(2, PS_BF16, 2, 1);
     else PS_LAUNCH(4, PS_BF16, 2, 1);
   } else {
-    if (nt == 1) PS_BY_CFG(1, PS_FP8_E4M3);
-    else if (nt == 2) PS_BY_CFG(2, PS_FP8_E4M3);
+    if (nt == 1) { if (occ == 2) PS_LAUNCH(1, PS_FP8_E4M3, 2, 2); else PS_LAUNCH(1, PS_FP8_E4M3, 2, 1); }
+    else if (nt == 2) { if (occ == 2) PS_LAUNCH(2, PS_FP8_E4M3, 2, 2); else PS_LAUNCH(2, PS_FP8_E4M3, 2, 1); }
     else PS_LAUNCH(4, PS_FP8_E4M3, 2, 1);
   }
-#undef PS_BY_CFG
 #undef PS_LAUNCH
   return PS_OK;
 }

@@ -42,10 +42,28 @@ struct ps_layout {
   std::vector<int32_t> slot_base;    // [R+1]
   int64_t num_slots = 0;
 
+  // persistent-kernel schedules: for a set of items, the items regrouped by workgroup (8 int32 each,
+  // workgroup w owns [indptr[w], indptr[w+1])) -- one schedule per launchable set
+  struct schedule {
+    int64_t off_items = 0, off_indptr = 0;  // blob offsets in words
+    int32_t num_wg = 0, max_rows = 0, occ = 1;  // occ: workgroups per compute unit the grid was sized for
+  };
+  schedule sched_prefix, sched_suffix, sched_all;
+
   // device table blob (int32 words) and section offsets in words
   std::vector<int32_t> blob;
   int64_t off_blk = 0, off_req = 0, off_items = 0, off_slot = 0;
 };
+
+// Waves per SIMD the MFMA kernel is built for, by the widest row group it must carry.
+inline int ps_mfma_occupancy(int max_rows, int kv_dtype) {
+  // two workgroups per compute unit where the kernel fits in 256 VGPRs: one 16-row tile, or e4m3 KV
+  // (half-size tile buffers) with up to two
+  if (max_rows <= 16) return 2;
+  if (max_rows <= 32 && kv_dtype == PS_FP8_E4M3) return 2;
+  return 1;
+}
+constexpr int kPsMfmaMaxChunk = 4096;  // tokens per MFMA work item (32 tiles per wave)
 
 // layout.cpp
 int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* opt);
