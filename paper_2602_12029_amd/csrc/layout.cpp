@@ -61,8 +61,9 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   for (int32_t l : lay->prefix_len) total += l;
   for (int32_t l : lay->suffix_len) total += l;
   total *= g.num_kv_heads;
-  // two workgroups per compute unit are resident; aim for about one full-size chunk per resident slot
-  const int64_t ideal = std::max<int64_t>(1, ceil_div(total, int64_t(num_cus) * 2));
+  // aim for about one full-size chunk per compute unit: long items amortise the per-item merge and keep
+  // the number of partial states (workspace traffic) low; the many small suffix items fill the gaps
+  const int64_t ideal = std::max<int64_t>(1, ceil_div(total, int64_t(num_cus)));
   auto pick = [&](int32_t asked) -> int64_t {
     if (asked > 0) return round_up(asked, granule);
     return std::min<int64_t>(std::max<int64_t>(round_up(ideal, granule), round_up(256, granule)), round_up(4096, granule));

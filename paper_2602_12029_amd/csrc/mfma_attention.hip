@@ -58,12 +58,12 @@ struct TileRegs<PS_FP8_E4M3> {
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
 
-// two e4m3 codes (bytes 2*half, 2*half+1 of w) -> two bf16 in one register (exact)
+// two e4m3 codes (bytes 2*half, 2*half+1 of w) -> two bf16 in one register (exact): one
+// v_cvt_scalef32_pk_bf16_fp8 with scale 1 (the instruction applies only the scale's exponent, so the real
+// per-block scales are applied to the scores and probabilities instead)
 __device__ __forceinline__ uint32_t e4m3x2_to_bf16x2(uint32_t w, bool hi) {
-  const f32x2 f = hi ? __builtin_amdgcn_cvt_pk_f32_fp8(w, true) : __builtin_amdgcn_cvt_pk_f32_fp8(w, false);
-  bf16x2 b;
-  b.x = (__bf16)f.x;
-  b.y = (__bf16)f.y;
+  const bf16x2 b = hi ? __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true)
+                      : __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false);
   return __builtin_bit_cast(uint32_t, b);
 }
 
