@@ -36,7 +36,8 @@ int32_t check_geometry(const ps_geometry& g) {
 
 bool ps_mfma_supported(const ps_geometry& g) {
   return g.q_dtype == PS_BF16 && (g.kv_dtype == PS_BF16 || g.kv_dtype == PS_FP8_E4M3) && g.head_dim == 128 &&
-         g.block_size % 16 == 0 && (g.num_q_heads / g.num_kv_heads) <= 64;
+         g.block_size % 16 == 0 && ((g.block_size / 16) & (g.block_size / 16 - 1)) == 0 &&  // 16, 32, 64, ...
+         (g.num_q_heads / g.num_kv_heads) <= 64;
 }
 
 // ---------------------------------------------------------------------------------------------------

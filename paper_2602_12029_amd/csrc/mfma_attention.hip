@@ -87,6 +87,7 @@ __device__ __forceinline__ int q_chunk_elem(int step, int kg) {
 struct ItemCtx {
   int blk_off, tok_begin, tok_end, req_off, n_req, kv_head, split_local;
   int rows, nt_used, my_tiles, sub0, sub_end;
+  int64_t head_base;   // address of the item's KV head slice in block 0
 };
 
 // Per-lane metadata of an item: block ids (and e4m3 scales) of this wave's tiles.
@@ -122,13 +123,19 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
   const int kg = lane >> 4;
   const int G = p.group;
   const float neg_inf = -__builtin_inff();
-  const int sub_per_blk = p.block_size >> 4;  // 16-token sub-blocks per physical block
+  // 16-token sub-blocks per physical block: a power of two (the launcher checks), so index math is shifts
+  const int sub_shift = __builtin_ctz(unsigned(p.block_size >> 4));
+  const int sub_mask = (p.block_size >> 4) - 1;
   constexpr int kEsz = KVT == PS_BF16 ? 2 : 1;
   const int tok_bytes = int(p.s_tok) * kEsz;
   const int kv_bytes = int(p.s_kv) * kEsz;    // K -> V distance inside a (block, head)
   // per-lane byte offsets inside a 16-token sub-block
   const int k_lane_off = n * tok_bytes + kg * 16;
   const int v_lane_off = 4 * kg * tok_bytes + n * (8 * kEsz);
+
+  const int64_t kv_base = reinterpret_cast<int64_t>(p.kv);
+  const int64_t blk_bytes = p.s_block * kEsz;
+  const int sub_bytes = 16 * tok_bytes;
 
   // ---- item headers: staged in LDS (circular) so that looking two items ahead costs no memory round trip ----
   auto stage_headers = [&](int first, int count) {   // items [first, first + count) -> their ring slots
@@ -152,6 +159,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
     c.my_tiles = tiles_total > wave ? (tiles_total - wave + kWaves - 1) / kWaves : 0;
     c.sub0 = c.tok_begin >> 4;
     c.sub_end = (c.tok_end + 15) >> 4;
+    c.head_base = kv_base + int64_t(c.kv_head) * p.s_head * kEsz;
     return c;
   };
 
@@ -161,7 +169,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
     const int k = lane >> 1;
     const int sub = c.sub0 + 2 * (wave + kWaves * k) + (lane & 1);
     if (k < c.my_tiles && sub < c.sub_end) {
-      m.ids = p.blk[c.blk_off + sub / sub_per_blk];
+      m.ids = p.blk[c.blk_off + (sub >> sub_shift)];
       if constexpr (KVT == PS_FP8_E4M3) {
         const float* sc = p.scales + (int64_t(m.ids) * p.num_kv_heads + c.kv_head) * 2;
         m.ksc = sc[0];
@@ -203,18 +211,18 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
 
   // ---- tile loads: buffer loads, block base in SGPRs, two loop-invariant VGPR offsets ---------------------
   // `live` false (or a 16-token block past the segment end) gives a zero-sized descriptor: zeros, no traffic.
-  const int64_t kv_base = reinterpret_cast<int64_t>(p.kv);
-  auto load_tile = [&](TileRegs<KVT>& tr, int sub0, int sub_end, int kv_head, int id_a, int id_b, int k, bool live) {
-    const int sub_a = sub0 + 2 * (wave + kWaves * k);
+  auto load_item_tile = [&](TileRegs<KVT>& tr, const ItemCtx& c, const ItemMeta& m, int k, bool live) {
+    const int sub_a = c.sub0 + 2 * (wave + kWaves * k);
+    const int idx = (2 * k) & 63;
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
       const int sub = sub_a + b;
-      const bool valid = live && sub < sub_end;
-      const int id = b ? id_b : id_a;
-      const int64_t off = (int64_t(id) * p.s_block + int64_t(kv_head) * p.s_head +
-                           int64_t((sub % sub_per_blk) << 4) * p.s_tok) * kEsz;
-      const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
-          reinterpret_cast<void*>(valid ? kv_base + off : kv_base), 0, valid ? 0x7fffffff : 0, 0x00020000);
+      const bool valid = live && k < c.my_tiles && sub < c.sub_end;
+      const int id = __builtin_amdgcn_readlane(m.ids, idx + b);
+      const int64_t addr = c.head_base + int64_t(id) * blk_bytes + (sub & sub_mask) * sub_bytes;
+      // a descriptor of size zero fetches nothing and returns zeros, whatever its base
+      const __amdgpu_buffer_rsrc_t rs =
+          __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(addr), 0, valid ? 0x7fffffff : 0, 0x00020000);
       if constexpr (KVT == PS_BF16) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) tr.k[b][s] = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off + 64 * s, 0, 0);
@@ -229,12 +237,6 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
           tr.v[4 * b + i] = __builtin_amdgcn_raw_buffer_load_b64(rs, v_lane_off, kv_bytes + i * tok_bytes, 0);
       }
     }
-  };
-  // tile k of an item of this wave (k may lie past the item's tiles: then nothing is fetched)
-  auto load_item_tile = [&](TileRegs<KVT>& tr, const ItemCtx& c, const ItemMeta& m, int k, bool live) {
-    const int idx = (2 * k) & 63;
-    load_tile(tr, c.sub0, c.sub_end, c.kv_head, __builtin_amdgcn_readlane(m.ids, idx),
-              __builtin_amdgcn_readlane(m.ids, idx + 1), k, live && k < c.my_tiles);
   };
 
   // ---- running state of the current item -------------------------------------------------------------------
@@ -458,21 +460,20 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
     // every item occupies at least one full turn of the ring, so its last NB - 1 slots always exist to
     // fetch ahead into the next item
     const int slots = max(NB, (cur.my_tiles + NB - 1) / NB * NB);
-    for (int s0 = 0; s0 < slots; s0 += NB) {
+    int s0 = 0;
+    for (; s0 + NB < slots; s0 += NB) {                 // every slot fetched ahead still belongs to this item
 #pragma unroll
       for (int u = 0; u < NB; ++u) {
-        const int ahead = s0 + u + NB - 1;              // slot whose loads go out now
-        const bool in_next = ahead >= slots;
-        const int ka = in_next ? ahead - slots : ahead;
-        const int idx = (2 * ka) & 63;
-        const int id_a = in_next ? __builtin_amdgcn_readlane(meta_nxt.ids, idx) : __builtin_amdgcn_readlane(meta.ids, idx);
-        const int id_b = in_next ? __builtin_amdgcn_readlane(meta_nxt.ids, idx + 1)
-                                 : __builtin_amdgcn_readlane(meta.ids, idx + 1);
-        const bool live = in_next ? (has_next && ka < nxt.my_tiles) : (ka < cur.my_tiles);
-        load_tile(buf[(u + NB - 1) % NB], in_next ? nxt.sub0 : cur.sub0, in_next ? nxt.sub_end : cur.sub_end,
-                  in_next ? nxt.kv_head : cur.kv_head, id_a, id_b, ka, live);
+        load_item_tile(buf[(u + NB - 1) % NB], cur, meta, s0 + u + NB - 1, true);
         if (s0 + u < cur.my_tiles) compute_tile(buf[u], cur, meta, s0 + u);
       }
+    }
+    // last turn of the ring: its first fetch is the item's last slot, the others reach into the next item
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+      if (u == 0) load_item_tile(buf[NB - 1], cur, meta, s0 + NB - 1, true);
+      else load_item_tile(buf[u - 1], nxt, meta_nxt, u - 1, has_next);
+      if (s0 + u < cur.my_tiles) compute_tile(buf[u], cur, meta, s0 + u);
     }
 
     epilogue(cur);   // ends with a barrier: sm_q and the consumed half of the header ring are free
@@ -496,7 +497,9 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
 int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max_rows, int occ, const ps_item* wg_items,
                               const int32_t* wg_indptr, int num_wg, hipStream_t st) {
   if (num_wg <= 0) return PS_OK;
-  if (g.head_dim != kD || g.q_dtype != PS_BF16 || g.block_size % 16 != 0 || max_rows > 64) return PS_ERR_UNSUPPORTED;
+  const int spb = g.block_size / 16;
+  if (g.head_dim != kD || g.q_dtype != PS_BF16 || g.block_size % 16 != 0 || (spb & (spb - 1)) != 0 || max_rows > 64)
+    return PS_ERR_UNSUPPORTED;
   if (g.kv_dtype != PS_BF16 && g.kv_dtype != PS_FP8_E4M3) return PS_ERR_UNSUPPORTED;
   const dim3 grid(num_wg), block(256);
   const int nt = max_rows <= 16 ? 1 : (max_rows <= 32 ? 2 : 4);
