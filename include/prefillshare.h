@@ -117,6 +117,14 @@ int32_t ps_layout_replan(ps_layout* layout, const ps_plan_options* options);
 int32_t ps_layout_plan(const ps_layout* layout, int32_t* num_items, const int32_t** items,
                        const int32_t** slot_base, int32_t* prefix_variant, int32_t* suffix_variant);
 
+/* Schedule of the persistent matrix-core kernel for one launchable set of items (which: 0 = prefix items,
+ * 1 = suffix items, 2 = both): the set's items regrouped by workgroup, int32[n][8] in the item format
+ * above, workgroup w owning rows [indptr[w], indptr[w+1]).  Items are packed longest-first onto
+ * num_cus x (resident workgroups per compute unit) workgroups.  *num_workgroups is 0 where the set does not
+ * run on the matrix-core kernel.  Host views, valid until the next replan/release. */
+int32_t ps_layout_schedule(const ps_layout* layout, int32_t which, int32_t* num_workgroups,
+                           const int32_t** items, const int32_t** indptr);
+
 /* Size of the int32 table blob, and its copy to device memory (at least that many bytes, 16-byte
  * aligned) on `stream`. */
 int64_t ps_layout_device_bytes(const ps_layout* layout);

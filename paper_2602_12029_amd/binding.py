@@ -22,7 +22,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libprefills
 EXPORTS = [
     "ps_pool_create", "ps_pool_destroy", "ps_pool_num_free", "ps_pool_free_list", "ps_pool_refcounts",
     "ps_kv_layout", "ps_layout_release", "ps_layout_tables", "ps_layout_replan", "ps_layout_plan",
-    "ps_layout_device_bytes", "ps_layout_upload", "ps_workspace_bytes", "ps_workspace_layout",
+    "ps_layout_schedule", "ps_layout_device_bytes", "ps_layout_upload", "ps_workspace_bytes", "ps_workspace_layout",
     "ps_prefix_attention", "ps_suffix_attention", "ps_prefix_suffix_attention", "ps_merge_states", "ps_decode_attention",
     "ps_strerror", "ps_last_hip_error",
 ]
@@ -184,6 +184,18 @@ def ps_layout_plan(layout, num_requests: int) -> dict:
            "ps_layout_plan")
     return {"items": _view(items, n.value * 8).reshape(-1, 8), "slot_base": _view(slots, num_requests + 1),
             "prefix_variant": pv.value, "suffix_variant": sv.value}
+
+
+def ps_layout_schedule(layout, which: int) -> dict:
+    """which: 0 prefix items, 1 suffix items, 2 both.  Returns {} where the set does not use the MFMA kernel."""
+    n = C.c_int32()
+    items, indptr = _I32P(), _I32P()
+    _check(_lib().ps_layout_schedule(layout, C.c_int32(which), C.byref(n), C.byref(items), C.byref(indptr)),
+           "ps_layout_schedule")
+    if n.value == 0:
+        return {}
+    ip = _view(indptr, n.value + 1)
+    return {"indptr": ip, "items": _view(items, int(ip[-1]) * 8).reshape(-1, 8)}
 
 
 def ps_layout_device_bytes(layout) -> int:

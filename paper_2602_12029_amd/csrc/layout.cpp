@@ -405,6 +405,16 @@ int32_t ps_layout_plan(const ps_layout* lay, int32_t* num_items, const int32_t**
   return PS_OK;
 }
 
+int32_t ps_layout_schedule(const ps_layout* lay, int32_t which, int32_t* num_workgroups, const int32_t** items,
+                           const int32_t** indptr) {
+  if (!lay || which < 0 || which > 2) return PS_ERR_INVALID_ARG;
+  const ps_layout::schedule& s = which == 0 ? lay->sched_prefix : (which == 1 ? lay->sched_suffix : lay->sched_all);
+  if (num_workgroups) *num_workgroups = s.num_wg;
+  if (items) *items = s.num_wg ? lay->blob.data() + s.off_items : nullptr;
+  if (indptr) *indptr = s.num_wg ? lay->blob.data() + s.off_indptr : nullptr;
+  return PS_OK;
+}
+
 int64_t ps_layout_device_bytes(const ps_layout* lay) { return lay ? int64_t(lay->blob.size()) * 4 : -1; }
 
 int64_t ps_workspace_bytes(const ps_layout* lay) {

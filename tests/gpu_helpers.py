@@ -29,8 +29,9 @@ class GpuCase:
         scales = None if self.data.scales is None else torch.from_numpy(self.data.scales).to(device)
         self.batch = DecodeBatch(self.layout, self.geo, w.num_requests, q, kv, scales)
 
-    def replan(self, prefix_chunk=0, suffix_chunk=0, prefix_variant="auto", suffix_variant="auto"):
-        self.batch.replan(B.plan_options(prefix_chunk, suffix_chunk, VARIANT[prefix_variant], VARIANT[suffix_variant]))
+    def replan(self, prefix_chunk=0, suffix_chunk=0, prefix_variant="auto", suffix_variant="auto", num_cus=0):
+        self.batch.replan(B.plan_options(prefix_chunk, suffix_chunk, VARIANT[prefix_variant], VARIANT[suffix_variant],
+                                         num_cus))
 
     def poison_workspace(self):
         self.batch.workspace.view(torch.float32).fill_(float("nan"))

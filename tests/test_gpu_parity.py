@@ -46,7 +46,9 @@ def _check(case, requests=None, label=""):
 
 def _variants(w):
     g = w.geometry
-    return ["wave", "mfma"] if (g.q_dtype == "bf16" and g.kv_dtype != "f32" and g.head_dim == 128) else ["wave"]
+    spb = g.block_size // 16
+    mfma = g.q_dtype == "bf16" and g.kv_dtype != "f32" and g.head_dim == 128 and g.block_size % 16 == 0 and spb & (spb - 1) == 0
+    return ["wave", "mfma"] if mfma else ["wave"]
 
 
 def test_tiny_fp32_default_and_split(gpu):
@@ -124,6 +126,8 @@ RAGGED = [
     ("d64_bf16", wl.Geometry(8, 2, 64, 16, "bf16", "bf16"), 2, [200], [[0, 1]], [9, 70]),
     ("d256_f32", wl.Geometry(4, 1, 256, 16, "f32", "f32"), 2, [100], [[0, 1]], [3, 40]),
     ("many_models", wl.Geometry(32, 2, 128, 16, "bf16", "bf16"), 10, [300], [list(range(10))], list(range(1, 11))),
+    ("block64_fp8", wl.Geometry(16, 2, 128, 64, "bf16", "fp8_e4m3"), 3, [450, 64], [[0, 1, 2], [1]], [70, 1, 200, 129]),
+    ("block48_bf16", wl.Geometry(8, 2, 128, 48, "bf16", "bf16"), 2, [200], [[0, 1]], [50, 7]),
 ]
 
 
@@ -138,6 +142,26 @@ def test_ragged_shapes(gpu, spec):
             case.poison_workspace()
             case.batch.decode_attention()
             _check(case, label=f"{name} {variant} chunks {pc}/{sc}")
+    case.close()
+
+
+def test_long_item_lists_per_workgroup(gpu):
+    """Few workgroups, hundreds of small items each: the persistent kernel's item pipeline, its header ring
+    refills and every kind of item boundary (waves without a tile, one-tile items, ragged tails)."""
+    geo = wl.Geometry(32, 8, 128, 16, "bf16", "bf16")
+    rng = np.random.default_rng(23)
+    w = wl.make_workload("lists", geo, 3, [1999, 700, 33, 1024, 2500, 64], [[0, 1, 2]] * 6,
+                         rng.integers(0, 200, 18).tolist(), pool_factor=1.3, seed=23)
+    case = gpu(w)
+    from paper_2602_12029_amd import binding as B
+    for pc, sc, cus in ((64, 32, 1), (32, 32, 2), (128, 64, 3)):
+        case.replan(pc, sc, "mfma", "mfma", num_cus=cus)
+        sch = B.ps_layout_schedule(case.layout, 2)
+        if cus <= 2:
+            assert np.diff(sch["indptr"]).max() > 128      # more items per workgroup than the header ring holds
+        case.poison_workspace()
+        case.batch.decode_attention()
+        _check(case, label=f"lists chunks {pc}/{sc} on {cus} CU")
     case.close()
 
 

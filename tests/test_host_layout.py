@@ -150,6 +150,47 @@ def test_replan_invariants_ragged_and_empty_segments():
     B.ps_pool_destroy(pool)
 
 
+@pytest.mark.parametrize("name", ["b8", "mixed", "fp8_70b"])
+def test_schedules_cover_every_item_once_and_balance(name):
+    w = wl.named_workload(name)
+    pool, lay, _, _ = _both(w)
+    items = B.ps_layout_plan(lay, w.num_requests)["items"]
+    sets = {0: items[items[:, 7] == 0], 1: items[items[:, 7] == 1], 2: items}
+    for which, expect in sets.items():
+        sch = B.ps_layout_schedule(lay, which)
+        assert sch, "bf16 / fp8 workloads run on the matrix-core kernel"
+        got = sch["items"]
+        key = lambda a: sorted(map(tuple, a.tolist()))
+        assert key(got) == key(expect)                                   # a permutation of the set
+        ip = sch["indptr"]
+        assert ip[0] == 0 and ip[-1] == len(got) and np.all(np.diff(ip) >= 1)
+        assert len(ip) - 1 <= 512
+        cost = (got[:, 2] - got[:, 1]) + 64
+        loads = np.array([cost[a:b].sum() for a, b in zip(ip[:-1], ip[1:])])
+        assert loads.max() - loads.min() <= cost.max()                   # longest-processing-time-first bound
+        for a, b in zip(ip[:-1], ip[1:]):
+            assert np.all(np.diff(cost[a:b]) <= 0)                       # each list longest first
+    B.ps_layout_release(pool, lay)
+    B.ps_pool_destroy(pool)
+
+
+def test_kernel_family_selection():
+    def variants(geo):
+        w = wl.make_workload("v", geo, 1, [64], [[0]], [8], seed=1)
+        pool, lay, _, _ = _both(w)
+        plan = B.ps_layout_plan(lay, 1)
+        sch = B.ps_layout_schedule(lay, 2)
+        B.ps_layout_release(pool, lay)
+        B.ps_pool_destroy(pool)
+        return plan["prefix_variant"], plan["suffix_variant"], bool(sch)
+    assert variants(wl.Geometry(8, 2, 128, 16, "bf16", "bf16")) == (B.PS_VARIANT_MFMA, B.PS_VARIANT_MFMA, True)
+    assert variants(wl.Geometry(8, 2, 128, 64, "bf16", "fp8_e4m3")) == (B.PS_VARIANT_MFMA, B.PS_VARIANT_MFMA, True)
+    # fp32 inputs, other head sizes and block sizes that are not 16 * 2^k go to the wavefront-reduction kernel
+    assert variants(wl.Geometry(8, 2, 128, 16, "f32", "f32")) == (B.PS_VARIANT_WAVE, B.PS_VARIANT_WAVE, False)
+    assert variants(wl.Geometry(8, 2, 64, 16, "bf16", "bf16")) == (B.PS_VARIANT_WAVE, B.PS_VARIANT_WAVE, False)
+    assert variants(wl.Geometry(8, 2, 128, 48, "bf16", "bf16")) == (B.PS_VARIANT_WAVE, B.PS_VARIANT_WAVE, False)
+
+
 def test_many_models_split_into_row_chunks():
     geo = wl.Geometry(32, 2, 64, 16, "f32", "f32")           # group of 16: at most 4 requests per item
     w = wl.make_workload("many", geo, 10, [64], [list(range(10))], [1] * 10, seed=4)
