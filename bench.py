@@ -30,6 +30,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="b8", help="tiny | b8 | long | mixed | fp8_70b")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--models", type=int, default=0, help="override the number of decode models M (b8, long, fp8_70b)")
     ap.add_argument("--copies", type=int, default=3, help="distinct KV pool copies rotated between steps")
     ap.add_argument("--prefix-chunk", type=int, default=0)
     ap.add_argument("--suffix-chunk", type=int, default=0)
@@ -114,7 +115,7 @@ def main():
         sys.exit("bench.py: no GPU visible")
     dev = "cuda:0"
     variant = {"auto": B.PS_VARIANT_AUTO, "wave": B.PS_VARIANT_WAVE, "mfma": B.PS_VARIANT_MFMA}
-    w = wl.named_workload(args.workload, args.seed)
+    w = wl.named_workload(args.workload, args.seed, args.models or None)
     g = w.geometry
     geo = B.geometry(g.num_q_heads, g.num_kv_heads, g.head_dim, g.block_size, g.q_dtype, g.kv_dtype)
     pool = B.ps_pool_create(w.num_blocks, w.free_order)

@@ -249,7 +249,7 @@ def make_workload(name: str, geometry: Geometry, num_models: int, prefix_len: Se
     return w
 
 
-def named_workload(name: str, seed: int = 0) -> Workload:
+def named_workload(name: str, seed: int = 0, models: Optional[int] = None) -> Workload:
     """The five benchmark configurations (synthetic stand-ins for multi-agent traffic).
 
     tiny     M=2, 1 prompt, prefix 256, suffix 8, 4 q / 2 kv heads, d 64, fp32
@@ -258,6 +258,9 @@ def named_workload(name: str, seed: int = 0) -> Workload:
     mixed    M=6, 256 prompts, prefix log-uniform [512,16384], 2-6 models per prompt,
              suffix U[1,1024], bf16
     fp8_70b  M=4, 64 prompts, prefix 8192, suffix U[1,512], 64/8 heads, bf16 Q, e4m3 KV
+
+    `models` overrides M for the configurations in which every model decodes on every prompt (b8, long,
+    fp8_70b): same prompts and prefixes, M private suffixes per prompt (for sweeps over M).
     """
     len_rng = _rng(seed, 1)
     mem_rng = _rng(seed, 2)
@@ -266,12 +269,12 @@ def named_workload(name: str, seed: int = 0) -> Workload:
         return make_workload(name, geo, 2, [256], [[0, 1]], [8, 8], 1.0, seed)
     if name == "b8":
         geo = Geometry(32, 8, 128, 16, "bf16", "bf16")
-        m, p = 4, 32
+        m, p = (models or 4), 32
         return make_workload(name, geo, m, [4096] * p, [list(range(m))] * p,
                              len_rng.integers(1, 513, size=p * m), 1.0, seed)
     if name == "long":
         geo = Geometry(32, 8, 128, 16, "bf16", "bf16")
-        m, p = 8, 8
+        m, p = (models or 8), 8
         return make_workload(name, geo, m, [32768] * p, [list(range(m))] * p,
                              len_rng.integers(256, 2049, size=p * m), 1.5, seed)
     if name == "mixed":
@@ -285,7 +288,7 @@ def named_workload(name: str, seed: int = 0) -> Workload:
         return make_workload(name, geo, m, prefix, membership, len_rng.integers(1, 1025, size=nreq), 1.0, seed)
     if name == "fp8_70b":
         geo = Geometry(64, 8, 128, 16, "bf16", "fp8_e4m3")
-        m, p = 4, 64
+        m, p = (models or 4), 64
         return make_workload(name, geo, m, [8192] * p, [list(range(m))] * p,
                              len_rng.integers(1, 513, size=p * m), 1.0, seed)
     raise KeyError(f"unknown workload {name!r}; choose from {CONFIG_NAMES}")
