@@ -252,9 +252,14 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
     }
   };
 
-  auto compute_tile = [&](TileRegs<KVT>& tr, const ItemCtx& c, const ItemMeta& meta, int k) {
+  // all_rows_tag / full_tag: std::true_type promises that every row tile is in use / that the tile has all its
+  // 32 tokens, which removes the uniform branches from the body so that the compiler can schedule the transposes
+  // and conversions under the matrix instructions; std::false_type decides at run time.
+  auto compute_tile = [&](TileRegs<KVT>& tr, const ItemCtx& c, const ItemMeta& meta, int k, auto all_rows_tag,
+                          auto full_tag) {
+    constexpr bool kAllRows = decltype(all_rows_tag)::value, kFull = decltype(full_tag)::value;
     const int tok0 = c.tok_begin + kTile * (wave + kWaves * k);  // first token of the tile
-    const bool full = tok0 + kTile <= c.tok_end;
+    const bool full = kFull || tok0 + kTile <= c.tok_end;
     float sc_k[2] = {p.scale_log2, p.scale_log2}, sc_v[2] = {1.f, 1.f};
     if constexpr (KVT == PS_FP8_E4M3) {
 #pragma unroll
@@ -284,7 +289,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
       pb[t] = bf16x8{};
-      if (t < c.nt_used) {
+      if (kAllRows || t < c.nt_used) {
         bf16x8 qb[4];
 #pragma unroll
         for (int st = 0; st < 4; ++st)
@@ -349,13 +354,15 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
       uint32_t w[4];
 #pragma unroll
       for (int i2 = 0; i2 < 4; ++i2) {
+        // low (even cc) or high (odd cc) halves of a pair of token rows: one byte permute
         const uint32_t a = vr[2 * i2][cc >> 1], b = vr[2 * i2 + 1][cc >> 1];
-        w[i2] = (cc & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
+        w[i2] = __builtin_amdgcn_perm(b, a, (cc & 1) ? 0x07060302u : 0x05040100u);
       }
       const bf16x8 vt = as_bf16x8(u32x4{w[0], w[1], w[2], w[3]});
 #pragma unroll
       for (int t = 0; t < NT; ++t)
-        if (t < c.nt_used) acc[t][cc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, pb[t], acc[t][cc], 0, 0, 0);
+        if (kAllRows || t < c.nt_used)
+          acc[t][cc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, pb[t], acc[t][cc], 0, 0, 0);
     }
   };
 
@@ -461,19 +468,25 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
     // fetch ahead into the next item
     const int slots = max(NB, (cur.my_tiles + NB - 1) / NB * NB);
     int s0 = 0;
-    for (; s0 + NB < slots; s0 += NB) {                 // every slot fetched ahead still belongs to this item
+    // Turns before the last: every slot fetched ahead still belongs to this item, and every tile computed is a
+    // complete one (the item's ragged tile, if any, is its last and falls into the last turn).
+    auto full_turns = [&](auto all_rows_tag) {
+      for (; s0 + NB < slots; s0 += NB) {
 #pragma unroll
-      for (int u = 0; u < NB; ++u) {
-        load_item_tile(buf[(u + NB - 1) % NB], cur, meta, s0 + u + NB - 1, true);
-        if (s0 + u < cur.my_tiles) compute_tile(buf[u], cur, meta, s0 + u);
+        for (int u = 0; u < NB; ++u) {
+          load_item_tile(buf[(u + NB - 1) % NB], cur, meta, s0 + u + NB - 1, true);
+          compute_tile(buf[u], cur, meta, s0 + u, all_rows_tag, std::true_type{});
+        }
       }
-    }
+    };
+    if (NT == 1) full_turns(std::true_type{});
+    else full_turns(std::false_type{});
     // last turn of the ring: its first fetch is the item's last slot, the others reach into the next item
 #pragma unroll
     for (int u = 0; u < NB; ++u) {
       if (u == 0) load_item_tile(buf[NB - 1], cur, meta, s0 + NB - 1, true);
       else load_item_tile(buf[u - 1], nxt, meta_nxt, u - 1, has_next);
-      if (s0 + u < cur.my_tiles) compute_tile(buf[u], cur, meta, s0 + u);
+      if (s0 + u < cur.my_tiles) compute_tile(buf[u], cur, meta, s0 + u, std::false_type{}, std::false_type{});
     }
 
     epilogue(cur);   // ends with a barrier: sm_q and the consumed half of the header ring are free
