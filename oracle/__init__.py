@@ -9,4 +9,4 @@ loops, closed forms, placement/permutation invariance, split-and-merge
 exactness, a library SDPA for the single-model case, the e4m3 format table, and
 the Eq. 9 block-count / refcount invariants.  No function here is unpinned.
 """
-from . import attention, fp8, layout  # noqa: F401
+from . import attention, fp8, kv_update, layout  # noqa: F401

@@ -134,3 +134,46 @@ def release_layout(pool: BlockPool, lay: Layout) -> None:
     for blk in np.nonzero((drop > 0) & (pool.refcount == 0))[0]:
         pool.free.append(int(blk))
     lay.released = True
+
+
+def append_step(pool: BlockPool, lay: Layout, active=None) -> np.ndarray:
+    """One decode step of cache growth (Method, Eq. 6: every step returns the new entries dC_t that are
+    appended to the module's own cache; Background, Eq. 4: the concatenation).
+
+    Each active request gains one token at logical position Ls_r of its private segment.  Requests are
+    served in ascending index; a request whose Ls_r is a multiple of the block size (no private block yet,
+    or the last one is full) first takes one block from the head of the free list, refcount 1, appended to
+    its private list.  Shared prefix blocks are never written (they stay read-only, Eq. 9).  A step that
+    does not fit leaves pool and layout untouched.
+
+    Returns dest[R] int64: global slot index block * B + slot where the new token of request r is stored,
+    -1 for inactive requests.
+    """
+    if lay.released:
+        raise LayoutError("layout already released")
+    num_r = len(lay.req_prompt)
+    act = np.ones(num_r, bool) if active is None else np.asarray(active).astype(bool)
+    if len(act) != num_r:
+        raise LayoutError("active mask has the wrong length")
+    bsz = lay.block_size
+    need = [r for r in range(num_r) if act[r] and int(lay.suffix_len[r]) % bsz == 0]
+    if len(need) > len(pool.free):
+        raise OutOfBlocks(f"need {len(need)} blocks, {len(pool.free)} free")
+    lists = [list(lay.suffix_blk[lay.suffix_blk_indptr[r]:lay.suffix_blk_indptr[r + 1]]) for r in range(num_r)]
+    dest = np.full(num_r, -1, np.int64)
+    for r in range(num_r):
+        if not act[r]:
+            continue
+        pos = int(lay.suffix_len[r])
+        if pos % bsz == 0:
+            blk = pool.free.popleft()
+            pool.refcount[blk] += 1
+            lists[r].append(blk)
+        dest[r] = int(lists[r][pos // bsz]) * bsz + pos % bsz
+        lay.suffix_len[r] = pos + 1
+    indptr = np.zeros(num_r + 1, np.int32)
+    for r in range(num_r):
+        indptr[r + 1] = indptr[r] + len(lists[r])
+    lay.suffix_blk_indptr = indptr
+    lay.suffix_blk = np.asarray([b for l in lists for b in l], np.int32)
+    return dest

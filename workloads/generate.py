@@ -10,7 +10,9 @@ Nothing here computes attention or decides where blocks live: lengths, sharing
 structure, the pool's free order and the *stored bits* of Q/K/V are drawn from
 PCG64 streams keyed by (seed, tag, index), so every item can be regenerated on
 its own and in any order.  Draw tags: 1 lengths, 2 membership, 3 free order,
-4 Q, 5 prefix K/V (index = prompt), 6 suffix K/V (index = request).
+4 Q, 5 prefix K/V (index = prompt), 6 suffix K/V (index = request), 7 / 8 unquantised
+prefix / suffix K/V as a worker hands them over, 9 the K/V of the token each request
+appends in a decode step (index = step).
 
 Storage formats: 'f32' -> float32, 'bf16' -> uint16 bit patterns (fp32 draws
 rounded to nearest-even), 'fp8_e4m3' -> uint8 OCP e4m3fn codes plus one fp32
@@ -148,6 +150,30 @@ class Workload:
 
     def suffix_kv(self, request: int) -> Segment:
         return self._segment(6, request, int(self.suffix_len[request]))
+
+    # ---- unquantised sources (what a prefill or decode worker hands over) ----
+    def _source(self, tag: int, index: int, tokens: int):
+        """K, V [tokens, Hkv, d]: N(0,1) values times a per-token gain drawn log-uniformly from [1/4, 4]
+        (so that tokens differ in magnitude), as bf16 bit patterns -- float32 for float32 pools."""
+        g = self.geometry
+        rng = _rng(self.seed, tag, index)
+        out = []
+        for _ in range(2):
+            x = rng.standard_normal((int(tokens), g.num_kv_heads, g.head_dim), dtype=np.float32)
+            gain = np.exp2(rng.uniform(-2.0, 2.0, size=(int(tokens), 1, 1))).astype(np.float32)
+            x = x * gain
+            out.append(x if g.kv_dtype == "f32" else bf16_bits_from_f32(x))
+        return out[0], out[1]
+
+    def prefix_source(self, prompt: int):
+        return self._source(7, prompt, int(self.prefix_len[prompt]))
+
+    def suffix_source(self, request: int):
+        return self._source(8, request, int(self.suffix_len[request]))
+
+    def step_tokens(self, step: int):
+        """K, V [R, Hkv, d] of the one token every request appends in decode step `step`."""
+        return self._source(9, step, self.num_requests)
 
 
 def _quantise_tiles(x: np.ndarray, block: int):
