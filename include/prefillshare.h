@@ -105,6 +105,10 @@ int32_t ps_layout_tables(const ps_layout* layout,
                          const int32_t** group_indptr, const int32_t** group_req,
                          const int32_t** suffix_blk_indptr, const int32_t** suffix_blk);
 
+/* Host views of the segment lengths in tokens (prefix_len[P], suffix_len[R]); suffix_len changes with
+ * ps_layout_append.  Valid until release. */
+int32_t ps_layout_lengths(const ps_layout* layout, const int32_t** prefix_len, const int32_t** suffix_len);
+
 /* ---- split plan -------------------------------------------------------------------------------
  * Re-derives the plan with explicit options (NULL = defaults).  Invalidates earlier uploads of this
  * layout's table blob and the sizes reported below. */
@@ -160,6 +164,47 @@ int32_t ps_merge_states(const ps_layout* layout, const void* dev_tables, const v
 int32_t ps_decode_attention(const ps_layout* layout, const void* dev_tables, const void* q,
                             const void* kv_pool, const float* kv_scales, void* workspace,
                             void* out, float* out_lse, void* stream);
+
+/* ---- cache growth -------------------------------------------------------------------------------------
+ * A decode step returns the step's new cache entries, which are appended to the decode module's own cache
+ * (Method Eq. 6; Background Eq. 2 and Eq. 4); the shared prefix cache comes from a prefill worker and is
+ * handed to the decode workers (Method Eq. 5; System Design, execution pipeline steps 1 and 3).
+ *
+ * ps_layout_append (host): one step of table growth.  active = int32[R], non-zero where the request appends a
+ * token, or NULL = every request.  Requests in ascending index; a request whose private length is a multiple
+ * of the block size (no private block yet, or its last one is full) first takes the block at the head of the
+ * free list (refcount 1); then its private length grows by one.  Shared prefix blocks are never written.
+ * Re-derives the split plan with the options last used, so earlier uploads of the table blob and the sizes
+ * reported by ps_layout_device_bytes / ps_workspace_bytes are invalid afterwards.  *dest (may be NULL)
+ * receives a host view int32[R], valid until the next append/release: block * block_size + slot where the
+ * request's new token belongs, -1 for inactive requests.  PS_ERR_OOM: too few free blocks, nothing changed.
+ * PS_ERR_INVALID_ARG also for pools with more than 2^31 slots. */
+int32_t ps_layout_append(ps_pool* pool, ps_layout* layout, const int32_t* active, const int32_t** dest);
+
+/* ps_kv_append (device, asynchronous): stores the tokens reserved by the last ps_layout_append.  dev_tables
+ * must be an upload made after that call.  new_k, new_v: device [R][Hkv][d] contiguous, bf16 for bf16 and
+ * e4m3 pools, float32 for float32 pools; rows of inactive requests are ignored.  bf16 / float32 pools
+ * store the bits.  e4m3 pools, per (block, KV head) and separately for K and V, with a = max |x| of the new
+ * token in float32: the tile's scale becomes max(old scale, a / 448) (slot 0 of a fresh block: a / 448, or 1
+ * if a = 0); if it grew, the tokens already in the tile are re-encoded from their stored values,
+ * (decode(code) * old) / new in float32; the new token is stored as the round-to-nearest-even e4m3fn code of
+ * x / scale.  kv_scales is read and written. */
+int32_t ps_kv_append(const ps_layout* layout, const void* dev_tables, const void* new_k, const void* new_v,
+                     void* kv_pool, float* kv_scales, void* stream);
+
+/* ps_kv_ingest (device, asynchronous): stores whole segments handed over as contiguous tensors.  which: 0 =
+ * every prompt's shared prefix, 1 = every request's private suffix.  src_k, src_v: device, token-major
+ * [T][Hkv][d] with T = the sum of the segment lengths of that kind, segments back to back in index order;
+ * element (t, h, c) at t * src_stride_tok + h * src_stride_head + c (strides in elements, multiples of 16
+ * bytes, base pointers 16-byte aligned); bf16 for bf16 and e4m3 pools, float32 for float32 pools.  Token j of
+ * a segment goes to slot j % block_size of the segment's block j / block_size; slots past the segment's
+ * length are not written.  e4m3 pools: per (block, KV head), separately for K and V, a = max |x| over the
+ * tile's valid tokens, scale = a / 448 in float32 (1 if a = 0), code = round-to-nearest-even e4m3fn of
+ * x / scale (float32 division); kv_scales is written.  PS_ERR_UNSUPPORTED: head_dim not a multiple of 8
+ * (4 for float32), or an e4m3 tile of more than 16384 elements. */
+int32_t ps_kv_ingest(const ps_layout* layout, const void* dev_tables, int32_t which, const void* src_k,
+                     const void* src_v, int64_t src_stride_tok, int64_t src_stride_head, void* kv_pool,
+                     float* kv_scales, void* stream);
 
 const char* ps_strerror(int32_t status);
 int32_t ps_last_hip_error(void);

@@ -24,6 +24,7 @@ EXPORTS = [
     "ps_kv_layout", "ps_layout_release", "ps_layout_tables", "ps_layout_replan", "ps_layout_plan",
     "ps_layout_schedule", "ps_layout_device_bytes", "ps_layout_upload", "ps_workspace_bytes", "ps_workspace_layout",
     "ps_prefix_attention", "ps_suffix_attention", "ps_prefix_suffix_attention", "ps_merge_states", "ps_decode_attention",
+    "ps_layout_lengths", "ps_layout_append", "ps_kv_append", "ps_kv_ingest",
     "ps_strerror", "ps_last_hip_error",
 ]
 
@@ -171,6 +172,25 @@ def ps_layout_tables(layout, num_prompts: int, num_requests: int) -> dict:
             "suffix_blk_indptr": sbi, "suffix_blk": _view(ptrs[5], int(sbi[-1]))}
 
 
+def ps_layout_lengths(layout, num_prompts: int, num_requests: int) -> dict:
+    pl, sl = _I32P(), _I32P()
+    _check(_lib().ps_layout_lengths(layout, C.byref(pl), C.byref(sl)), "ps_layout_lengths")
+    return {"prefix_len": _view(pl, num_prompts), "suffix_len": _view(sl, num_requests)}
+
+
+def ps_layout_append(pool, layout, num_requests: int, active=None) -> np.ndarray:
+    """One decode step of table growth; returns dest[R] (block * B + slot of each new token, -1 = inactive)."""
+    if active is None:
+        ap = None
+    else:
+        arr, ap = _i32(active)
+        if arr.size != num_requests:
+            raise ValueError("active mask has the wrong length")
+    dest = _I32P()
+    _check(_lib().ps_layout_append(pool, layout, ap, C.byref(dest)), "ps_layout_append")
+    return _view(dest, num_requests)
+
+
 def ps_layout_replan(layout, options: ps_plan_options | None = None):
     st = _lib().ps_layout_replan(layout, C.byref(options) if options is not None else None)
     _check(st, "ps_layout_replan")
@@ -244,6 +264,17 @@ def ps_merge_states(layout, dev_tables, workspace, out, out_lse=0, stream=0):
 def ps_decode_attention(layout, dev_tables, q, kv_pool, kv_scales, workspace, out, out_lse=0, stream=0):
     _check(_lib().ps_decode_attention(layout, _p(dev_tables), _p(q), _p(kv_pool), _p(kv_scales), _p(workspace),
                                       _p(out), _p(out_lse), _p(stream)), "ps_decode_attention")
+
+
+def ps_kv_append(layout, dev_tables, new_k, new_v, kv_pool, kv_scales, stream=0):
+    _check(_lib().ps_kv_append(layout, _p(dev_tables), _p(new_k), _p(new_v), _p(kv_pool), _p(kv_scales), _p(stream)),
+           "ps_kv_append")
+
+
+def ps_kv_ingest(layout, dev_tables, which: int, src_k, src_v, src_stride_tok: int, src_stride_head: int, kv_pool,
+                 kv_scales, stream=0):
+    _check(_lib().ps_kv_ingest(layout, _p(dev_tables), C.c_int32(which), _p(src_k), _p(src_v), C.c_int64(src_stride_tok),
+                               C.c_int64(src_stride_head), _p(kv_pool), _p(kv_scales), _p(stream)), "ps_kv_ingest")
 
 
 def ps_strerror(status: int) -> str:

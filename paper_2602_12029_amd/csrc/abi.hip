@@ -122,6 +122,34 @@ int32_t ps_prefix_suffix_attention(const ps_layout* lay, const void* dev_tables,
   return launch_set(lay, p, dev_tables, WorkSet::kSuffix, st);
 }
 
+int32_t ps_kv_ingest(const ps_layout* lay, const void* dev_tables, int32_t which, const void* src_k, const void* src_v,
+                     int64_t src_stride_tok, int64_t src_stride_head, void* kv_pool, float* kv_scales, void* stream) {
+  if (!lay || !dev_tables || which < 0 || which > 1) return PS_ERR_INVALID_ARG;
+  const ps_geometry& g = lay->geo;
+  const size_t entries = which ? lay->suffix_blk.size() : lay->prefix_blk.size();
+  if (entries == 0) return PS_OK;
+  if (!src_k || !src_v || !kv_pool || (g.kv_dtype == PS_FP8_E4M3 && !kv_scales)) return PS_ERR_INVALID_ARG;
+  const int64_t esz = g.kv_dtype == PS_F32 ? 4 : 2;   // source element: float32 for float32 pools, else bf16
+  if (src_stride_head < g.head_dim || src_stride_tok < g.head_dim || (src_stride_head * esz) % 16 ||
+      (src_stride_tok * esz) % 16 || reinterpret_cast<uintptr_t>(src_k) % 16 || reinterpret_cast<uintptr_t>(src_v) % 16)
+    return PS_ERR_SHAPE;
+  if (int32_t rc = psdev::launch_kv_ingest(lay, dev_tables, which, src_k, src_v, src_stride_tok, src_stride_head,
+                                           kv_pool, kv_scales, static_cast<hipStream_t>(stream)))
+    return rc;
+  return check_hip(hipGetLastError());
+}
+
+int32_t ps_kv_append(const ps_layout* lay, const void* dev_tables, const void* new_k, const void* new_v, void* kv_pool,
+                     float* kv_scales, void* stream) {
+  if (!lay || !dev_tables) return PS_ERR_INVALID_ARG;
+  if (lay->num_requests == 0) return PS_OK;
+  if (!new_k || !new_v || !kv_pool || (lay->geo.kv_dtype == PS_FP8_E4M3 && !kv_scales)) return PS_ERR_INVALID_ARG;
+  if (int32_t rc = psdev::launch_kv_append(lay, dev_tables, new_k, new_v, kv_pool, kv_scales,
+                                           static_cast<hipStream_t>(stream)))
+    return rc;
+  return check_hip(hipGetLastError());
+}
+
 int32_t ps_decode_attention(const ps_layout* lay, const void* dev_tables, const void* q, const void* kv_pool,
                             const float* kv_scales, void* workspace, void* out, float* out_lse, void* stream) {
   if (lay && lay->num_requests && !out) return PS_ERR_INVALID_ARG;

@@ -1,0 +1,266 @@
+// Writing KV into the paged pool: whole-segment ingest (a prefill worker's shared prefix cache, or a private
+// segment produced elsewhere, handed over as contiguous [token][kv_head][d] tensors) and the per-step append
+// of one new token per request.  bf16 / float32 pools store the source bits; e4m3 pools quantise per
+// (block, kv head) tile with one float32 scale for K and one for V.
+//
+// Quantiser (every decision in float32 so that results are reproducible bit for bit): a = max |x| over the
+// tile's valid tokens, scale = a / 448 (1 if a = 0), code = round-to-nearest-even e4m3fn of x / scale.  An
+// append whose token raises the tile's scale re-encodes the tokens already stored from their stored values:
+// y = (decode(code) * scale_old) / scale_new.
+//
+// Both kernels are plain streaming code: one wavefront per (block, kv head, K|V) tile (ingest) or per
+// (request, kv head, K|V) row (append); HBM-bound, no matrix work.
+#include "device_common.h"
+#include "launch.h"
+
+namespace psdev {
+
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+// e4m3fn code -> float32 (exact)
+__device__ __forceinline__ float e4m3_to_f32(uint32_t code) {
+  const uint32_t e = (code >> 3) & 0xf, m = code & 7;
+  const float mag = e ? __uint_as_float(((e + 120u) << 23) | (m << 20)) : float(m) * 0x1p-9f;
+  return (code & 0x80) ? -mag : mag;
+}
+
+// two float32 -> two e4m3fn codes in the low 16 bits (v_cvt_pk_fp8_f32: nearest even).  Inputs never reach the
+// midpoint above 448 here (|x| <= tile maximum), so saturation behaviour is not relied upon.
+__device__ __forceinline__ uint32_t f32x2_to_e4m3(float a, float b) {
+  return uint32_t(__builtin_amdgcn_cvt_pk_fp8_f32(a, b, 0, false)) & 0xffffu;
+}
+
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) x = fmaxf(x, lane_xor(x, m));
+  return x;
+}
+
+struct KvWriteParams {
+  const int32_t* blk;        // concatenated block array
+  const int32_t* seg_blk0;   // per segment: first entry in blk
+  const int32_t* seg_len;    // tokens
+  const int32_t* seg_tok0;   // first token in the ragged source of its kind
+  const int32_t* blk_seg;    // owning segment of every blk entry
+  const int32_t* dest;       // [R] block * B + slot of the token being appended, -1 = none
+  void* kv;
+  float* scales;
+  int32_t num_kv_heads, head_dim, block_size;
+  int64_t s_block, s_head, s_kv, s_tok;  // pool strides, elements
+};
+
+// ---- ingest, storage formats that keep the source bits (T = uint16_t for bf16, float) --------------------
+template <typename T>
+__global__ __launch_bounds__(256) void ingest_copy_kernel(KvWriteParams p, const T* __restrict__ src_k,
+                                                          const T* __restrict__ src_v, int64_t src_s_tok,
+                                                          int64_t src_s_head, int entry0, int num_entries) {
+  constexpr int kVec = 16 / int(sizeof(T));
+  const int lane = threadIdx.x & 63;
+  const int64_t tile = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);   // (entry, head, which)
+  if (tile >= int64_t(num_entries) * p.num_kv_heads * 2) return;
+  const int which = int(tile & 1);
+  const int h = int((tile >> 1) % p.num_kv_heads);
+  const int e = entry0 + int((tile >> 1) / p.num_kv_heads);
+  const int s = p.blk_seg[e];
+  const int first_tok = (e - p.seg_blk0[s]) * p.block_size;
+  const int n_valid = min(p.block_size, p.seg_len[s] - first_tok);
+  const T* src = (which ? src_v : src_k) + (int64_t(p.seg_tok0[s]) + first_tok) * src_s_tok + int64_t(h) * src_s_head;
+  T* dst = static_cast<T*>(p.kv) + int64_t(p.blk[e]) * p.s_block + int64_t(h) * p.s_head + int64_t(which) * p.s_kv;
+  const int cpt = p.head_dim / kVec;   // 16-byte chunks per token
+  for (int c = lane; c < n_valid * cpt; c += 64) {
+    const int t = c / cpt, col = (c % cpt) * kVec;
+    *reinterpret_cast<u32x4*>(dst + int64_t(t) * p.s_tok + col) =
+        *reinterpret_cast<const u32x4*>(src + int64_t(t) * src_s_tok + col);
+  }
+}
+
+// ---- ingest, bf16 source -> e4m3 pool.  CH: 16-byte source chunks a lane keeps in registers ---------------
+template <int CH>
+__global__ __launch_bounds__(256) void ingest_e4m3_kernel(KvWriteParams p, const uint16_t* __restrict__ src_k,
+                                                          const uint16_t* __restrict__ src_v, int64_t src_s_tok,
+                                                          int64_t src_s_head, int entry0, int num_entries) {
+  const int lane = threadIdx.x & 63;
+  const int64_t tile = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  if (tile >= int64_t(num_entries) * p.num_kv_heads * 2) return;
+  const int which = int(tile & 1);
+  const int h = int((tile >> 1) % p.num_kv_heads);
+  const int e = entry0 + int((tile >> 1) / p.num_kv_heads);
+  const int s = p.blk_seg[e];
+  const int first_tok = (e - p.seg_blk0[s]) * p.block_size;
+  const int n_valid = min(p.block_size, p.seg_len[s] - first_tok);
+  const uint16_t* src = (which ? src_v : src_k) + (int64_t(p.seg_tok0[s]) + first_tok) * src_s_tok + int64_t(h) * src_s_head;
+  const int id = p.blk[e];
+  uint8_t* dst = static_cast<uint8_t*>(p.kv) + int64_t(id) * p.s_block + int64_t(h) * p.s_head + int64_t(which) * p.s_kv;
+  const int cpt = p.head_dim / 8;
+  const int total = n_valid * cpt;
+  u32x4 raw[CH];
+  float amax = 0.f;
+#pragma unroll
+  for (int i = 0; i < CH; ++i) {
+    const int c = lane + 64 * i;
+    raw[i] = u32x4{0, 0, 0, 0};
+    if (c < total) raw[i] = *reinterpret_cast<const u32x4*>(src + int64_t(c / cpt) * src_s_tok + (c % cpt) * 8);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      amax = fmaxf(amax, fabsf(bf16_bits_to_f32(raw[i][j] & 0xffffu)));
+      amax = fmaxf(amax, fabsf(bf16_bits_to_f32(raw[i][j] >> 16)));
+    }
+  }
+  amax = wave_max(amax);
+  const float scale = amax > 0.f ? amax / 448.f : 1.f;
+  if (lane == 0) p.scales[(int64_t(id) * p.num_kv_heads + h) * 2 + which] = scale;
+#pragma unroll
+  for (int i = 0; i < CH; ++i) {
+    const int c = lane + 64 * i;
+    if (c < total) {
+      u32x2 out;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const uint32_t w0 = raw[i][2 * j], w1 = raw[i][2 * j + 1];
+        const uint32_t lo = f32x2_to_e4m3(bf16_bits_to_f32(w0 & 0xffffu) / scale, bf16_bits_to_f32(w0 >> 16) / scale);
+        const uint32_t hi = f32x2_to_e4m3(bf16_bits_to_f32(w1 & 0xffffu) / scale, bf16_bits_to_f32(w1 >> 16) / scale);
+        out[j] = lo | (hi << 16);
+      }
+      *reinterpret_cast<u32x2*>(dst + int64_t(c / cpt) * p.s_tok + (c % cpt) * 8) = out;
+    }
+  }
+}
+
+// ---- append: one wavefront per (request, kv head, K|V) ----------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void append_copy_kernel(KvWriteParams p, const T* __restrict__ new_k,
+                                                          const T* __restrict__ new_v, int num_requests) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  if (row >= int64_t(num_requests) * p.num_kv_heads * 2) return;
+  const int which = int(row & 1);
+  const int h = int((row >> 1) % p.num_kv_heads);
+  const int r = int((row >> 1) / p.num_kv_heads);
+  const int dest = p.dest[r];
+  if (dest < 0) return;
+  const int id = dest / p.block_size, slot = dest % p.block_size;
+  const T* src = (which ? new_v : new_k) + (int64_t(r) * p.num_kv_heads + h) * p.head_dim;
+  T* dst = static_cast<T*>(p.kv) + int64_t(id) * p.s_block + int64_t(h) * p.s_head + int64_t(which) * p.s_kv +
+           int64_t(slot) * p.s_tok;
+  for (int c = lane; c < p.head_dim; c += 64) dst[c] = src[c];
+}
+
+__global__ __launch_bounds__(256) void append_e4m3_kernel(KvWriteParams p, const uint16_t* __restrict__ new_k,
+                                                          const uint16_t* __restrict__ new_v, int num_requests) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  if (row >= int64_t(num_requests) * p.num_kv_heads * 2) return;
+  const int which = int(row & 1);
+  const int h = int((row >> 1) % p.num_kv_heads);
+  const int r = int((row >> 1) / p.num_kv_heads);
+  const int dest = p.dest[r];
+  if (dest < 0) return;
+  const int id = dest / p.block_size, slot = dest % p.block_size;
+  const uint16_t* src = (which ? new_v : new_k) + (int64_t(r) * p.num_kv_heads + h) * p.head_dim;
+  uint8_t* tile = static_cast<uint8_t*>(p.kv) + int64_t(id) * p.s_block + int64_t(h) * p.s_head + int64_t(which) * p.s_kv;
+  float* scale_ptr = p.scales + (int64_t(id) * p.num_kv_heads + h) * 2 + which;
+  float amax = 0.f;
+  for (int c = lane; c < p.head_dim; c += 64) amax = fmaxf(amax, fabsf(bf16_bits_to_f32(src[c])));
+  amax = wave_max(amax);
+  const float cand = amax / 448.f;
+  float scale;
+  if (slot == 0) {
+    scale = amax > 0.f ? cand : 1.f;
+  } else {
+    const float old = *scale_ptr;
+    scale = fmaxf(old, cand);
+    if (scale != old) {   // the tile's scale grew: re-encode what is stored, from the stored values
+      for (int c = lane; c < slot * p.head_dim; c += 64) {
+        uint8_t* at = tile + int64_t(c / p.head_dim) * p.s_tok + c % p.head_dim;
+        *at = uint8_t(f32x2_to_e4m3((e4m3_to_f32(*at) * old) / scale, 0.f) & 0xffu);
+      }
+    }
+  }
+  if (lane == 0) *scale_ptr = scale;
+  uint8_t* dst = tile + int64_t(slot) * p.s_tok;
+  for (int c = lane; c < p.head_dim; c += 64) dst[c] = uint8_t(f32x2_to_e4m3(bf16_bits_to_f32(src[c]) / scale, 0.f) & 0xffu);
+}
+
+KvWriteParams make_write_params(const ps_layout* lay, const void* dev_tables, void* kv, float* scales) {
+  const int32_t* t = static_cast<const int32_t*>(dev_tables);
+  const ps_geometry& g = lay->geo;
+  KvWriteParams p{};
+  p.blk = t + lay->off_blk;
+  p.seg_blk0 = t + lay->off_seg_blk0;
+  p.seg_len = t + lay->off_seg_len;
+  p.seg_tok0 = t + lay->off_seg_tok0;
+  p.blk_seg = t + lay->off_blk_seg;
+  p.dest = t + lay->off_dest;
+  p.kv = kv;
+  p.scales = scales;
+  p.num_kv_heads = g.num_kv_heads;
+  p.head_dim = g.head_dim;
+  p.block_size = g.block_size;
+  p.s_block = g.kv_stride_block;
+  p.s_head = g.kv_stride_head;
+  p.s_kv = g.kv_stride_kv;
+  p.s_tok = g.kv_stride_tok;
+  return p;
+}
+
+}  // namespace
+
+int32_t launch_kv_ingest(const ps_layout* lay, const void* dev_tables, int which, const void* src_k, const void* src_v,
+                         int64_t src_s_tok, int64_t src_s_head, void* kv, float* scales, hipStream_t st) {
+  const ps_geometry& g = lay->geo;
+  const int n_prefix = int(lay->prefix_blk.size());
+  const int entry0 = which ? n_prefix : 0;
+  const int num_entries = which ? int(lay->suffix_blk.size()) : n_prefix;
+  if (num_entries == 0) return PS_OK;
+  const int64_t tiles = int64_t(num_entries) * g.num_kv_heads * 2;
+  const int64_t grid64 = (tiles + 3) / 4;
+  if (grid64 > INT32_MAX) return PS_ERR_INVALID_ARG;
+  const dim3 grid{unsigned(grid64)}, block{256};
+  const KvWriteParams p = make_write_params(lay, dev_tables, kv, scales);
+  if (g.kv_dtype == PS_F32) {
+    if (g.head_dim % 4) return PS_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(ingest_copy_kernel<float>, grid, block, 0, st, p, static_cast<const float*>(src_k),
+                       static_cast<const float*>(src_v), src_s_tok, src_s_head, entry0, num_entries);
+  } else if (g.kv_dtype == PS_BF16) {
+    if (g.head_dim % 8) return PS_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(ingest_copy_kernel<uint16_t>, grid, block, 0, st, p, static_cast<const uint16_t*>(src_k),
+                       static_cast<const uint16_t*>(src_v), src_s_tok, src_s_head, entry0, num_entries);
+  } else {
+    if (g.head_dim % 8) return PS_ERR_UNSUPPORTED;
+    const int64_t chunks = (int64_t(g.block_size) * (g.head_dim / 8) + 63) / 64;   // per lane, whole tile in registers
+#define PS_INGEST(CH)                                                                                            \
+  hipLaunchKernelGGL(ingest_e4m3_kernel<CH>, grid, block, 0, st, p, static_cast<const uint16_t*>(src_k),          \
+                     static_cast<const uint16_t*>(src_v), src_s_tok, src_s_head, entry0, num_entries)
+    if (chunks <= 4) PS_INGEST(4);
+    else if (chunks <= 8) PS_INGEST(8);
+    else if (chunks <= 16) PS_INGEST(16);
+    else if (chunks <= 32) PS_INGEST(32);
+    else return PS_ERR_UNSUPPORTED;
+#undef PS_INGEST
+  }
+  return PS_OK;
+}
+
+int32_t launch_kv_append(const ps_layout* lay, const void* dev_tables, const void* new_k, const void* new_v, void* kv,
+                         float* scales, hipStream_t st) {
+  const ps_geometry& g = lay->geo;
+  if (lay->num_requests == 0) return PS_OK;
+  const int64_t rows = int64_t(lay->num_requests) * g.num_kv_heads * 2;
+  const dim3 grid{unsigned((rows + 3) / 4)}, block{256};
+  const KvWriteParams p = make_write_params(lay, dev_tables, kv, scales);
+  if (g.kv_dtype == PS_F32)
+    hipLaunchKernelGGL(append_copy_kernel<float>, grid, block, 0, st, p, static_cast<const float*>(new_k),
+                       static_cast<const float*>(new_v), lay->num_requests);
+  else if (g.kv_dtype == PS_BF16)
+    hipLaunchKernelGGL(append_copy_kernel<uint16_t>, grid, block, 0, st, p, static_cast<const uint16_t*>(new_k),
+                       static_cast<const uint16_t*>(new_v), lay->num_requests);
+  else
+    hipLaunchKernelGGL(append_e4m3_kernel, grid, block, 0, st, p, static_cast<const uint16_t*>(new_k),
+                       static_cast<const uint16_t*>(new_v), lay->num_requests);
+  return PS_OK;
+}
+
+}  // namespace psdev

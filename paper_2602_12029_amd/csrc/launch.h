@@ -11,6 +11,12 @@ int32_t launch_wave_attention(const AttnParams& p, const ps_geometry& g, int ite
 // Persistent launch: workgroup w walks wg_items[wg_indptr[w] .. wg_indptr[w+1]).
 int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max_rows, int occ, const ps_item* wg_items,
                               const int32_t* wg_indptr, int num_wg, hipStream_t st);
+// Cache writes: whole segments of one kind (0 = shared prefixes, 1 = private suffixes) from ragged contiguous
+// sources, and the one token per request reserved by the last ps_layout_append.
+int32_t launch_kv_ingest(const ps_layout* lay, const void* dev_tables, int which, const void* src_k, const void* src_v,
+                         int64_t src_s_tok, int64_t src_s_head, void* kv, float* scales, hipStream_t st);
+int32_t launch_kv_append(const ps_layout* lay, const void* dev_tables, const void* new_k, const void* new_v, void* kv,
+                         float* scales, hipStream_t st);
 int32_t launch_merge(const int32_t* slot_base, const float* ws_o, const float* ws_lse, void* out, float* out_lse,
                      int num_requests, const ps_geometry& g, hipStream_t st);
 

@@ -190,6 +190,7 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   if (pre_mfma && suf_mfma) pk_all = pack(0, n_items);
 
   // device blob: [block ids: prefix ++ suffix][request list: group_req ++ identity][items][slot_base][schedules]
+  // [segment directory][destinations of the last append]
   auto pad4 = [](int64_t n) { return (n + 3) / 4 * 4; };
   lay->off_blk = 0;
   lay->off_req = pad4(lay->off_blk + int64_t(lay->prefix_blk.size() + lay->suffix_blk.size()));
@@ -210,8 +211,39 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   place(lay->sched_prefix, pk_prefix);
   place(lay->sched_suffix, pk_suffix);
   place(lay->sched_all, pk_all);
+  // segment directory (cache-writing kernels)
+  const int64_t num_seg = int64_t(P) + R, num_blk_entries = int64_t(lay->prefix_blk.size() + lay->suffix_blk.size());
+  lay->off_seg_blk0 = words;
+  lay->off_seg_len = pad4(lay->off_seg_blk0 + num_seg);
+  lay->off_seg_tok0 = pad4(lay->off_seg_len + num_seg);
+  lay->off_blk_seg = pad4(lay->off_seg_tok0 + num_seg);
+  lay->off_dest = pad4(lay->off_blk_seg + num_blk_entries);
+  words = pad4(lay->off_dest + R);
   lay->blob.assign(size_t(std::max<int64_t>(words, 4)), 0);
   int32_t* b = lay->blob.data();
+  {
+    int64_t tok = 0;
+    for (int32_t p = 0; p < P; ++p) {
+      b[lay->off_seg_blk0 + p] = lay->prefix_blk_indptr[size_t(p)];
+      b[lay->off_seg_len + p] = lay->prefix_len[size_t(p)];
+      if (tok > INT32_MAX) return PS_ERR_INVALID_ARG;
+      b[lay->off_seg_tok0 + p] = int32_t(tok);
+      tok += lay->prefix_len[size_t(p)];
+      for (int32_t i = lay->prefix_blk_indptr[size_t(p)]; i < lay->prefix_blk_indptr[size_t(p) + 1]; ++i) b[lay->off_blk_seg + i] = p;
+    }
+    tok = 0;
+    for (int32_t r = 0; r < R; ++r) {
+      b[lay->off_seg_blk0 + P + r] = total_prefix_blocks + lay->suffix_blk_indptr[size_t(r)];
+      b[lay->off_seg_len + P + r] = lay->suffix_len[size_t(r)];
+      if (tok > INT32_MAX) return PS_ERR_INVALID_ARG;
+      b[lay->off_seg_tok0 + P + r] = int32_t(tok);
+      tok += lay->suffix_len[size_t(r)];
+      for (int32_t i = lay->suffix_blk_indptr[size_t(r)]; i < lay->suffix_blk_indptr[size_t(r) + 1]; ++i)
+        b[lay->off_blk_seg + total_prefix_blocks + i] = P + r;
+    }
+    lay->append_dest.resize(size_t(R), -1);
+    std::copy(lay->append_dest.begin(), lay->append_dest.end(), b + lay->off_dest);
+  }
   auto fill = [&](const ps_layout::schedule& s, const packed& pk) {
     if (pk.items.empty()) return;
     std::memcpy(b + s.off_items, pk.items.data(), pk.items.size() * sizeof(ps_item));
@@ -386,6 +418,54 @@ int32_t ps_layout_tables(const ps_layout* lay, const int32_t** prefix_blk_indptr
   if (group_req) *group_req = lay->group_req.data();
   if (suffix_blk_indptr) *suffix_blk_indptr = lay->suffix_blk_indptr.data();
   if (suffix_blk) *suffix_blk = lay->suffix_blk.data();
+  return PS_OK;
+}
+
+int32_t ps_layout_lengths(const ps_layout* lay, const int32_t** prefix_len, const int32_t** suffix_len) {
+  if (!lay) return PS_ERR_INVALID_ARG;
+  if (prefix_len) *prefix_len = lay->prefix_len.data();
+  if (suffix_len) *suffix_len = lay->suffix_len.data();
+  return PS_OK;
+}
+
+int32_t ps_layout_append(ps_pool* pool, ps_layout* lay, const int32_t* active, const int32_t** dest) {
+  if (!pool || !lay) return PS_ERR_INVALID_ARG;
+  const int32_t R = lay->num_requests, B = lay->geo.block_size;
+  if (int64_t(pool->num_blocks) * B > INT32_MAX) return PS_ERR_INVALID_ARG;  // slot indices are int32
+  auto is_active = [&](int32_t r) { return !active || active[r] != 0; };
+  int64_t needed = 0;
+  for (int32_t r = 0; r < R; ++r) {
+    if (!is_active(r)) continue;
+    if (lay->suffix_len[size_t(r)] == INT32_MAX) return PS_ERR_INVALID_ARG;
+    if (lay->suffix_len[size_t(r)] % B == 0) ++needed;
+  }
+  if (needed > int64_t(pool->free_list.size())) return PS_ERR_OOM;
+  // requests in ascending index; one whose private length is a multiple of the block size (none yet, or the
+  // last block is full) takes the block at the head of the free list
+  std::vector<int32_t> blk, indptr(size_t(R) + 1, 0);
+  blk.reserve(lay->suffix_blk.size() + size_t(needed));
+  lay->append_dest.assign(size_t(R), -1);
+  for (int32_t r = 0; r < R; ++r) {
+    const size_t first = blk.size();
+    blk.insert(blk.end(), lay->suffix_blk.begin() + lay->suffix_blk_indptr[size_t(r)],
+               lay->suffix_blk.begin() + lay->suffix_blk_indptr[size_t(r) + 1]);
+    if (is_active(r)) {
+      const int32_t pos = lay->suffix_len[size_t(r)];
+      if (pos % B == 0) {
+        const int32_t b = pool->free_list.front();
+        pool->free_list.pop_front();
+        pool->refcount[size_t(b)] += 1;
+        blk.push_back(b);
+      }
+      lay->append_dest[size_t(r)] = blk[first + size_t(pos / B)] * B + pos % B;
+      lay->suffix_len[size_t(r)] = pos + 1;
+    }
+    indptr[size_t(r) + 1] = int32_t(blk.size());
+  }
+  lay->suffix_blk.swap(blk);
+  lay->suffix_blk_indptr.swap(indptr);
+  if (int32_t st = ps_plan_build(lay, &lay->opt)) return st;
+  if (dest) *dest = lay->append_dest.data();
   return PS_OK;
 }
 

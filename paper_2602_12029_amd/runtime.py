@@ -78,6 +78,22 @@ class DecodeBatch:
                               (self.kv if kv is None else kv).data_ptr(), self._sc(), self.workspace.data_ptr(),
                               self.out.data_ptr(), self.lse.data_ptr() if with_lse else 0, _stream())
 
+    def kv_ingest(self, which: int, src_k: torch.Tensor, src_v: torch.Tensor):
+        """Store every segment of one kind (0 prefixes, 1 suffixes) from ragged [T, Hkv, d] sources."""
+        assert src_k.stride(2) == 1 and src_v.stride() == src_k.stride()
+        B.ps_kv_ingest(self.layout, self.tables.data_ptr(), which, src_k.data_ptr(), src_v.data_ptr(),
+                       src_k.stride(0), src_k.stride(1), self.kv.data_ptr(), self._sc(), _stream())
+
+    def append_step(self, pool, new_k: torch.Tensor, new_v: torch.Tensor, active=None):
+        """One decode step of cache growth: tables grow on the host and are uploaded again, then the new
+        tokens ([R, Hkv, d], contiguous) are stored.  Returns the destinations the host chose."""
+        dest = B.ps_layout_append(pool, self.layout, self.num_requests, active).copy()
+        self._sync_plan()
+        assert new_k.is_contiguous() and new_v.is_contiguous()
+        B.ps_kv_append(self.layout, self.tables.data_ptr(), new_k.data_ptr(), new_v.data_ptr(), self.kv.data_ptr(),
+                       self._sc(), _stream())
+        return dest
+
     def workspace_views(self):
         """(o [slots, Hq, d] fp32, lse [slots, Hq] fp32) views of the partial-state workspace."""
         slots, off = B.ps_workspace_layout(self.layout)

@@ -235,3 +235,89 @@ def test_error_paths():
     assert B.ps_pool_num_free(pool) == 3
     B.ps_pool_destroy(other)
     B.ps_pool_destroy(pool)
+
+
+# ---- table growth (ps_layout_append) -------------------------------------------------------------------
+def _same_state(w, pool, lay, opool, olay):
+    t = B.ps_layout_tables(lay, w.num_prompts, w.num_requests)
+    for key in t:
+        assert np.array_equal(t[key], getattr(olay, key)), key
+    lens = B.ps_layout_lengths(lay, w.num_prompts, w.num_requests)
+    assert np.array_equal(lens["suffix_len"], olay.suffix_len) and np.array_equal(lens["prefix_len"], olay.prefix_len)
+    assert np.array_equal(B.ps_pool_refcounts(pool, opool.num_blocks), opool.refcount)
+    assert np.array_equal(B.ps_pool_free_list(pool), np.array(opool.free, np.int32))
+
+
+def test_append_hand_worked_instance():
+    g = json.load(open(os.path.join(ROOT, "tests", "golden", "layout_small.json")))
+    geo = B.geometry(4, 2, 64, g["block_size"], "f32", "f32")
+    pool = B.ps_pool_create(g["num_blocks"], g["free_order"])
+    lay = B.ps_kv_layout(pool, geo, g["prefix_len"], g["req_prompt"], g["req_model"], g["suffix_len"])
+    for step in g["append"]["steps"]:
+        if step.get("out_of_blocks"):
+            before = (B.ps_layout_tables(lay, 2, 3)["suffix_blk"].tolist(), B.ps_pool_free_list(pool).tolist())
+            with pytest.raises(B.PsError) as e:
+                B.ps_layout_append(pool, lay, 3, step["active"])
+            assert e.value.status == B.PS_ERR_OOM
+            assert before == (B.ps_layout_tables(lay, 2, 3)["suffix_blk"].tolist(), B.ps_pool_free_list(pool).tolist())
+            continue
+        dest = B.ps_layout_append(pool, lay, 3, step["active"])
+        assert dest.tolist() == step["dest"]
+        t = B.ps_layout_tables(lay, 2, 3)
+        assert t["suffix_blk_indptr"].tolist() == step["suffix_blk_indptr"] and t["suffix_blk"].tolist() == step["suffix_blk"]
+        assert B.ps_layout_lengths(lay, 2, 3)["suffix_len"].tolist() == step["suffix_len"]
+        assert B.ps_pool_refcounts(pool, 8).tolist() == step["refcount"] and B.ps_pool_free_list(pool).tolist() == step["free"]
+    B.ps_layout_release(pool, lay)
+    assert B.ps_pool_free_list(pool).tolist() == g["append"]["free_after_release"]
+    B.ps_pool_destroy(pool)
+
+
+def test_append_bit_exact_against_oracle_policy_and_plan_invariants():
+    import dataclasses
+    rng = np.random.default_rng(5)
+    for trial in range(12):
+        bsz = int(rng.choice([1, 4, 16, 48]))
+        num_p, num_m = int(rng.integers(1, 5)), int(rng.integers(1, 4))
+        membership = [sorted(rng.choice(num_m, size=int(rng.integers(1, num_m + 1)), replace=False).tolist())
+                      for _ in range(num_p)]
+        nreq = sum(len(m) for m in membership)
+        geo = wl.Geometry(4, 2, 64, bsz, "f32", "f32")
+        w = wl.make_workload("r", geo, num_m, rng.integers(0, 100, num_p), membership, rng.integers(0, 40, nreq),
+                             pool_factor=float(rng.uniform(1.3, 2.5)), seed=100 + trial)
+        pool, lay, opool, olay = _both(w)
+        for step in range(int(rng.integers(3, 3 * bsz + 6))):
+            active = None if step % 3 == 0 else (rng.random(nreq) < 0.6).astype(np.int32)
+            try:
+                odest = ol.append_step(opool, olay, active)
+            except ol.OutOfBlocks:
+                with pytest.raises(B.PsError) as e:
+                    B.ps_layout_append(pool, lay, nreq, active)
+                assert e.value.status == B.PS_ERR_OOM
+                _same_state(w, pool, lay, opool, olay)           # a refused step changes nothing on either side
+                break
+            dest = B.ps_layout_append(pool, lay, nreq, active)
+            assert np.array_equal(dest, odest), (trial, step)
+            _same_state(w, pool, lay, opool, olay)
+        grown = dataclasses.replace(w, suffix_len=olay.suffix_len.copy())
+        _check_plan(grown, lay, B.ps_layout_plan(lay, nreq))
+        B.ps_layout_release(pool, lay)
+        ol.release_layout(opool, olay)
+        assert np.array_equal(B.ps_pool_free_list(pool), np.array(opool.free, np.int32))
+        B.ps_pool_destroy(pool)
+
+
+def test_append_keeps_the_plan_options():
+    w = wl.named_workload("b8")
+    pool = B.ps_pool_create(w.num_blocks + w.num_requests, None)
+    g = w.geometry
+    lay = B.ps_kv_layout(pool, B.geometry(g.num_q_heads, g.num_kv_heads, g.head_dim, g.block_size, g.q_dtype, g.kv_dtype),
+                         w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
+    B.ps_layout_replan(lay, B.plan_options(1024, 64))
+    before = B.ps_layout_plan(lay, w.num_requests)["items"]
+    B.ps_layout_append(pool, lay, w.num_requests)
+    after = B.ps_layout_plan(lay, w.num_requests)["items"]
+    assert (after[after[:, 7] == 0][:, 2] - after[after[:, 7] == 0][:, 1]).max() == 1024
+    assert (after[after[:, 7] == 1][:, 2] - after[after[:, 7] == 1][:, 1]).max() <= 64
+    assert len(after) >= len(before)
+    B.ps_layout_release(pool, lay)
+    B.ps_pool_destroy(pool)

@@ -153,14 +153,14 @@ class Workload:
 
     # ---- unquantised sources (what a prefill or decode worker hands over) ----
     def _source(self, tag: int, index: int, tokens: int):
-        """K, V [tokens, Hkv, d]: N(0,1) values times a per-token gain drawn log-uniformly from [1/4, 4]
-        (so that tokens differ in magnitude), as bf16 bit patterns -- float32 for float32 pools."""
+        """K, V [tokens, Hkv, d]: N(0,1) values times a per-token gain drawn log-uniformly from [1/4, 1]
+        (so that tokens differ in magnitude while values stay in the range of the N(0,1) workloads), as bf16 bit patterns -- float32 for float32 pools."""
         g = self.geometry
         rng = _rng(self.seed, tag, index)
         out = []
         for _ in range(2):
             x = rng.standard_normal((int(tokens), g.num_kv_heads, g.head_dim), dtype=np.float32)
-            gain = np.exp2(rng.uniform(-2.0, 2.0, size=(int(tokens), 1, 1))).astype(np.float32)
+            gain = np.exp2(rng.uniform(-2.0, 0.0, size=(int(tokens), 1, 1))).astype(np.float32)
             x = x * gain
             out.append(x if g.kv_dtype == "f32" else bf16_bits_from_f32(x))
         return out[0], out[1]
