@@ -29,6 +29,9 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="b8", help="tiny | b8 | long | mixed | fp8_70b")
+    ap.add_argument("--path", default="decode", choices=["decode", "ingest"],
+                    help="decode: the attention step (the headline metric); ingest: hand-off of the batch's KV into "
+                         "the paged pool (ps_kv_ingest over every prefix and suffix), a step = one whole hand-off")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--models", type=int, default=0, help="override the number of decode models M (b8, long, fp8_70b)")
     ap.add_argument("--copies", type=int, default=3, help="distinct KV pool copies rotated between steps")
@@ -101,11 +104,149 @@ def cpu_baseline(w, lay_tables, data, seconds):
                       f"workload has {w.num_prompts} prompts / {w.num_requests} requests, cycled), {wall:.1f} s wall"}
 
 
+def calibrate_copy(dev):
+    """A plain elementwise kernel of known traffic (reads 2^30 bytes, writes 2^30 bytes per launch): the
+    reference the HBM byte counters of a profiler run are scaled by."""
+    import torch
+    src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        torch.add(src, 1, out=dst)
+    torch.cuda.synchronize()
+    del src, dst
+
+
+def cpu_ingest_baseline(w, olay, sources, seconds):
+    """Time the oracle's ingest on whole prompts until about `seconds` have passed."""
+    from oracle import kv_update as ku
+    import workloads as wl
+    g = w.geometry
+    shape = (w.num_blocks, g.num_kv_heads, 2, g.block_size, g.head_dim)
+    kv = np.zeros(shape, wl.generate.STORAGE[g.kv_dtype])
+    scales = np.ones((w.num_blocks, g.num_kv_heads, 2), np.float32) if g.kv_dtype == "fp8_e4m3" else None
+    esz_src = 4 if g.kv_dtype == "f32" else 2
+    esz_dst = wl.generate.ELEM_BYTES[g.kv_dtype]
+    done, prompts = 0, 0
+    wall0, cpu0 = time.perf_counter(), time.process_time()
+    for p in list(range(w.num_prompts)) * 64:
+        ids = olay.prefix_blk[olay.prefix_blk_indptr[p]:olay.prefix_blk_indptr[p + 1]]
+        ku.ingest_segment(kv, scales, g.kv_dtype, ids, sources[p][0], sources[p][1])
+        done += int(w.prefix_len[p]) * g.num_kv_heads * g.head_dim * 2 * (esz_src + esz_dst)
+        prompts += 1
+        if time.perf_counter() - wall0 >= seconds:
+            break
+    wall = time.perf_counter() - wall0
+    cpu = time.process_time() - cpu0
+    return {"value": done / wall / 1e9, "unit": "GB/s", "cores": max(1, int(round(cpu / wall))), "kind": "oracle",
+            "sample": f"numpy oracle ingest of {prompts} prompt prefixes (the workload has {w.num_prompts}, cycled), "
+                      f"{wall:.1f} s wall"}
+
+
+def main_ingest(args):
+    """--path ingest: one step stores every prefix and every suffix of the batch from contiguous sources."""
+    import torch
+    import workloads as wl
+    from oracle import layout as ol
+    from paper_2602_12029_amd import binding as B
+    from paper_2602_12029_amd.runtime import DecodeBatch, to_device
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    dev = "cuda:0"
+    w = wl.named_workload(args.workload, args.seed, args.models or None)
+    g = w.geometry
+    geo = B.geometry(g.num_q_heads, g.num_kv_heads, g.head_dim, g.block_size, g.q_dtype, g.kv_dtype)
+    pool = B.ps_pool_create(w.num_blocks, w.free_order)
+    layout = B.ps_kv_layout(pool, geo, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
+    src_dtype = "f32" if g.kv_dtype == "f32" else "bf16"
+    pre = [w.prefix_source(p) for p in range(w.num_prompts)]
+    suf = [w.suffix_source(r) for r in range(w.num_requests)]
+
+    def ragged(parts, which):
+        parts = [x[which] for x in parts if x[which].shape[0]]
+        return to_device(np.concatenate(parts, axis=0), src_dtype, dev) if parts else None
+
+    # two copies of the sources, alternated, so that a step does not find its input in the last-level cache
+    srcs = [[(ragged(pre, 0), ragged(pre, 1)), (ragged(suf, 0), ragged(suf, 1))]]
+    srcs.append([tuple(None if t is None else t.clone() for t in pair) for pair in srcs[0]])
+    nelem = w.num_blocks * g.num_kv_heads * 2 * g.block_size * g.head_dim
+    torch_dtype = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch.uint8}[g.kv_dtype]
+    kv = torch.zeros(nelem, dtype=torch_dtype, device=dev)
+    scales = torch.ones((w.num_blocks, g.num_kv_heads, 2), dtype=torch.float32, device=dev) if g.kv_dtype == "fp8_e4m3" else None
+    q = to_device(w.q_bits(), g.q_dtype, dev)
+    batch = DecodeBatch(layout, geo, w.num_requests, q, kv, scales)
+    stream = int(torch.cuda.current_stream().cuda_stream)
+
+    def step(i, ev=None, slot=0):
+        (pk, pv), (sk, sv) = srcs[i % 2]
+        if ev is not None:
+            ev.record(slot, 0, stream)
+        if pk is not None:
+            batch.kv_ingest(0, pk, pv)
+        if ev is not None:
+            ev.record(slot, 1, stream)
+        if sk is not None:
+            batch.kv_ingest(1, sk, sv)
+
+    if args.calibrate_copy:
+        calibrate_copy(dev)
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev = None if args.no_events else HipEvents(args.steps)
+    every = max(1, args.event_every)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, ev if (ev is not None and i % every == 0) else None, i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    esz_src = 4 if g.kv_dtype == "f32" else 2
+    esz_dst = wl.generate.ELEM_BYTES[g.kv_dtype]
+    per_tok = g.num_kv_heads * g.head_dim * 2 * (esz_src + esz_dst)
+    t_pre, t_suf = int(w.prefix_len.astype(np.int64).sum()), int(w.suffix_len.astype(np.int64).sum())
+    scale_bytes = w.blocks_needed() * g.num_kv_heads * 8 if g.kv_dtype == "fp8_e4m3" else 0
+    moved = (t_pre + t_suf) * per_tok + scale_bytes
+    pre_blocks = int(((w.prefix_len.astype(np.int64) + g.block_size - 1) // g.block_size).sum())
+    pre_bytes = t_pre * per_tok + (pre_blocks * g.num_kv_heads * 8 if g.kv_dtype == "fp8_e4m3" else 0)
+    roofline = {"bound": "hbm", "kernel": "ingest (shared prefixes)", "achieved": None, "peak": PEAK_HBM_GBS,
+                "unit": "GB/s", "frac": None, "traffic": None}
+    if ev is not None:
+        k_ms = float(np.mean([ev.elapsed_ms(i) for i in range(0, args.steps, every)]))
+        roofline.update(achieved=pre_bytes / (k_ms * 1e-3) / 1e9, kernel_ms=k_ms, algorithmic_bytes=pre_bytes)
+        roofline["frac"] = roofline["achieved"] / PEAK_HBM_GBS
+    summary = os.path.join(ROOT, "profiles", f"ingest_kernel_{args.workload}.md")
+    if os.path.exists(summary):
+        for text in open(summary):
+            if text.startswith("traffic_bytes_per_launch:"):
+                roofline["traffic"] = float(text.split(":")[1])
+    value = moved / (ms_per_step * 1e-3) / 1e9
+    line = {
+        "metric": "KV hand-off ingest into the paged pool: bytes read + written, GB/s",
+        "value": value, "unit": "GB/s", "pct_of_peak_hbm": 100.0 * value / PEAK_HBM_GBS,
+        "tokens_per_s": (t_pre + t_suf) / (ms_per_step * 1e-3),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"bf16": "bf16", "fp8_e4m3": "bf16 -> fp8_e4m3", "f32": "f32"}[g.kv_dtype], "data": "synthetic",
+        "config": {"workload": args.workload, "path": "ingest", "prompts": w.num_prompts, "requests": w.num_requests,
+                   "prefix_tokens": t_pre, "suffix_tokens": t_suf, "kv_heads": g.num_kv_heads, "head_dim": g.head_dim,
+                   "block_size": g.block_size, "moved_bytes": moved},
+        "roofline": roofline,
+    }
+    if args.cpu_seconds > 0:
+        opool = ol.BlockPool(w.num_blocks, w.free_order)
+        olay = ol.build_layout(opool, g.block_size, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
+        line["cpu_baseline"] = cpu_ingest_baseline(w, olay, pre, args.cpu_seconds)
+    print(json.dumps(line))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs the decode attention of ONE GPU (no collectives, no sharding); "
                  "use --gpus 1")
+    if args.path == "ingest":
+        return main_ingest(args)
     import torch
     import workloads as wl
     from paper_2602_12029_amd import binding as B
@@ -140,13 +281,8 @@ def main():
     def attention(kv):      # the dominant kernel(s): prefix + suffix work list
         B.ps_prefix_suffix_attention(layout, tp, qp, kv.data_ptr(), sc, wp, stream)
 
-    if args.calibrate_copy:      # known traffic: reads 2^30 bytes, writes 2^30 bytes per launch
-        src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            torch.add(src, 1, out=dst)
-        torch.cuda.synchronize()
-        del src, dst
+    if args.calibrate_copy:
+        calibrate_copy(dev)
 
     for i in range(args.warmup):
         batch.decode_attention(with_lse=False, kv=copies[i % len(copies)])

@@ -41,10 +41,8 @@ __device__ __forceinline__ float wave_max(float x) {
 
 struct KvWriteParams {
   const int32_t* blk;        // concatenated block array
-  const int32_t* seg_blk0;   // per segment: first entry in blk
-  const int32_t* seg_len;    // tokens
-  const int32_t* seg_tok0;   // first token in the ragged source of its kind
-  const int32_t* blk_seg;    // owning segment of every blk entry
+  const int32_t* ent_tok0;   // per entry: its first token in the ragged source of its kind
+  const int32_t* ent_valid;  // per entry: tokens stored in the block
   const int32_t* dest;       // [R] block * B + slot of the token being appended, -1 = none
   void* kv;
   float* scales;
@@ -64,10 +62,8 @@ __global__ __launch_bounds__(256) void ingest_copy_kernel(KvWriteParams p, const
   const int which = int(tile & 1);
   const int h = int((tile >> 1) % p.num_kv_heads);
   const int e = entry0 + int((tile >> 1) / p.num_kv_heads);
-  const int s = p.blk_seg[e];
-  const int first_tok = (e - p.seg_blk0[s]) * p.block_size;
-  const int n_valid = min(p.block_size, p.seg_len[s] - first_tok);
-  const T* src = (which ? src_v : src_k) + (int64_t(p.seg_tok0[s]) + first_tok) * src_s_tok + int64_t(h) * src_s_head;
+  const int n_valid = p.ent_valid[e];
+  const T* src = (which ? src_v : src_k) + int64_t(p.ent_tok0[e]) * src_s_tok + int64_t(h) * src_s_head;
   T* dst = static_cast<T*>(p.kv) + int64_t(p.blk[e]) * p.s_block + int64_t(h) * p.s_head + int64_t(which) * p.s_kv;
   const int cpt = p.head_dim / kVec;   // 16-byte chunks per token
   for (int c = lane; c < n_valid * cpt; c += 64) {
@@ -77,32 +73,37 @@ __global__ __launch_bounds__(256) void ingest_copy_kernel(KvWriteParams p, const
   }
 }
 
-// ---- ingest, bf16 source -> e4m3 pool.  CH: 16-byte source chunks a lane keeps in registers ---------------
-template <int CH>
+// ---- ingest, bf16 source -> e4m3 pool.  CH: 16-byte source chunks a lane keeps in registers; SHIFT >= 0:
+// head_dim / 8 chunks per token is 2^SHIFT (index math by shifts), -1: any multiple of 8 ------------------------
+template <int CH, int SHIFT>
 __global__ __launch_bounds__(256) void ingest_e4m3_kernel(KvWriteParams p, const uint16_t* __restrict__ src_k,
                                                           const uint16_t* __restrict__ src_v, int64_t src_s_tok,
                                                           int64_t src_s_head, int entry0, int num_entries) {
   const int lane = threadIdx.x & 63;
-  const int64_t tile = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);
+  const int64_t tile = int64_t(blockIdx.x) * 4 + __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
   if (tile >= int64_t(num_entries) * p.num_kv_heads * 2) return;
   const int which = int(tile & 1);
   const int h = int((tile >> 1) % p.num_kv_heads);
   const int e = entry0 + int((tile >> 1) / p.num_kv_heads);
-  const int s = p.blk_seg[e];
-  const int first_tok = (e - p.seg_blk0[s]) * p.block_size;
-  const int n_valid = min(p.block_size, p.seg_len[s] - first_tok);
-  const uint16_t* src = (which ? src_v : src_k) + (int64_t(p.seg_tok0[s]) + first_tok) * src_s_tok + int64_t(h) * src_s_head;
+  const int n_valid = p.ent_valid[e];
+  const uint16_t* src = (which ? src_v : src_k) + int64_t(p.ent_tok0[e]) * src_s_tok + int64_t(h) * src_s_head;
   const int id = p.blk[e];
   uint8_t* dst = static_cast<uint8_t*>(p.kv) + int64_t(id) * p.s_block + int64_t(h) * p.s_head + int64_t(which) * p.s_kv;
   const int cpt = p.head_dim / 8;
   const int total = n_valid * cpt;
+  auto token_of = [&](int c) { return SHIFT >= 0 ? c >> SHIFT : c / cpt; };
+  auto column_of = [&](int c) { return (SHIFT >= 0 ? c & ((1 << SHIFT) - 1) : c % cpt) * 8; };
+  // every load goes out before anything waits: chunks past the tile re-read its last chunk and are zeroed after
   u32x4 raw[CH];
+#pragma unroll
+  for (int i = 0; i < CH; ++i) {
+    const int c = min(lane + 64 * i, total - 1);
+    raw[i] = *reinterpret_cast<const u32x4*>(src + int64_t(token_of(c)) * src_s_tok + column_of(c));
+  }
   float amax = 0.f;
 #pragma unroll
   for (int i = 0; i < CH; ++i) {
-    const int c = lane + 64 * i;
-    raw[i] = u32x4{0, 0, 0, 0};
-    if (c < total) raw[i] = *reinterpret_cast<const u32x4*>(src + int64_t(c / cpt) * src_s_tok + (c % cpt) * 8);
+    if (lane + 64 * i >= total) raw[i] = u32x4{0, 0, 0, 0};
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       amax = fmaxf(amax, fabsf(bf16_bits_to_f32(raw[i][j] & 0xffffu)));
@@ -112,19 +113,41 @@ __global__ __launch_bounds__(256) void ingest_e4m3_kernel(KvWriteParams p, const
   amax = wave_max(amax);
   const float scale = amax > 0.f ? amax / 448.f : 1.f;
   if (lane == 0) p.scales[(int64_t(id) * p.num_kv_heads + h) * 2 + which] = scale;
+  // x / scale without a division per element.  q0 = x * RN(1 / scale) is within 2 ulp of the exact quotient and
+  // the correctly rounded quotient within 0.5 ulp, so both lie on the same side of every rounding boundary of
+  // e4m3 -- and get the same code -- unless q0 is within a few ulp of one.  Boundaries (midpoints of neighbouring
+  // e4m3 values) have the float32 pattern "3 mantissa bits, then 1000...0" in the normal range; a chunk in which
+  // any lane is that close to one, or may fall into the subnormal range of e4m3 (an absolute grid), is redone with
+  // the real division.  The stored codes are therefore exactly those of RN(x / scale) everywhere.
+  const float rinv = 1.f / scale;
+  const float subnormal_below = scale * 0x1.000002p-6f;   // |x| under this: the quotient may be under 2^-6
 #pragma unroll
   for (int i = 0; i < CH; ++i) {
     const int c = lane + 64 * i;
+    float x[8], q[8];
+    bool risky = false;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      x[2 * j] = bf16_bits_to_f32(raw[i][j] & 0xffffu);
+      x[2 * j + 1] = bf16_bits_to_f32(raw[i][j] >> 16);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      q[j] = x[j] * rinv;
+      // low 20 mantissa bits within [0x7fffc, 0x80004]: shifted to the top of the word, offset so the window starts at 0
+      risky |= (__float_as_uint(q[j]) << 12) + 0x80004000u <= 0x8000u;
+      risky |= fabsf(x[j]) < subnormal_below;               // subnormal range of e4m3 (also catches exact zeros)
+    }
+    risky = risky && c < total;                               // lanes past the tile hold zeros: no say
+    if (__builtin_amdgcn_ballot_w64(risky) != 0) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) q[j] = x[j] / scale;
+    }
     if (c < total) {
       u32x2 out;
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const uint32_t w0 = raw[i][2 * j], w1 = raw[i][2 * j + 1];
-        const uint32_t lo = f32x2_to_e4m3(bf16_bits_to_f32(w0 & 0xffffu) / scale, bf16_bits_to_f32(w0 >> 16) / scale);
-        const uint32_t hi = f32x2_to_e4m3(bf16_bits_to_f32(w1 & 0xffffu) / scale, bf16_bits_to_f32(w1 >> 16) / scale);
-        out[j] = lo | (hi << 16);
-      }
-      *reinterpret_cast<u32x2*>(dst + int64_t(c / cpt) * p.s_tok + (c % cpt) * 8) = out;
+      out[0] = f32x2_to_e4m3(q[0], q[1]) | (f32x2_to_e4m3(q[2], q[3]) << 16);
+      out[1] = f32x2_to_e4m3(q[4], q[5]) | (f32x2_to_e4m3(q[6], q[7]) << 16);
+      *reinterpret_cast<u32x2*>(dst + int64_t(token_of(c)) * p.s_tok + column_of(c)) = out;
     }
   }
 }
@@ -189,10 +212,8 @@ KvWriteParams make_write_params(const ps_layout* lay, const void* dev_tables, vo
   const ps_geometry& g = lay->geo;
   KvWriteParams p{};
   p.blk = t + lay->off_blk;
-  p.seg_blk0 = t + lay->off_seg_blk0;
-  p.seg_len = t + lay->off_seg_len;
-  p.seg_tok0 = t + lay->off_seg_tok0;
-  p.blk_seg = t + lay->off_blk_seg;
+  p.ent_tok0 = t + lay->off_ent_tok0;
+  p.ent_valid = t + lay->off_ent_valid;
   p.dest = t + lay->off_dest;
   p.kv = kv;
   p.scales = scales;
@@ -231,14 +252,22 @@ int32_t launch_kv_ingest(const ps_layout* lay, const void* dev_tables, int which
   } else {
     if (g.head_dim % 8) return PS_ERR_UNSUPPORTED;
     const int64_t chunks = (int64_t(g.block_size) * (g.head_dim / 8) + 63) / 64;   // per lane, whole tile in registers
-#define PS_INGEST(CH)                                                                                            \
-  hipLaunchKernelGGL(ingest_e4m3_kernel<CH>, grid, block, 0, st, p, static_cast<const uint16_t*>(src_k),          \
+#define PS_INGEST(CH, SHIFT)                                                                                     \
+  hipLaunchKernelGGL((ingest_e4m3_kernel<CH, SHIFT>), grid, block, 0, st, p, static_cast<const uint16_t*>(src_k), \
                      static_cast<const uint16_t*>(src_v), src_s_tok, src_s_head, entry0, num_entries)
-    if (chunks <= 4) PS_INGEST(4);
-    else if (chunks <= 8) PS_INGEST(8);
-    else if (chunks <= 16) PS_INGEST(16);
-    else if (chunks <= 32) PS_INGEST(32);
-    else return PS_ERR_UNSUPPORTED;
+    if (g.head_dim == 128) {   // 16 chunks per token
+      if (chunks <= 4) PS_INGEST(4, 4);
+      else if (chunks <= 8) PS_INGEST(8, 4);
+      else if (chunks <= 16) PS_INGEST(16, 4);
+      else if (chunks <= 32) PS_INGEST(32, 4);
+      else return PS_ERR_UNSUPPORTED;
+    } else {
+      if (chunks <= 4) PS_INGEST(4, -1);
+      else if (chunks <= 8) PS_INGEST(8, -1);
+      else if (chunks <= 16) PS_INGEST(16, -1);
+      else if (chunks <= 32) PS_INGEST(32, -1);
+      else return PS_ERR_UNSUPPORTED;
+    }
 #undef PS_INGEST
   }
   return PS_OK;

@@ -190,7 +190,7 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   if (pre_mfma && suf_mfma) pk_all = pack(0, n_items);
 
   // device blob: [block ids: prefix ++ suffix][request list: group_req ++ identity][items][slot_base][schedules]
-  // [segment directory][destinations of the last append]
+  // [per-block source offsets and valid counts][destinations of the last append]
   auto pad4 = [](int64_t n) { return (n + 3) / 4 * 4; };
   lay->off_blk = 0;
   lay->off_req = pad4(lay->off_blk + int64_t(lay->prefix_blk.size() + lay->suffix_blk.size()));
@@ -211,36 +211,32 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   place(lay->sched_prefix, pk_prefix);
   place(lay->sched_suffix, pk_suffix);
   place(lay->sched_all, pk_all);
-  // segment directory (cache-writing kernels)
-  const int64_t num_seg = int64_t(P) + R, num_blk_entries = int64_t(lay->prefix_blk.size() + lay->suffix_blk.size());
-  lay->off_seg_blk0 = words;
-  lay->off_seg_len = pad4(lay->off_seg_blk0 + num_seg);
-  lay->off_seg_tok0 = pad4(lay->off_seg_len + num_seg);
-  lay->off_blk_seg = pad4(lay->off_seg_tok0 + num_seg);
-  lay->off_dest = pad4(lay->off_blk_seg + num_blk_entries);
+  // per-block directory for the cache-writing kernels
+  const int64_t num_blk_entries = int64_t(lay->prefix_blk.size() + lay->suffix_blk.size());
+  lay->off_ent_tok0 = words;
+  lay->off_ent_valid = pad4(lay->off_ent_tok0 + num_blk_entries);
+  lay->off_dest = pad4(lay->off_ent_valid + num_blk_entries);
   words = pad4(lay->off_dest + R);
   lay->blob.assign(size_t(std::max<int64_t>(words, 4)), 0);
   int32_t* b = lay->blob.data();
   {
-    int64_t tok = 0;
-    for (int32_t p = 0; p < P; ++p) {
-      b[lay->off_seg_blk0 + p] = lay->prefix_blk_indptr[size_t(p)];
-      b[lay->off_seg_len + p] = lay->prefix_len[size_t(p)];
-      if (tok > INT32_MAX) return PS_ERR_INVALID_ARG;
-      b[lay->off_seg_tok0 + p] = int32_t(tok);
-      tok += lay->prefix_len[size_t(p)];
-      for (int32_t i = lay->prefix_blk_indptr[size_t(p)]; i < lay->prefix_blk_indptr[size_t(p) + 1]; ++i) b[lay->off_blk_seg + i] = p;
-    }
-    tok = 0;
-    for (int32_t r = 0; r < R; ++r) {
-      b[lay->off_seg_blk0 + P + r] = total_prefix_blocks + lay->suffix_blk_indptr[size_t(r)];
-      b[lay->off_seg_len + P + r] = lay->suffix_len[size_t(r)];
-      if (tok > INT32_MAX) return PS_ERR_INVALID_ARG;
-      b[lay->off_seg_tok0 + P + r] = int32_t(tok);
-      tok += lay->suffix_len[size_t(r)];
-      for (int32_t i = lay->suffix_blk_indptr[size_t(r)]; i < lay->suffix_blk_indptr[size_t(r) + 1]; ++i)
-        b[lay->off_blk_seg + total_prefix_blocks + i] = P + r;
-    }
+    const int32_t B = g.block_size;
+    auto fill_entries = [&](const std::vector<int32_t>& indptr, const std::vector<int32_t>& len, int32_t entry0) {
+      int64_t tok = 0;
+      for (size_t s = 0; s + 1 < indptr.size(); ++s) {
+        for (int32_t i = indptr[s]; i < indptr[s + 1]; ++i) {
+          const int64_t first = int64_t(i - indptr[s]) * B;
+          if (tok + first > INT32_MAX) return false;
+          b[lay->off_ent_tok0 + entry0 + i] = int32_t(tok + first);
+          b[lay->off_ent_valid + entry0 + i] = int32_t(std::min<int64_t>(B, len[s] - first));
+        }
+        tok += len[s];
+      }
+      return true;
+    };
+    if (!fill_entries(lay->prefix_blk_indptr, lay->prefix_len, 0) ||
+        !fill_entries(lay->suffix_blk_indptr, lay->suffix_len, total_prefix_blocks))
+      return PS_ERR_INVALID_ARG;
     lay->append_dest.resize(size_t(R), -1);
     std::copy(lay->append_dest.begin(), lay->append_dest.end(), b + lay->off_dest);
   }

@@ -56,10 +56,10 @@ struct ps_layout {
   // device table blob (int32 words) and section offsets in words
   std::vector<int32_t> blob;
   int64_t off_blk = 0, off_req = 0, off_items = 0, off_slot = 0;
-  // segment directory for the cache-writing kernels; segments are the P prefixes then the R suffixes:
-  // first entry in the concatenated block array, length in tokens, first token in the ragged source of its
-  // kind; then the owning segment of every block-array entry, then append_dest
-  int64_t off_seg_blk0 = 0, off_seg_len = 0, off_seg_tok0 = 0, off_blk_seg = 0, off_dest = 0;
+  // for the cache-writing kernels, per entry of the concatenated block array: index of its first token in the
+  // ragged source tensor of its kind (prefixes back to back / suffixes back to back) and its number of valid
+  // tokens; then append_dest
+  int64_t off_ent_tok0 = 0, off_ent_valid = 0, off_dest = 0;
 };
 
 // Waves per SIMD the MFMA kernel is built for, by the widest row group it must carry.
