@@ -1,4 +1,4 @@
-"""CPU oracle for shared-prefix decode attention -- TEST INFRASTRUCTURE ONLY.
+"""CPU oracle for shared-prefix decode attention and cache growth -- TEST INFRASTRUCTURE ONLY.
 
 Plain, slow, fp64 numpy.  Only tests, the smoke check and the benchmark's
 cpu_baseline leg may import this package; the product path (the HIP library and
@@ -7,6 +7,10 @@ its Python binding) never does, and this package imports nothing from it.
 Parity pins (tests/test_oracle_*.py): brute-force dense attention in Python
 loops, closed forms, placement/permutation invariance, split-and-merge
 exactness, a library SDPA for the single-model case, the e4m3 format table, and
-the Eq. 9 block-count / refcount invariants.  No function here is unpinned.
+the Eq. 9 block-count / refcount invariants.  The cache-writing side (e4m3
+encoder, ingest, append, table growth; tests/test_oracle_kv_update.py) is pinned
+by the format table, an independently written quantiser, exact round trips,
+error bounds, order-of-arrival identities between append and ingest, scalar
+brute force and a hand-worked table.  No function here is unpinned.
 """
 from . import attention, fp8, kv_update, layout  # noqa: F401
