@@ -80,11 +80,12 @@ __global__ __launch_bounds__(256) void ingest_e4m3_kernel(KvWriteParams p, const
                                                           const uint16_t* __restrict__ src_v, int64_t src_s_tok,
                                                           int64_t src_s_head, int entry0, int num_entries) {
   const int lane = threadIdx.x & 63;
-  const int64_t tile = int64_t(blockIdx.x) * 4 + __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
-  if (tile >= int64_t(num_entries) * p.num_kv_heads * 2) return;
-  const int which = int(tile & 1);
-  const int h = int((tile >> 1) % p.num_kv_heads);
-  const int e = entry0 + int((tile >> 1) / p.num_kv_heads);
+  // wave-uniform tile coordinates (the launcher keeps the tile count under 2^31)
+  const uint32_t tile = blockIdx.x * 4u + uint32_t(__builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6));
+  if (tile >= uint32_t(num_entries) * uint32_t(p.num_kv_heads) * 2u) return;
+  const int which = int(tile & 1u);
+  const int h = int((tile >> 1) % uint32_t(p.num_kv_heads));
+  const int e = entry0 + int((tile >> 1) / uint32_t(p.num_kv_heads));
   const int n_valid = p.ent_valid[e];
   const uint16_t* src = (which ? src_v : src_k) + int64_t(p.ent_tok0[e]) * src_s_tok + int64_t(h) * src_s_head;
   const int id = p.blk[e];
@@ -140,13 +141,25 @@ __global__ __launch_bounds__(256) void ingest_e4m3_kernel(KvWriteParams p, const
     }
     risky = risky && c < total;                               // lanes past the tile hold zeros: no say
     if (__builtin_amdgcn_ballot_w64(risky) != 0) {
+      // second look: a quotient near a boundary that is exact (zero residual x - q0 * scale; ties of short
+      // mantissas are common with bf16 inputs) is the correctly rounded quotient already
+      bool divide = false;
 #pragma unroll
-      for (int j = 0; j < 8; ++j) q[j] = x[j] / scale;
+      for (int j = 0; j < 8; ++j) {
+        const bool near = (__float_as_uint(q[j]) << 12) + 0x80004000u <= 0x8000u;
+        divide |= near && __builtin_fmaf(-q[j], scale, x[j]) != 0.f;
+        divide |= fabsf(x[j]) < subnormal_below;
+      }
+      divide = divide && c < total;
+      if (__builtin_amdgcn_ballot_w64(divide) != 0) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) q[j] = x[j] / scale;
+      }
     }
     if (c < total) {
       u32x2 out;
-      out[0] = f32x2_to_e4m3(q[0], q[1]) | (f32x2_to_e4m3(q[2], q[3]) << 16);
-      out[1] = f32x2_to_e4m3(q[4], q[5]) | (f32x2_to_e4m3(q[6], q[7]) << 16);
+      out[0] = uint32_t(__builtin_amdgcn_cvt_pk_fp8_f32(q[2], q[3], __builtin_amdgcn_cvt_pk_fp8_f32(q[0], q[1], 0, false), true));
+      out[1] = uint32_t(__builtin_amdgcn_cvt_pk_fp8_f32(q[6], q[7], __builtin_amdgcn_cvt_pk_fp8_f32(q[4], q[5], 0, false), true));
       *reinterpret_cast<u32x2*>(dst + int64_t(token_of(c)) * p.s_tok + column_of(c)) = out;
     }
   }
@@ -238,7 +251,7 @@ int32_t launch_kv_ingest(const ps_layout* lay, const void* dev_tables, int which
   if (num_entries == 0) return PS_OK;
   const int64_t tiles = int64_t(num_entries) * g.num_kv_heads * 2;
   const int64_t grid64 = (tiles + 3) / 4;
-  if (grid64 > INT32_MAX) return PS_ERR_INVALID_ARG;
+  if (tiles > INT32_MAX) return PS_ERR_INVALID_ARG;
   const dim3 grid{unsigned(grid64)}, block{256};
   const KvWriteParams p = make_write_params(lay, dev_tables, kv, scales);
   if (g.kv_dtype == PS_F32) {

@@ -27,6 +27,17 @@ def test_reciprocal_shortcut_with_fallback_equals_division():
     shortcut = fp8.encode(q0)
     assert (shortcut != exact).sum() > 1000                       # the inputs are adversarial ...
     assert (np.where(near | subnormal, exact, shortcut) == exact).all()   # ... and the fallback catches every one
+    # a near quotient with zero residual x - q0 * s is exact and needs no division either (the product of two
+    # float32 values and its difference from x are exact in float64)
+    residual = x.astype(np.float64) - q0.astype(np.float64) * s.astype(np.float64)
+    divide = (near & (residual != 0)) | subnormal
+    assert (np.where(divide, exact, shortcut) == exact).all()
+    # ... which is what makes ties of short mantissas (bf16 inputs, power-of-two scales) cheap
+    xb = (rng.integers(0x3F80, 0x4000, n).astype(np.uint32) << np.uint32(16)).view(np.float32)
+    sb = np.float32(2.0 ** -7)
+    qb = xb * np.float32(128)
+    nearb = ((qb.view(np.uint32) << np.uint32(12)) + np.uint32(0x80004000)).astype(np.uint32) <= 0x8000
+    assert nearb.mean() > 0.05 and not (nearb & ((xb.astype(np.float64) - qb.astype(np.float64) * float(sb)) != 0)).any()
     # ordinary data rarely needs the fallback
     y = rng.standard_normal(n).astype(np.float32)
     q = (y * np.float32(1 / 0.0078)).astype(np.float32)
