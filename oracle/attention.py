@@ -98,26 +98,37 @@ def merge_states(o_parts: np.ndarray, lse_parts: np.ndarray):
     return o, lse
 
 
-def request_kv(kv, scales, kv_dtype, lay, r: int):
-    """Concatenated (K, V) of request r: prefix of its prompt, then its own suffix."""
+def request_kv(kv, scales, kv_dtype, lay, r: int, prefix_visible=None):
+    """Concatenated (K, V) of request r: prefix of its prompt, then its own suffix.
+
+    prefix_visible[r] (optional) cuts the prefix to its first prefix_visible[r] tokens.  This is how a
+    chunk of new prompt tokens is prefilled against the cache (System Design, execution pipeline step 1:
+    later steps extend the cache only for the newly appended tokens): the chunk's tokens are stored as
+    the continuation of the shared prefix, every one of them is a query row on that prompt, and row i
+    sees the old cache plus the chunk's tokens 0..i -- ordinary causal attention written as a length.
+    """
     p = int(lay.req_prompt[r])
+    seen = int(lay.prefix_len[p]) if prefix_visible is None else int(prefix_visible[r])
+    if not 0 <= seen <= int(lay.prefix_len[p]):
+        raise ValueError("visible prefix length out of range")
     kp, vp = gather_segment(kv, scales, kv_dtype,
-                            lay.prefix_blk[lay.prefix_blk_indptr[p]:lay.prefix_blk_indptr[p + 1]],
-                            int(lay.prefix_len[p]))
+                            lay.prefix_blk[lay.prefix_blk_indptr[p]:lay.prefix_blk_indptr[p + 1]], seen)
     ks, vs = gather_segment(kv, scales, kv_dtype,
                             lay.suffix_blk[lay.suffix_blk_indptr[r]:lay.suffix_blk_indptr[r + 1]],
                             int(lay.suffix_len[r]))
     return np.concatenate([kp, ks], axis=0), np.concatenate([vp, vs], axis=0)
 
 
-def decode_attention(q_bits, q_dtype: str, kv, scales, kv_dtype: str, lay, requests=None):
-    """Whole-step oracle: (O [n, Hq, d], LSE [n, Hq]) for `requests` (default: all, in order)."""
+def decode_attention(q_bits, q_dtype: str, kv, scales, kv_dtype: str, lay, requests=None, prefix_visible=None):
+    """Whole-step oracle: (O [n, Hq, d], LSE [n, Hq]) for `requests` (default: all, in order).
+
+    prefix_visible: optional int [R], see request_kv."""
     q = widen(q_bits, q_dtype)
     reqs = range(q.shape[0]) if requests is None else list(requests)
     out = np.zeros((len(reqs),) + q.shape[1:], np.float64)
     lse = np.zeros((len(reqs), q.shape[1]), np.float64)
     for i, r in enumerate(reqs):
-        k, v = request_kv(kv, scales, kv_dtype, lay, r)
+        k, v = request_kv(kv, scales, kv_dtype, lay, r, prefix_visible)
         out[i], lse[i] = attention_state(q[r], k, v)
     return out, lse
 
