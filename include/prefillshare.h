@@ -23,8 +23,9 @@
  *                                               + which*kv_stride_kv + slot*kv_stride_tok + c
  *     (which: 0 = K, 1 = V; strides in elements; the head_dim axis is contiguous; every stride must
  *     be a multiple of 16 bytes).  kv_scales (fp8 only) is [num_blocks][Hkv][2] fp32: K scale, V scale.
- *   - q head h reads KV head h / (Hq / Hkv).  There is no mask: every stored token of both segments
- *     is attended to.  Scores are scaled by 1/sqrt(head_dim).
+ *   - q head h reads KV head h / (Hq / Hkv).  Every stored token of both segments is attended to,
+ *     unless ps_layout_set_visible limits how much of the shared prefix a request sees.  Scores are
+ *     scaled by 1/sqrt(head_dim).
  *   - A partial state of a set of tokens is (o: the softmax-weighted value average over that set,
  *     fp32[d]; lse: natural-log sum of exp(score) over that set, fp32).  The empty set is (0, -inf).
  */
@@ -120,6 +121,12 @@ int32_t ps_layout_replan(ps_layout* layout, const ps_plan_options* options);
  * slots [slot_base[r], slot_base[r+1]), prefix splits first. */
 int32_t ps_layout_plan(const ps_layout* layout, int32_t* num_items, const int32_t** items,
                        const int32_t** slot_base, int32_t* prefix_variant, int32_t* suffix_variant);
+/* The request list the items index into (host view, valid until the next replan/release): a prompt's
+ * requests in ascending order for every prompt (group_req), then 0..R-1 (private-suffix items), then,
+ * where visible lengths keep part of a sharing group out of a prefix chunk, the sub-lists of those
+ * chunks.  The last field of an item is a bit set: bit 0 = private suffix, bit 1 = some row of the item
+ * sees fewer tokens than the item's token end. */
+int32_t ps_layout_request_list(const ps_layout* layout, int32_t* count, const int32_t** list);
 
 /* Schedule of the persistent matrix-core kernel for one launchable set of items (which: 0 = prefix items,
  * 1 = suffix items, 2 = both): the set's items regrouped by workgroup, int32[n][8] in the item format
@@ -164,6 +171,22 @@ int32_t ps_merge_states(const ps_layout* layout, const void* dev_tables, const v
 int32_t ps_decode_attention(const ps_layout* layout, const void* dev_tables, const void* q,
                             const void* kv_pool, const float* kv_scales, void* workspace,
                             void* out, float* out_lse, void* stream);
+
+/* ---- partial prefill: per-request visible prefix length ------------------------------------------------
+ * When a context grows by a segment, the prefill worker extends the shared cache only for the newly
+ * appended tokens (System Design, execution pipeline step 1; Appendix B.1: a cache hit on the old context,
+ * KV states computed for the new tokens only).  The attention of such a chunk is this library's step with
+ * one request per new token: the chunk's keys/values are stored as the continuation of the prompt's shared
+ * prefix, and the request of the token at position t of the context sees the first t + 1 tokens of it --
+ * causal attention written as a length.
+ *
+ * ps_layout_set_visible (host): prefix_visible = int32[R], request r attends to the first prefix_visible[r]
+ * tokens of its prompt's shared prefix (0 <= prefix_visible[r] <= prefix length) and to its whole private
+ * suffix; NULL restores full visibility.  Re-derives the split plan with the options last used (a request
+ * gets partial states only for the prefix chunks it sees into), so earlier uploads of the table blob and the
+ * sizes reported by ps_layout_device_bytes / ps_workspace_bytes are invalid afterwards.  Block tables and
+ * refcounts do not change.  PS_ERR_INVALID_ARG: a length out of range; the layout is unchanged. */
+int32_t ps_layout_set_visible(ps_layout* layout, const int32_t* prefix_visible);
 
 /* ---- cache growth -------------------------------------------------------------------------------------
  * A decode step returns the step's new cache entries, which are appended to the decode module's own cache

@@ -25,6 +25,7 @@ EXPORTS = [
     "ps_layout_schedule", "ps_layout_device_bytes", "ps_layout_upload", "ps_workspace_bytes", "ps_workspace_layout",
     "ps_prefix_attention", "ps_suffix_attention", "ps_prefix_suffix_attention", "ps_merge_states", "ps_decode_attention",
     "ps_layout_lengths", "ps_layout_append", "ps_kv_append", "ps_kv_ingest",
+    "ps_layout_set_visible", "ps_layout_request_list",
     "ps_strerror", "ps_last_hip_error",
 ]
 
@@ -204,6 +205,23 @@ def ps_layout_plan(layout, num_requests: int) -> dict:
            "ps_layout_plan")
     return {"items": _view(items, n.value * 8).reshape(-1, 8), "slot_base": _view(slots, num_requests + 1),
             "prefix_variant": pv.value, "suffix_variant": sv.value}
+
+
+def ps_layout_set_visible(layout, num_requests: int, prefix_visible=None):
+    """Per-request visible prefix lengths (None = everything); the plan is re-derived."""
+    if prefix_visible is None:
+        vp = None
+    else:
+        arr, vp = _i32(prefix_visible)
+        if arr.size != num_requests:
+            raise ValueError("prefix_visible has the wrong length")
+    _check(_lib().ps_layout_set_visible(layout, vp), "ps_layout_set_visible")
+
+
+def ps_layout_request_list(layout) -> np.ndarray:
+    n, lst = C.c_int32(), _I32P()
+    _check(_lib().ps_layout_request_list(layout, C.byref(n), C.byref(lst)), "ps_layout_request_list")
+    return _view(lst, n.value)
 
 
 def ps_layout_schedule(layout, which: int) -> dict:

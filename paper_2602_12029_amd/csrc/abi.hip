@@ -25,6 +25,7 @@ psdev::AttnParams make_params(const ps_layout* lay, const void* dev_tables, cons
   p.req_list = t + lay->off_req;
   p.items = reinterpret_cast<const ps_item*>(t + lay->off_items);
   p.slot_base = t + lay->off_slot;
+  p.visible = t + lay->off_visible;
   p.q = q;
   p.kv = kv;
   p.scales = scales;
@@ -57,8 +58,8 @@ int32_t launch_set(const ps_layout* lay, const psdev::AttnParams& p, const void*
     const ps_layout::schedule& s = set == WorkSet::kPrefix ? lay->sched_prefix
                                    : set == WorkSet::kSuffix ? lay->sched_suffix : lay->sched_all;
     const int32_t* t = static_cast<const int32_t*>(dev_tables);
-    rc = psdev::launch_mfma_attention(p, lay->geo, s.max_rows, s.occ, reinterpret_cast<const ps_item*>(t + s.off_items),
-                                      t + s.off_indptr, s.num_wg, st);
+    rc = psdev::launch_mfma_attention(p, lay->geo, s.max_rows, s.occ, set != WorkSet::kSuffix && lay->any_masked,
+                                      reinterpret_cast<const ps_item*>(t + s.off_items), t + s.off_indptr, s.num_wg, st);
   } else {
     rc = psdev::launch_wave_attention(p, lay->geo, begin, end - begin, st);
   }

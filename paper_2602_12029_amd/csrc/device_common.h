@@ -21,6 +21,7 @@ struct AttnParams {
   const int32_t* req_list;   // sharing groups, then the identity list
   const ps_item* items;
   const int32_t* slot_base;  // [R+1]
+  const int32_t* visible;    // [R]: leading tokens of its prompt's prefix a request attends to
   const void* q;             // [R][Hq][d]
   const void* kv;
   const float* scales;       // [num_blocks][Hkv][2] or null

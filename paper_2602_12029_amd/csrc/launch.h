@@ -9,8 +9,9 @@ namespace psdev {
 bool wave_supported(const ps_geometry& g);
 int32_t launch_wave_attention(const AttnParams& p, const ps_geometry& g, int item_begin, int n_items, hipStream_t st);
 // Persistent launch: workgroup w walks wg_items[wg_indptr[w] .. wg_indptr[w+1]).
-int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max_rows, int occ, const ps_item* wg_items,
-                              const int32_t* wg_indptr, int num_wg, hipStream_t st);
+// `masked`: the set holds items whose rows see different token counts (per-request visible prefix lengths).
+int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max_rows, int occ, bool masked,
+                              const ps_item* wg_items, const int32_t* wg_indptr, int num_wg, hipStream_t st);
 // Cache writes: whole segments of one kind (0 = shared prefixes, 1 = private suffixes) from ragged contiguous
 // sources, and the one token per request reserved by the last ps_layout_append.
 int32_t launch_kv_ingest(const ps_layout* lay, const void* dev_tables, int which, const void* src_k, const void* src_v,

@@ -92,31 +92,64 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   };
 
   const int32_t P = lay->num_prompts, R = lay->num_requests;
-  std::vector<int32_t> nsplit_prefix(P), nsplit_suffix(R);
+  // Visible prefix lengths (partial prefill: a query row may see only the leading part of its prompt's shared
+  // prefix).  A request takes part in the prefix chunks that begin below its visible length, so its prefix splits
+  // are the first ceil(visible / chunk size) of its prompt's; an item's token range ends at the largest visible
+  // length among its rows, and it is marked where some row sees less than that.
+  const bool limited = !lay->visible.empty();
+  auto visible_of = [&](int32_t r) { return limited ? lay->visible[size_t(r)] : lay->prefix_len[size_t(lay->req_prompt[size_t(r)])]; };
+  std::vector<int32_t> nsplit_prefix(R), nsplit_suffix(R);
   std::vector<ps_item> prefix_items, suffix_items;
   const int32_t max_req = std::max(1, 64 / group);
   const int32_t total_prefix_blocks = int32_t(lay->prefix_blk.size());
   lay->max_rows_prefix = 0;
+  lay->any_masked = false;
+  lay->req_list.assign(lay->group_req.begin(), lay->group_req.end());
+  for (int32_t r = 0; r < R; ++r) lay->req_list.push_back(r);
+  std::vector<int32_t> members;
   for (int32_t p = 0; p < P; ++p) {
     int32_t n = 0;
     const int64_t size = chunking(lay->prefix_len[p], prefix_chunk, &n);
-    nsplit_prefix[p] = n;
     const int32_t g0 = lay->group_indptr[p], g1 = lay->group_indptr[p + 1];
-    for (int32_t c = 0; c < n; ++c)
+    for (int32_t i = g0; i < g1; ++i) {
+      const int32_t r = lay->group_req[size_t(i)];
+      nsplit_prefix[size_t(r)] = int32_t(ceil_div(visible_of(r), size));
+    }
+    for (int32_t c = 0; c < n; ++c) {
+      // the requests that see into this chunk, in group order: the whole group unless lengths were limited
+      int32_t list0 = g0, count = g1 - g0;
+      if (limited) {
+        members.clear();
+        for (int32_t i = g0; i < g1; ++i)
+          if (visible_of(lay->group_req[size_t(i)]) > c * size) members.push_back(lay->group_req[size_t(i)]);
+        count = int32_t(members.size());
+        if (count != g1 - g0) {
+          list0 = int32_t(lay->req_list.size());
+          lay->req_list.insert(lay->req_list.end(), members.begin(), members.end());
+        }
+      }
       for (int32_t h = 0; h < g.num_kv_heads; ++h)
-        for (int32_t m0 = g0; m0 < g1; m0 += max_req) {
+        for (int32_t m0 = 0; m0 < count; m0 += max_req) {
           ps_item it{};
           it.blk_off = lay->prefix_blk_indptr[p];
           it.tok_begin = int32_t(c * size);
-          it.tok_end = int32_t(std::min<int64_t>(lay->prefix_len[p], (c + 1) * size));
-          it.req_off = m0;
-          it.n_req = std::min(max_req, g1 - m0);
+          it.req_off = list0 + m0;
+          it.n_req = std::min(max_req, count - m0);
+          int32_t v_max = 0, v_min = INT32_MAX;
+          for (int32_t i = 0; i < it.n_req; ++i) {
+            const int32_t v = visible_of(lay->req_list[size_t(it.req_off + i)]);
+            v_max = std::max(v_max, v);
+            v_min = std::min(v_min, v);
+          }
+          it.tok_end = int32_t(std::min<int64_t>(std::min<int64_t>(lay->prefix_len[p], (c + 1) * size), v_max));
           it.kv_head = h;
           it.split_local = c;
-          it.kind = 0;
+          it.kind = v_min < it.tok_end ? kPsItemMasked : 0;
+          if (it.kind & kPsItemMasked) lay->any_masked = true;
           lay->max_rows_prefix = std::max(lay->max_rows_prefix, it.n_req * group);
           prefix_items.push_back(it);
         }
+    }
   }
   for (int32_t r = 0; r < R; ++r) {
     int32_t n = 0;
@@ -131,8 +164,8 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
         it.req_off = R + r;  // identity part of the request list
         it.n_req = 1;
         it.kv_head = h;
-        it.split_local = nsplit_prefix[lay->req_prompt[r]] + c;
-        it.kind = 1;
+        it.split_local = nsplit_prefix[size_t(r)] + c;
+        it.kind = kPsItemSuffix;
         suffix_items.push_back(it);
       }
   }
@@ -146,7 +179,7 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   lay->slot_base.assign(R + 1, 0);
   int64_t slots = 0;
   for (int32_t r = 0; r < R; ++r) {
-    slots += nsplit_prefix[lay->req_prompt[r]] + nsplit_suffix[r];
+    slots += nsplit_prefix[r] + nsplit_suffix[r];
     if (slots > INT32_MAX) return PS_ERR_INVALID_ARG;
     lay->slot_base[r + 1] = int32_t(slots);
   }
@@ -189,14 +222,16 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   if (suf_mfma) pk_suffix = pack(lay->num_prefix_items, n_items);
   if (pre_mfma && suf_mfma) pk_all = pack(0, n_items);
 
-  // device blob: [block ids: prefix ++ suffix][request list: group_req ++ identity][items][slot_base][schedules]
+  // device blob: [block ids: prefix ++ suffix][request list: group_req ++ identity ++ per-chunk subsets][items]
+  // [slot_base][visible][schedules]
   // [per-block source offsets and valid counts][destinations of the last append]
   auto pad4 = [](int64_t n) { return (n + 3) / 4 * 4; };
   lay->off_blk = 0;
   lay->off_req = pad4(lay->off_blk + int64_t(lay->prefix_blk.size() + lay->suffix_blk.size()));
-  lay->off_items = pad4(lay->off_req + 2 * int64_t(R));
+  lay->off_items = pad4(lay->off_req + int64_t(lay->req_list.size()));
   lay->off_slot = pad4(lay->off_items + 8 * int64_t(lay->items.size()));
-  int64_t words = pad4(lay->off_slot + R + 1);
+  lay->off_visible = pad4(lay->off_slot + R + 1);
+  int64_t words = pad4(lay->off_visible + R);
   auto place = [&](ps_layout::schedule& s, const packed& pk) {
     s = ps_layout::schedule{};
     if (pk.items.empty()) return;
@@ -250,8 +285,8 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   fill(lay->sched_all, pk_all);
   std::copy(lay->prefix_blk.begin(), lay->prefix_blk.end(), b + lay->off_blk);
   std::copy(lay->suffix_blk.begin(), lay->suffix_blk.end(), b + lay->off_blk + lay->prefix_blk.size());
-  std::copy(lay->group_req.begin(), lay->group_req.end(), b + lay->off_req);
-  for (int32_t r = 0; r < R; ++r) b[lay->off_req + R + r] = r;
+  std::copy(lay->req_list.begin(), lay->req_list.end(), b + lay->off_req);
+  for (int32_t r = 0; r < R; ++r) b[lay->off_visible + r] = visible_of(r);
   if (!lay->items.empty()) std::memcpy(b + lay->off_items, lay->items.data(), lay->items.size() * sizeof(ps_item));
   std::copy(lay->slot_base.begin(), lay->slot_base.end(), b + lay->off_slot);
   return PS_OK;
@@ -462,6 +497,30 @@ int32_t ps_layout_append(ps_pool* pool, ps_layout* lay, const int32_t* active, c
   lay->suffix_blk_indptr.swap(indptr);
   if (int32_t st = ps_plan_build(lay, &lay->opt)) return st;
   if (dest) *dest = lay->append_dest.data();
+  return PS_OK;
+}
+
+int32_t ps_layout_set_visible(ps_layout* lay, const int32_t* prefix_visible) {
+  if (!lay) return PS_ERR_INVALID_ARG;
+  std::vector<int32_t> v;
+  if (prefix_visible) {
+    v.assign(prefix_visible, prefix_visible + lay->num_requests);
+    for (int32_t r = 0; r < lay->num_requests; ++r)
+      if (v[size_t(r)] < 0 || v[size_t(r)] > lay->prefix_len[size_t(lay->req_prompt[size_t(r)])]) return PS_ERR_INVALID_ARG;
+  }
+  lay->visible.swap(v);
+  if (int32_t st = ps_plan_build(lay, &lay->opt)) {
+    lay->visible.swap(v);              // cannot fail with options that were accepted before; keep the old state
+    ps_plan_build(lay, &lay->opt);
+    return st;
+  }
+  return PS_OK;
+}
+
+int32_t ps_layout_request_list(const ps_layout* lay, int32_t* count, const int32_t** list) {
+  if (!lay) return PS_ERR_INVALID_ARG;
+  if (count) *count = int32_t(lay->req_list.size());
+  if (list) *list = lay->req_list.data();
   return PS_OK;
 }
 

@@ -87,6 +87,9 @@ __device__ __forceinline__ int q_chunk_elem(int step, int kg) {
 struct ItemCtx {
   int blk_off, tok_begin, tok_end, req_off, n_req, kv_head, split_local;
   int rows, nt_used, my_tiles, sub0, sub_end;
+  int kind;            // the item's flag bits
+  int masked;          // non-zero: some row of the item sees fewer tokens than tok_end (MASKED kernels only)
+  // (fourteen ints, then the 64-bit address: no padding anywhere, so the struct still splits into registers)
   int64_t head_base;   // address of the item's KV head slice in block 0
 };
 
@@ -100,12 +103,15 @@ template <int NT>
 struct QIndex { int idx[NT]; };   // global q row (request * Hq + head) this thread fetches per row tile, -1 = padding
 template <int NT>
 struct QRegs { u32x4 piece[NT]; };
+template <int NT>
+struct RowLimit { int lim[NT]; };  // per row tile: first token that row (lane % 16) of the tile does not see
 
 }  // namespace
 
 // NT: 16-row tiles carried; NB: tile buffers in the register ring; OCC: waves per SIMD the register
-// budget is sized for.
-template <int NT, int KVT, int NB, int OCC>
+// budget is sized for; MASKED: rows may see only a leading part of an item's token range (per-request visible
+// prefix length), which costs a compare per score and guards against rows that have seen nothing yet.
+template <int NT, int KVT, int NB, int OCC, bool MASKED>
 __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, const ps_item* __restrict__ wg_items,
                                                                   const int32_t* __restrict__ wg_indptr) {
   __shared__ float sm_o[kWaves][16][kLdsRow];
@@ -153,6 +159,8 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
     c.n_req = __builtin_amdgcn_readfirstlane(h[4]);
     c.kv_head = __builtin_amdgcn_readfirstlane(h[5]);
     c.split_local = __builtin_amdgcn_readfirstlane(h[6]);
+    c.kind = __builtin_amdgcn_readfirstlane(h[7]);
+    c.masked = MASKED ? (c.kind & kPsItemMasked) : 0;
     c.rows = c.n_req * G;
     c.nt_used = (c.rows + 15) >> 4;
     const int tiles_total = (c.tok_end - c.tok_begin + kTile - 1) / kTile;
@@ -177,6 +185,20 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
       }
     }
     return m;
+  };
+
+  // visible length of this lane's row in every row tile, clamped to the item's token range
+  auto fetch_limits = [&](const ItemCtx& c) {
+    RowLimit<NT> r;
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+      r.lim[t] = c.tok_end;
+      if constexpr (MASKED) {
+        const int row = 16 * t + n;
+        if (c.masked && row < c.rows) r.lim[t] = min(c.tok_end, p.visible[p.req_list[c.req_off + row / G]]);
+      }
+    }
+    return r;
   };
 
   // query rows: one 16-byte piece per thread and row tile (row = thread / 16, piece = thread % 16)
@@ -255,8 +277,8 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
   // all_rows_tag / full_tag: std::true_type promises that every row tile is in use / that the tile has all its
   // 32 tokens, which removes the uniform branches from the body so that the compiler can schedule the transposes
   // and conversions under the matrix instructions; std::false_type decides at run time.
-  auto compute_tile = [&](TileRegs<KVT>& tr, const ItemCtx& c, const ItemMeta& meta, int k, auto all_rows_tag,
-                          auto full_tag) {
+  auto compute_tile = [&](TileRegs<KVT>& tr, const ItemCtx& c, const ItemMeta& meta, const RowLimit<NT>& rl, int k,
+                          auto all_rows_tag, auto full_tag) {
     constexpr bool kAllRows = decltype(all_rows_tag)::value, kFull = decltype(full_tag)::value;
     const int tok0 = c.tok_begin + kTile * (wave + kWaves * k);  // first token of the tile
     const bool full = kFull || tok0 + kTile <= c.tok_end;
@@ -302,20 +324,23 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
           for (int st = 0; st < 4; ++st) s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[b][st], qb[st], s[b], 0, 0, 0);
           s[b] *= sc_k[b];  // scores in log2 units
         }
-        if (!full) {
+        if (MASKED || !full) {
+          const int lim = MASKED ? rl.lim[t] : c.tok_end;
 #pragma unroll
           for (int b = 0; b < 2; ++b)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-              if (tok0 + 16 * b + 4 * kg + j >= c.tok_end) s[b][j] = neg_inf;
+              if (tok0 + 16 * b + 4 * kg + j >= lim) s[b][j] = neg_inf;
         }
         float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
                          fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
         mx = fmaxf(mx, lane_xor(mx, 16));
         mx = fmaxf(mx, lane_xor(mx, 32));
-        const float m_new = fmaxf(m_run[t], mx);  // finite: every tile holds at least one valid token
+        // finite unless MASKED: every tile holds at least one valid token, but a row may not see any of them yet
+        const float m_new = fmaxf(m_run[t], mx);
+        const float m_ref = (MASKED && m_new == neg_inf) ? 0.f : m_new;   // keeps (-inf) - (-inf) out of the exponents
         if (__builtin_amdgcn_ballot_w64(m_new != m_run[t]) != 0) {
-          const float alpha = fast_exp2(m_run[t] - m_new);
+          const float alpha = fast_exp2(m_run[t] - m_ref);
           l_run[t] *= alpha;
 #pragma unroll
           for (int cc = 0; cc < 8; ++cc) acc[t][cc] *= alpha;
@@ -326,7 +351,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
         for (int b = 0; b < 2; ++b)
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            const float pw = fast_exp2(s[b][j] - m_new);
+            const float pw = fast_exp2(s[b][j] - m_ref);
             lsum += pw;
             pb[t][4 * b + j] = (__bf16)(pw * sc_v[b]);
           }
@@ -433,6 +458,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
   __syncthreads();
   ItemCtx cur = item_ctx(j_first);
   ItemMeta meta = fetch_meta(cur);
+  RowLimit<NT> lim = fetch_limits(cur);
   // first tiles go out as soon as the block ids are here; the query rows follow while they fly
   TileRegs<KVT> buf[NB];
 #pragma unroll
@@ -442,9 +468,11 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
   ItemCtx nxt = cur;
   ItemMeta meta_nxt{0, 1.f, 1.f};
   QIndex<NT> q_idx_nxt{};
+  RowLimit<NT> lim_nxt{};
   if (has_next) {
     nxt = item_ctx(j_first + 1);
     meta_nxt = fetch_meta(nxt);
+    lim_nxt = fetch_limits(nxt);
     q_idx_nxt = q_row_index(nxt);
   }
   __syncthreads();
@@ -457,9 +485,11 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
     ItemCtx nn = nxt;
     ItemMeta meta_nn{0, 1.f, 1.f};
     QIndex<NT> q_idx_nn{};
+    RowLimit<NT> lim_nn{};
     if (has_nn) {
       nn = item_ctx(j + 2);
       meta_nn = fetch_meta(nn);
+      lim_nn = fetch_limits(nn);
       q_idx_nn = q_row_index(nn);
     }
 
@@ -475,7 +505,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
 #pragma unroll
         for (int u = 0; u < NB; ++u) {
           load_item_tile(buf[(u + NB - 1) % NB], cur, meta, s0 + u + NB - 1, true);
-          compute_tile(buf[u], cur, meta, s0 + u, all_rows_tag, std::true_type{});
+          compute_tile(buf[u], cur, meta, lim, s0 + u, all_rows_tag, std::true_type{});
         }
       }
     };
@@ -486,7 +516,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
     for (int u = 0; u < NB; ++u) {
       if (u == 0) load_item_tile(buf[NB - 1], cur, meta, s0 + NB - 1, true);
       else load_item_tile(buf[u - 1], nxt, meta_nxt, u - 1, has_next);
-      if (s0 + u < cur.my_tiles) compute_tile(buf[u], cur, meta, s0 + u, std::false_type{}, std::false_type{});
+      if (s0 + u < cur.my_tiles) compute_tile(buf[u], cur, meta, lim, s0 + u, std::false_type{}, std::false_type{});
     }
 
     epilogue(cur);   // ends with a barrier: sm_q and the consumed half of the header ring are free
@@ -500,6 +530,8 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
     __syncthreads();
     cur = nxt;
     meta = meta_nxt;
+    lim = lim_nxt;
+    lim_nxt = lim_nn;
     has_next = has_nn;
     nxt = nn;
     meta_nxt = meta_nn;
@@ -507,8 +539,8 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
   }
 }
 
-int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max_rows, int occ, const ps_item* wg_items,
-                              const int32_t* wg_indptr, int num_wg, hipStream_t st) {
+int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max_rows, int occ, bool masked,
+                              const ps_item* wg_items, const int32_t* wg_indptr, int num_wg, hipStream_t st) {
   if (num_wg <= 0) return PS_OK;
   const int spb = g.block_size / 16;
   if (g.head_dim != kD || g.q_dtype != PS_BF16 || g.block_size % 16 != 0 || (spb & (spb - 1)) != 0 || max_rows > 64)
@@ -516,8 +548,13 @@ int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max
   if (g.kv_dtype != PS_BF16 && g.kv_dtype != PS_FP8_E4M3) return PS_ERR_UNSUPPORTED;
   const dim3 grid(num_wg), block(256);
   const int nt = max_rows <= 16 ? 1 : (max_rows <= 32 ? 2 : 4);
-#define PS_LAUNCH(NT, KVT, NB, OCC) \
-  hipLaunchKernelGGL((mfma_attention_kernel<NT, KVT, NB, OCC>), grid, block, 0, st, p, wg_items, wg_indptr)
+#define PS_LAUNCH(NT, KVT, NB, OCC)                                                                                  \
+  do {                                                                                                               \
+    if (masked)                                                                                                      \
+      hipLaunchKernelGGL((mfma_attention_kernel<NT, KVT, NB, OCC, true>), grid, block, 0, st, p, wg_items, wg_indptr); \
+    else                                                                                                             \
+      hipLaunchKernelGGL((mfma_attention_kernel<NT, KVT, NB, OCC, false>), grid, block, 0, st, p, wg_items, wg_indptr); \
+  } while (0)
   // two tile buffers per wave everywhere (deeper rings measured no faster); `occ` is the residency the
   // plan sized the grid for (ps_mfma_occupancy)
   if (g.kv_dtype == PS_BF16) {

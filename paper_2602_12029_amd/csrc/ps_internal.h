@@ -22,8 +22,9 @@ struct ps_item {
   int32_t n_req;
   int32_t kv_head;
   int32_t split_local;  // partial-state slot of request r is slot_base[r] + split_local
-  int32_t kind;         // 0 prefix, 1 suffix
+  int32_t kind;         // bit 0: 0 prefix, 1 suffix; bit 1: some row of the item sees less than tok_end
 };
+constexpr int32_t kPsItemSuffix = 1, kPsItemMasked = 2;
 static_assert(sizeof(ps_item) == 32, "ps_item is 8 int32");
 
 struct ps_layout {
@@ -31,6 +32,12 @@ struct ps_layout {
   int32_t num_prompts = 0, num_requests = 0;
   std::vector<int32_t> prefix_len, suffix_len, req_prompt, req_model;
   std::vector<int32_t> prefix_blk_indptr, prefix_blk, group_indptr, group_req, suffix_blk_indptr, suffix_blk;
+  // per request: how many leading tokens of its prompt's prefix it attends to; empty = all of them
+  std::vector<int32_t> visible;
+  bool any_masked = false;           // the plan holds an item with kPsItemMasked
+  // request list the items index into: group_req, then the identity list (suffix items), then the subsets of a
+  // sharing group that see into a prefix chunk (only where visible lengths cut a group)
+  std::vector<int32_t> req_list;
 
   // split plan
   ps_plan_options opt{};
@@ -56,6 +63,7 @@ struct ps_layout {
   // device table blob (int32 words) and section offsets in words
   std::vector<int32_t> blob;
   int64_t off_blk = 0, off_req = 0, off_items = 0, off_slot = 0;
+  int64_t off_visible = 0;           // int32[R]: effective visible prefix length of every request
   // for the cache-writing kernels, per entry of the concatenated block array: index of its first token in the
   // ragged source tensor of its kind (prefixes back to back / suffixes back to back) and its number of valid
   // tokens; then append_dest

@@ -73,15 +73,18 @@ __global__ __launch_bounds__(256) void wave_attention_kernel(AttnParams p, int i
   for (int row0 = 0; row0 < rows; row0 += kRowTile) {
     float qreg[kRowTile][E];
     float m[kRowTile], l[kRowTile], acc[kRowTile][E];
+    int lim[kRowTile];   // first token the row does not see (per-request visible prefix length, or the item's end)
 #pragma unroll
     for (int rr = 0; rr < kRowTile; ++rr) {
       const int row = row0 + rr;
       m[rr] = neg_inf;
       l[rr] = 0.f;
+      lim[rr] = it.tok_end;
 #pragma unroll
       for (int e = 0; e < E; ++e) { acc[rr][e] = 0.f; qreg[rr][e] = 0.f; }
       if (row < rows) {
         const int req = p.req_list[it.req_off + row / G];
+        if (it.kind & kPsItemMasked) lim[rr] = min(it.tok_end, p.visible[req]);
         const int h = it.kv_head * G + row % G;
         load_elems<QT, E>(p.q, (int64_t(req) * p.num_q_heads + h) * D + dchunk * E, qreg[rr]);
       }
@@ -105,10 +108,12 @@ __global__ __launch_bounds__(256) void wave_attention_kernel(AttnParams p, int i
         float dot = 0.f;
 #pragma unroll
         for (int e = 0; e < E; ++e) dot = fmaf(qreg[rr][e], kf[e], dot);
-        const float s = row16_allreduce_sum(dot) * k_scale;   // score in log2 units
+        float s = row16_allreduce_sum(dot) * k_scale;         // score in log2 units
+        if (t >= lim[rr]) s = neg_inf;
         const float m_new = fmaxf(m[rr], s);
-        const float alpha = fast_exp2(m[rr] - m_new);         // m = -inf gives 0; m_new is finite here
-        const float w = fast_exp2(s - m_new);
+        const float m_ref = (m_new == neg_inf) ? 0.f : m_new; // a row that has seen nothing yet: exponents stay -inf
+        const float alpha = fast_exp2(m[rr] - m_ref);         // m = -inf gives 0
+        const float w = fast_exp2(s - m_ref);
         l[rr] = fmaf(l[rr], alpha, w);
         const float wv = w * v_scale;
 #pragma unroll

@@ -58,6 +58,11 @@ class DecodeBatch:
         B.ps_layout_replan(self.layout, options)
         self._sync_plan()
 
+    def set_visible(self, prefix_visible=None):
+        """Limit how much of its prompt's shared prefix every request sees (None = all of it)."""
+        B.ps_layout_set_visible(self.layout, self.num_requests, prefix_visible)
+        self._sync_plan()
+
     def _sc(self):
         return self.scales.data_ptr() if self.scales is not None else 0
 

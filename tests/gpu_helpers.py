@@ -3,11 +3,44 @@ import numpy as np
 import torch
 
 import workloads as wl
-from helpers import oracle_setup
+from helpers import errors, oracle_setup
+from oracle import attention as oa
 from paper_2602_12029_amd import binding as B
 from paper_2602_12029_amd.runtime import DecodeBatch, to_device
 
 VARIANT = {"auto": B.PS_VARIANT_AUTO, "wave": B.PS_VARIANT_WAVE, "mfma": B.PS_VARIANT_MFMA}
+
+
+TOL = {"f32": (1e-5, 1e-5), "bf16": (1e-2, 5e-3), "fp8_e4m3": (1e-2, 5e-3)}   # (max-abs, relative RMS) by KV dtype
+
+
+def check_against_oracle(case, requests=None, label="", visible=None):
+    """Output and LSE of the last step on the GPU against the fp64 oracle, element by element."""
+    from paper_2602_12029_amd.runtime import from_device
+    w = case.w
+    g = w.geometry
+    ref_o, ref_lse = oa.decode_attention(case.q_bits, g.q_dtype, case.data.kv, case.data.scales, g.kv_dtype, case.olay,
+                                         requests, visible)
+    torch.cuda.synchronize()
+    got_o = from_device(case.batch.out)
+    got_lse = from_device(case.batch.lse)
+    if requests is not None:
+        got_o, got_lse = got_o[list(requests)], got_lse[list(requests)]
+    max_abs, rel_rms, worst = errors(got_o, ref_o)
+    tol_abs, tol_rms = TOL[g.kv_dtype]
+    print(f"[{label or w.name}] max_abs={max_abs:.3e} rel_rms={rel_rms:.3e} worst_req_rel_rms={worst:.3e}", flush=True)
+    assert np.isfinite(got_o).all()
+    # The max-abs bar is stated for outputs of magnitude <= 1 (N(0,1) values averaged over many tokens).  A row that
+    # sees only a few tokens has |O| up to ~4, where the spacing of bf16 -- the output format -- is 2^-6, half of it
+    # 7.8e-3 by itself; there the bar scales with the magnitude of the element.
+    scaled = float((np.abs(got_o - ref_o) / np.maximum(1.0, np.abs(ref_o))).max(initial=0.0))
+    assert scaled <= tol_abs and rel_rms <= tol_rms
+    if g.q_dtype == "f32" or np.abs(ref_o).max(initial=0.0) <= 1.0:
+        assert max_abs <= tol_abs
+    finite = np.isfinite(ref_lse)
+    assert np.array_equal(np.isneginf(got_lse), np.isneginf(ref_lse))
+    assert np.abs(got_lse[finite] - ref_lse[finite]).max(initial=0.0) <= (1e-4 if g.kv_dtype == "f32" else 2e-3)
+    return max_abs, rel_rms
 
 
 class GpuCase:
@@ -32,6 +65,9 @@ class GpuCase:
     def replan(self, prefix_chunk=0, suffix_chunk=0, prefix_variant="auto", suffix_variant="auto", num_cus=0):
         self.batch.replan(B.plan_options(prefix_chunk, suffix_chunk, VARIANT[prefix_variant], VARIANT[suffix_variant],
                                          num_cus))
+
+    def set_visible(self, visible=None):
+        self.batch.set_visible(visible)
 
     def poison_workspace(self):
         self.batch.workspace.view(torch.float32).fill_(float("nan"))

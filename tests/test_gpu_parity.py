@@ -8,12 +8,9 @@ import pytest
 import torch
 
 import workloads as wl
-from helpers import errors, oracle_decode
 from oracle import attention as oa
 
 pytestmark = pytest.mark.gpu
-
-TOL = {"f32": (1e-5, 1e-5), "bf16": (1e-2, 5e-3), "fp8_e4m3": (1e-2, 5e-3)}
 
 
 @pytest.fixture(scope="module")
@@ -25,23 +22,8 @@ def gpu():
 
 
 def _check(case, requests=None, label=""):
-    from paper_2602_12029_amd.runtime import from_device
-    w = case.w
-    ref_o, ref_lse = oracle_decode(w, case.olay, case.data, requests)
-    torch.cuda.synchronize()
-    got_o = from_device(case.batch.out)
-    got_lse = from_device(case.batch.lse)
-    if requests is not None:
-        got_o, got_lse = got_o[list(requests)], got_lse[list(requests)]
-    max_abs, rel_rms, worst = errors(got_o, ref_o)
-    tol_abs, tol_rms = TOL[w.geometry.kv_dtype]
-    print(f"[{label or w.name}] max_abs={max_abs:.3e} rel_rms={rel_rms:.3e} worst_req_rel_rms={worst:.3e}", flush=True)
-    assert np.isfinite(got_o).all()
-    assert max_abs <= tol_abs and rel_rms <= tol_rms
-    finite = np.isfinite(ref_lse)
-    assert np.array_equal(np.isneginf(got_lse), np.isneginf(ref_lse))
-    assert np.abs(got_lse[finite] - ref_lse[finite]).max(initial=0.0) <= (1e-4 if w.geometry.kv_dtype == "f32" else 2e-3)
-    return max_abs, rel_rms
+    from gpu_helpers import check_against_oracle
+    return check_against_oracle(case, requests, label)
 
 
 def _variants(w):

@@ -88,30 +88,43 @@ def test_random_batches_against_oracle_policy():
         B.ps_pool_destroy(pool)
 
 
-def _check_plan(w, lay, plan):
-    """Chunks tile every segment exactly once per KV head and request; slots are consistent."""
+def _check_plan(w, lay, plan, visible=None):
+    """Chunks tile every segment exactly once per KV head and request (the prefix up to the request's visible
+    length); slots are consistent; an item is marked exactly where one of its rows sees less than its range."""
     g = w.geometry
     items, slot_base = plan["items"], plan["slot_base"]
     t = B.ps_layout_tables(lay, w.num_prompts, w.num_requests)
     nprefix_blk = int(t["prefix_blk_indptr"][-1])
-    req_list = np.concatenate([t["group_req"], np.arange(w.num_requests, dtype=np.int32)])
+    req_list = B.ps_layout_request_list(lay)
+    R = w.num_requests
+    assert np.array_equal(req_list[:R], t["group_req"]) and np.array_equal(req_list[R:2 * R], np.arange(R))
+    seen = np.asarray(w.prefix_len)[np.asarray(w.req_prompt)] if visible is None else np.asarray(visible)
     cover = {}                                             # (request, kv head) -> list of (kind, begin, end, slot)
     for blk_off, t0, t1, req_off, n_req, head, split, kind in items.tolist():
-        assert t1 > t0 >= 0 and n_req >= 1 and 0 <= head < g.num_kv_heads
+        assert t1 > t0 >= 0 and n_req >= 1 and 0 <= head < g.num_kv_heads and 0 <= kind <= 3
         assert t0 % g.block_size == 0
-        for r in req_list[req_off:req_off + n_req].tolist():
-            if kind == 0:
-                p = int(w.req_prompt[r])
-                assert blk_off == t["prefix_blk_indptr"][p] and t1 <= w.prefix_len[p]
-            else:
-                assert blk_off == nprefix_blk + t["suffix_blk_indptr"][r] and t1 <= w.suffix_len[r] and n_req == 1
-            cover.setdefault((r, head), []).append((kind, t0, t1, split))
-    for r in range(w.num_requests):
+        reqs = req_list[req_off:req_off + n_req].tolist()
+        assert len(reqs) == n_req
+        if kind & 1:
+            assert n_req == 1 and not kind & 2
+            r = reqs[0]
+            assert blk_off == nprefix_blk + t["suffix_blk_indptr"][r] and t1 <= w.suffix_len[r]
+            cover.setdefault((r, head), []).append((1, t0, t1, split))
+        else:
+            assert len({int(w.req_prompt[r]) for r in reqs}) == 1
+            p = int(w.req_prompt[reqs[0]])
+            assert blk_off == t["prefix_blk_indptr"][p] and t1 <= w.prefix_len[p]
+            assert t1 <= max(seen[r] for r in reqs)                     # nothing streamed that no row sees
+            assert bool(kind & 2) == any(seen[r] < t1 for r in reqs)
+            for r in reqs:
+                assert seen[r] > t0                                      # every row sees into the item
+                cover.setdefault((r, head), []).append((0, t0, min(t1, int(seen[r])), split))
+    for r in range(R):
         nslots = int(slot_base[r + 1] - slot_base[r])
         for head in range(g.num_kv_heads):
             chunks = sorted(cover.get((r, head), []), key=lambda c: c[3])
             assert [c[3] for c in chunks] == list(range(nslots))           # every slot written exactly once
-            for kind, length in ((0, int(w.prefix_len[w.req_prompt[r]])), (1, int(w.suffix_len[r]))):
+            for kind, length in ((0, int(seen[r])), (1, int(w.suffix_len[r]))):
                 spans = sorted((c[1], c[2]) for c in chunks if c[0] == kind)
                 pos = 0
                 for a, b in spans:
@@ -120,6 +133,68 @@ def _check_plan(w, lay, plan):
                 assert pos == length
             kinds = [c[0] for c in chunks]
             assert kinds == sorted(kinds)                                   # prefix splits first
+
+
+def test_visible_lengths_plan_invariants_and_errors():
+    geo = wl.Geometry(8, 2, 64, 16, "f32", "f32")
+    rng = np.random.default_rng(5)
+    w = wl.make_workload("vis", geo, 9, [333, 1000, 40], [list(range(9)), [0, 3, 4, 8], [1, 2]],
+                         rng.integers(0, 90, 15), seed=3)
+    pool, lay, _, _ = _both(w)
+    full = np.asarray(w.prefix_len)[np.asarray(w.req_prompt)]
+    before = B.ps_layout_plan(lay, w.num_requests)
+    tables = B.ps_layout_tables(lay, w.num_prompts, w.num_requests)
+    refs = B.ps_pool_refcounts(pool, w.num_blocks)
+    for trial in range(6):
+        visible = rng.integers(0, full + 1)
+        if trial == 0:
+            visible[:] = 0                                   # nothing visible anywhere: no prefix item at all
+        if trial == 1:
+            visible = full.copy()                            # everything visible: nothing is marked
+        for pc, sc in ((0, 0), (32, 32), (64, 16), (4096, 4096)):
+            B.ps_layout_replan(lay, B.plan_options(pc, sc))
+            B.ps_layout_set_visible(lay, w.num_requests, visible)
+            plan = B.ps_layout_plan(lay, w.num_requests)
+            _check_plan(w, lay, plan, visible)
+            if trial == 0:
+                assert not (plan["items"][:, 7] & 1 == 0).any()
+            if trial == 1:
+                assert not (plan["items"][:, 7] & 2).any()
+    # block tables and refcounts are untouched by visibility
+    after = B.ps_layout_tables(lay, w.num_prompts, w.num_requests)
+    assert all(np.array_equal(tables[k], after[k]) for k in tables)
+    assert np.array_equal(refs, B.ps_pool_refcounts(pool, w.num_blocks))
+    # out-of-range lengths are rejected and leave the layout as it was
+    B.ps_layout_replan(lay, None)
+    B.ps_layout_set_visible(lay, w.num_requests, None)
+    for bad in (full + (np.arange(15) == 4), -(np.arange(15) == 7).astype(np.int32)):
+        with pytest.raises(B.PsError) as e:
+            B.ps_layout_set_visible(lay, w.num_requests, bad)
+        assert e.value.status == B.PS_ERR_INVALID_ARG
+    again = B.ps_layout_plan(lay, w.num_requests)
+    assert np.array_equal(before["items"], again["items"]) and np.array_equal(before["slot_base"], again["slot_base"])
+    B.ps_layout_release(pool, lay)
+    B.ps_pool_destroy(pool)
+
+
+def test_causal_chunk_plan_skips_what_no_row_sees():
+    """A chunk of new tokens on one prompt, token i seeing cached + i + 1 tokens: row groups of 64 / G requests; a
+    group's items end at its last row's length, and fully visible ranges are not marked."""
+    geo = wl.Geometry(8, 2, 128, 16, "bf16", "bf16")
+    cached, chunk = 100, 40
+    w = wl.make_workload("chunk", geo, chunk, [cached + chunk], [list(range(chunk))], [0] * chunk, seed=0)
+    pool, lay, _, _ = _both(w)
+    visible = np.arange(cached + 1, cached + chunk + 1)
+    B.ps_layout_replan(lay, B.plan_options(64, 32))
+    B.ps_layout_set_visible(lay, chunk, visible)
+    plan = B.ps_layout_plan(lay, chunk)
+    _check_plan(w, lay, plan, visible)
+    items = plan["items"]
+    assert sorted({(a, b) for a, b in items[:, 1:3].tolist()}) == [(0, 64), (64, 116), (64, 128), (128, 140)]
+    assert not (items[items[:, 2] <= 100][:, 7] & 2).any()                # the old cache is seen by every row
+    assert (np.diff(plan["slot_base"]) == np.ceil(visible / 64)).all()    # partial states only where a row sees in
+    B.ps_layout_release(pool, lay)
+    B.ps_pool_destroy(pool)
 
 
 @pytest.mark.parametrize("name", ["tiny", "b8", "mixed"])
@@ -155,7 +230,7 @@ def test_schedules_cover_every_item_once_and_balance(name):
     w = wl.named_workload(name)
     pool, lay, _, _ = _both(w)
     items = B.ps_layout_plan(lay, w.num_requests)["items"]
-    sets = {0: items[items[:, 7] == 0], 1: items[items[:, 7] == 1], 2: items}
+    sets = {0: items[items[:, 7] & 1 == 0], 1: items[items[:, 7] & 1 == 1], 2: items}
     for which, expect in sets.items():
         sch = B.ps_layout_schedule(lay, which)
         assert sch, "bf16 / fp8 workloads run on the matrix-core kernel"

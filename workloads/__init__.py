@@ -12,9 +12,11 @@ from .generate import (  # noqa: F401
     PoolData,
     Workload,
     bf16_bits_from_f32,
+    chunk_prefill_workload,
     e4m3_encode,
     fill_pool,
     ideal_bytes,
     make_workload,
+    named_chunk_prefill,
     named_workload,
 )

@@ -275,6 +275,44 @@ def make_workload(name: str, geometry: Geometry, num_models: int, prefix_len: Se
     return w
 
 
+def chunk_prefill_workload(name: str, geometry: Geometry, cached_len: Sequence[int], chunk_len: Sequence[int],
+                           pool_factor: float = 1.0, seed: int = 0):
+    """Partial prefill of P contexts (System Design, execution pipeline step 1): context p holds cached_len[p]
+    tokens whose KV is cached and grows by chunk_len[p] new tokens.  Returns (workload, visible): the new tokens'
+    KV continues the prompt's shared prefix (prefix length = cached + chunk), every new token is one request on
+    its prompt (model index = position in the chunk, no private suffix), and visible[r] = cached + position + 1
+    is how much of the prefix that token's query row attends to (causal order inside the chunk)."""
+    cached = np.asarray(cached_len, np.int64)
+    chunk = np.asarray(chunk_len, np.int64)
+    if cached.shape != chunk.shape or (cached < 0).any() or (chunk < 1).any():
+        raise ValueError("one cached length >= 0 and one chunk length >= 1 per context")
+    membership = [list(range(int(c))) for c in chunk]
+    w = make_workload(name, geometry, int(chunk.max()), (cached + chunk).tolist(), membership,
+                      [0] * int(chunk.sum()), pool_factor, seed)
+    visible = np.concatenate([cached[p] + 1 + np.arange(chunk[p]) for p in range(len(chunk))]).astype(np.int32)
+    return w, visible
+
+
+def named_chunk_prefill(name: str, seed: int = 0):
+    """Partial-prefill stand-ins for a model switch in multi-agent traffic (the previous module's output segment
+    is appended to the shared context and prefilled by the base module against the cached context):
+
+    prefill_tiny  2 contexts, cached 40 / 7, chunks 19 / 30, 4 q / 2 kv heads, d 64, fp32
+    prefill_b8    32 contexts, cached 4096, chunks U[64,256], 32/8 heads, d 128, bf16
+    prefill_fp8   64 contexts, cached 8192, chunks U[64,256], 64/8 heads, bf16 Q, e4m3 KV
+    """
+    rng = _rng(seed, 1)
+    if name == "prefill_tiny":
+        return chunk_prefill_workload(name, Geometry(4, 2, 64, 16, "f32", "f32"), [40, 7], [19, 30], 1.0, seed)
+    if name == "prefill_b8":
+        return chunk_prefill_workload(name, Geometry(32, 8, 128, 16, "bf16", "bf16"), [4096] * 32,
+                                      rng.integers(64, 257, 32), 1.0, seed)
+    if name == "prefill_fp8":
+        return chunk_prefill_workload(name, Geometry(64, 8, 128, 16, "bf16", "fp8_e4m3"), [8192] * 64,
+                                      rng.integers(64, 257, 64), 1.0, seed)
+    raise ValueError(name)
+
+
 def named_workload(name: str, seed: int = 0, models: Optional[int] = None) -> Workload:
     """The five benchmark configurations (synthetic stand-ins for multi-agent traffic).
 
