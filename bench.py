@@ -29,9 +29,11 @@ def parse():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="b8", help="tiny | b8 | long | mixed | fp8_70b")
-    ap.add_argument("--path", default="decode", choices=["decode", "ingest"],
+    ap.add_argument("--path", default="decode", choices=["decode", "ingest", "prefill"],
                     help="decode: the attention step (the headline metric); ingest: hand-off of the batch's KV into "
-                         "the paged pool (ps_kv_ingest over every prefix and suffix), a step = one whole hand-off")
+                         "the paged pool (ps_kv_ingest over every prefix and suffix), a step = one whole hand-off; "
+                         "prefill: attention of newly appended context tokens against the cached context "
+                         "(workloads prefill_b8 | prefill_fp8 | prefill_tiny)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--models", type=int, default=0, help="override the number of decode models M (b8, long, fp8_70b)")
     ap.add_argument("--copies", type=int, default=3, help="distinct KV pool copies rotated between steps")
@@ -240,6 +242,126 @@ def main_ingest(args):
     print(json.dumps(line))
 
 
+PEAK_MFMA_BF16_TFLOPS = 2500.0
+
+
+def cpu_prefill_baseline(w, visible, data, seconds):
+    """Time the oracle on query rows of the chunk workload, one by one, until about `seconds` have passed."""
+    from oracle import attention as oa
+    from oracle import layout as ol
+    g = w.geometry
+    opool = ol.BlockPool(w.num_blocks, w.free_order)
+    olay = ol.build_layout(opool, g.block_size, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
+    q_bits = w.q_bits()
+    rows = np.random.default_rng(0).permutation(w.num_requests).tolist()
+    done, flops = 0, 0
+    wall0, cpu0 = time.perf_counter(), time.process_time()
+    for r in rows:
+        oa.decode_attention(q_bits, g.q_dtype, data.kv, data.scales, g.kv_dtype, olay, [r], visible)
+        done += 1
+        flops += 4 * g.head_dim * g.num_q_heads * int(visible[r])
+        if time.perf_counter() - wall0 >= seconds:
+            break
+    wall = time.perf_counter() - wall0
+    cpu = time.process_time() - cpu0
+    return {"value": flops / wall / 1e12, "unit": "TFLOP/s", "cores": max(1, int(round(cpu / wall))), "kind": "oracle",
+            "tokens_per_s": done / wall,
+            "sample": f"fp64 numpy oracle over {done} of the {w.num_requests} new tokens (all q heads, seeded order), "
+                      f"{wall:.1f} s wall"}
+
+
+def main_prefill(args):
+    """--path prefill: one step = the attention of every newly appended context token against its context's cached
+    KV and the new tokens before it (ps_layout_set_visible + ps_decode_attention)."""
+    import torch
+    import workloads as wl
+    from paper_2602_12029_amd import binding as B
+    from paper_2602_12029_amd.runtime import DecodeBatch, to_device
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    dev = "cuda:0"
+    variant = {"auto": B.PS_VARIANT_AUTO, "wave": B.PS_VARIANT_WAVE, "mfma": B.PS_VARIANT_MFMA}
+    name = args.workload if args.workload.startswith("prefill") else "prefill_" + args.workload
+    w, visible = wl.named_chunk_prefill(name, args.seed)
+    g = w.geometry
+    geo = B.geometry(g.num_q_heads, g.num_kv_heads, g.head_dim, g.block_size, g.q_dtype, g.kv_dtype)
+    pool = B.ps_pool_create(w.num_blocks, w.free_order)
+    layout = B.ps_kv_layout(pool, geo, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
+    tables = B.ps_layout_tables(layout, w.num_prompts, w.num_requests)
+    data = wl.fill_pool(w, tables["prefix_blk_indptr"], tables["prefix_blk"], tables["suffix_blk_indptr"],
+                        tables["suffix_blk"])
+    q = to_device(w.q_bits(), g.q_dtype, dev)
+    kv0 = to_device(data.kv, g.kv_dtype, dev)
+    copies = [kv0] + [kv0.clone() for _ in range(max(0, args.copies - 1))]
+    scales = None if data.scales is None else torch.from_numpy(data.scales).to(dev)
+    batch = DecodeBatch(layout, geo, w.num_requests, q, kv0, scales)
+    t_lay0 = time.perf_counter()
+    B.ps_layout_replan(layout, B.plan_options(args.prefix_chunk, args.suffix_chunk, variant[args.prefix_variant],
+                                              variant[args.suffix_variant]))
+    batch.set_visible(visible)
+    t_plan_ms = (time.perf_counter() - t_lay0) * 1e3
+    plan = B.ps_layout_plan(layout, w.num_requests)
+    stream = int(torch.cuda.current_stream().cuda_stream)
+    sc = scales.data_ptr() if scales is not None else 0
+    tp, qp, wp, op = batch.tables.data_ptr(), q.data_ptr(), batch.workspace.data_ptr(), batch.out.data_ptr()
+
+    if args.calibrate_copy:
+        calibrate_copy(dev)
+    for i in range(args.warmup):
+        batch.decode_attention(with_lse=False, kv=copies[i % len(copies)])
+    torch.cuda.synchronize()
+    ev = None if args.no_events else HipEvents(args.steps)
+    every = max(1, args.event_every)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        kv = copies[i % len(copies)]
+        if ev is None or i % every:
+            batch.decode_attention(with_lse=False, kv=kv)
+        else:
+            ev.record(i, 0, stream)
+            B.ps_prefix_suffix_attention(layout, tp, qp, kv.data_ptr(), sc, wp, stream)
+            ev.record(i, 1, stream)
+            B.ps_merge_states(layout, tp, wp, op, 0, stream)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # algorithmic work: 2 d multiply-adds for the score and 2 d for the weighted value, per (q head, visible token)
+    flops = 4 * g.head_dim * g.num_q_heads * int(visible.astype(np.int64).sum())
+    ideal = wl.ideal_bytes(w)
+    roofline = {"bound": "mfma", "kernel": "attention (masked prefix work list)", "achieved": None,
+                "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s", "frac": None, "traffic": None}
+    if ev is not None:
+        k_ms = float(np.mean([ev.elapsed_ms(i) for i in range(0, args.steps, every)]))
+        roofline.update(achieved=flops / (k_ms * 1e-3) / 1e12, kernel_ms=k_ms, algorithmic_flops=flops)
+        roofline["frac"] = roofline["achieved"] / PEAK_MFMA_BF16_TFLOPS
+    summary = os.path.join(ROOT, "profiles", f"attention_kernel_{name}.md")
+    if os.path.exists(summary):
+        for text in open(summary):
+            if text.startswith("traffic_bytes_per_launch:"):
+                roofline["traffic"] = float(text.split(":")[1])
+    value = flops / (ms_per_step * 1e-3) / 1e12
+    line = {
+        "metric": "partial-prefill attention over the shared cache: algorithmic TFLOP/s + new tokens/sec",
+        "value": value, "unit": "TFLOP/s", "pct_of_peak_mfma": 100.0 * value / PEAK_MFMA_BF16_TFLOPS,
+        "tokens_per_s": w.num_requests / (ms_per_step * 1e-3),
+        "ideal_byte_gbs": ideal / (ms_per_step * 1e-3) / 1e9,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if g.kv_dtype == "bf16" else ("fp8_e4m3 KV / bf16 Q" if g.kv_dtype == "fp8_e4m3" else "f32"),
+        "data": "synthetic",
+        "config": {"workload": name, "path": "prefill", "contexts": w.num_prompts, "new_tokens": w.num_requests,
+                   "cached_tokens": int((w.prefix_len.astype(np.int64)).sum()) - w.num_requests,
+                   "q_heads": g.num_q_heads, "kv_heads": g.num_kv_heads, "head_dim": g.head_dim,
+                   "block_size": g.block_size, "ideal_bytes": ideal, "pool_copies": len(copies),
+                   "plan_items": int(plan["items"].shape[0]), "plan_ms": t_plan_ms},
+        "roofline": roofline,
+    }
+    if args.cpu_seconds > 0:
+        line["cpu_baseline"] = cpu_prefill_baseline(w, visible, data, args.cpu_seconds)
+    print(json.dumps(line))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -247,6 +369,8 @@ def main():
                  "use --gpus 1")
     if args.path == "ingest":
         return main_ingest(args)
+    if args.path == "prefill":
+        return main_prefill(args)
     import torch
     import workloads as wl
     from paper_2602_12029_amd import binding as B
