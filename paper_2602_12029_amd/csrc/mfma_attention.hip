@@ -39,6 +39,7 @@ constexpr int kTile = 32;         // tokens per tile buffer
 constexpr int kLdsRow = kD + 4;   // padded row of the merge buffer (floats)
 constexpr int kQRow = kD + 8;     // padded query row (bf16), 16 bytes of padding against bank conflicts
 constexpr int kHdrRing = 128;     // item headers staged in LDS (circular, refilled in halves)
+constexpr float kLazy = 8.f;      // log2 units the row maximum may run ahead of the softmax reference before a rescale
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
@@ -96,7 +97,7 @@ struct ItemCtx {
 // Per-lane metadata of an item: block ids (and e4m3 scales) of this wave's tiles.
 struct ItemMeta {
   int ids;
-  float ksc, vsc;
+  float ksc, lvs;   // e4m3: K scale and log2 of the V scale of the block (1 and 0 otherwise)
 };
 
 template <int NT>
@@ -173,7 +174,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
 
   // block ids (and scales) of this wave's tiles of an item: lane 2k+h <- 16-token block h of tile k
   auto fetch_meta = [&](const ItemCtx& c) {
-    ItemMeta m{0, 1.f, 1.f};
+    ItemMeta m{0, 1.f, 0.f};
     const int k = lane >> 1;
     const int sub = c.sub0 + 2 * (wave + kWaves * k) + (lane & 1);
     if (k < c.my_tiles && sub < c.sub_end) {
@@ -181,7 +182,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
       if constexpr (KVT == PS_FP8_E4M3) {
         const float* sc = p.scales + (int64_t(m.ids) * p.num_kv_heads + c.kv_head) * 2;
         m.ksc = sc[0];
-        m.vsc = sc[1];
+        m.lvs = __builtin_amdgcn_logf(sc[1]);   // log2
       }
     }
     return m;
@@ -282,12 +283,16 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
     constexpr bool kAllRows = decltype(all_rows_tag)::value, kFull = decltype(full_tag)::value;
     const int tok0 = c.tok_begin + kTile * (wave + kWaves * k);  // first token of the tile
     const bool full = kFull || tok0 + kTile <= c.tok_end;
-    float sc_k[2] = {p.scale_log2, p.scale_log2}, sc_v[2] = {1.f, 1.f};
+    // Per 16-token block: scores are raw dot products times sc_k (1/sqrt(d) in log2 units, times the block's K
+    // scale); the block's V scale rides in the exponent of the probabilities (lvs = log2 of it), so that the
+    // unscaled V codes can go into the matrix cores, and comes out of the row sums again through inv_v.
+    float sc_k[2] = {p.scale_log2, p.scale_log2}, lvs[2] = {0.f, 0.f}, inv_v[2] = {1.f, 1.f};
     if constexpr (KVT == PS_FP8_E4M3) {
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
         sc_k[b] *= __int_as_float(__builtin_amdgcn_readlane(__float_as_int(meta.ksc), 2 * k + b));
-        sc_v[b] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(meta.vsc), 2 * k + b));
+        lvs[b] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(meta.lvs), 2 * k + b));
+        inv_v[b] = fast_exp2(-lvs[b]);
       }
     }
 
@@ -322,7 +327,6 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
           s[b] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int st = 0; st < 4; ++st) s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[b][st], qb[st], s[b], 0, 0, 0);
-          s[b] *= sc_k[b];  // scores in log2 units
         }
         if (MASKED || !full) {
           const int lim = MASKED ? rl.lim[t] : c.tok_end;
@@ -332,30 +336,36 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
             for (int j = 0; j < 4; ++j)
               if (tok0 + 16 * b + 4 * kg + j >= lim) s[b][j] = neg_inf;
         }
-        float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
-                         fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
+        // row maximum in log2 units (the scales are positive, so a block's maximum scales like its scores)
+        float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])) * sc_k[0],
+                         fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])) * sc_k[1]);
         mx = fmaxf(mx, lane_xor(mx, 16));
         mx = fmaxf(mx, lane_xor(mx, 32));
-        // finite unless MASKED: every tile holds at least one valid token, but a row may not see any of them yet
-        const float m_new = fmaxf(m_run[t], mx);
-        const float m_ref = (MASKED && m_new == neg_inf) ? 0.f : m_new;   // keeps (-inf) - (-inf) out of the exponents
-        if (__builtin_amdgcn_ballot_w64(m_new != m_run[t]) != 0) {
-          const float alpha = fast_exp2(m_run[t] - m_ref);
+        // The running reference m_run follows the row maximum lazily: it moves (and the accumulators are rescaled)
+        // only when the maximum gets more than kLazy ahead of it, so probabilities stay below 2^kLazy instead of
+        // below 1 -- the same result by shift invariance of softmax, without a rescale on almost every tile.
+        // A row that has seen nothing yet (MASKED) has m_run = mx = -inf and stays there.
+        if (__builtin_amdgcn_ballot_w64(mx > m_run[t] + kLazy) != 0) {
+          const float m_new = (mx > m_run[t] + kLazy) ? mx : m_run[t];
+          const float alpha = (m_new == m_run[t]) ? 1.f : fast_exp2(m_run[t] - m_new);   // -inf -> finite gives 0
           l_run[t] *= alpha;
 #pragma unroll
           for (int cc = 0; cc < 8; ++cc) acc[t][cc] *= alpha;
           m_run[t] = m_new;
         }
-        float lsum = 0.f;
+        const float m_ref = (MASKED && m_run[t] == neg_inf) ? 0.f : m_run[t];   // keeps (-inf) - (-inf) out of the exponents
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < 2; ++b) {
+          const float shift = lvs[b] - m_ref;
+          float lsum = 0.f;
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
-            const float pw = fast_exp2(s[b][j] - m_ref);
+            const float pw = fast_exp2(__builtin_fmaf(s[b][j], sc_k[b], shift));   // probability times the V scale
             lsum += pw;
-            pb[t][4 * b + j] = (__bf16)(pw * sc_v[b]);
+            pb[t][4 * b + j] = (__bf16)pw;
           }
-        l_run[t] += lsum;
+          l_run[t] += (KVT == PS_FP8_E4M3) ? lsum * inv_v[b] : lsum;
+        }
       }
     }
     // V rows of this lane's 8 tokens as bf16, invalid tokens zeroed (their slots may hold anything)
@@ -466,7 +476,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
   store_q(load_q(q_row_index(cur)));
   bool has_next = j_first + 1 < j_last;
   ItemCtx nxt = cur;
-  ItemMeta meta_nxt{0, 1.f, 1.f};
+  ItemMeta meta_nxt{0, 1.f, 0.f};
   QIndex<NT> q_idx_nxt{};
   RowLimit<NT> lim_nxt{};
   if (has_next) {
@@ -483,7 +493,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
     if (has_next) q_nxt = load_q(q_idx_nxt);
     const bool has_nn = j + 2 < j_last;
     ItemCtx nn = nxt;
-    ItemMeta meta_nn{0, 1.f, 1.f};
+    ItemMeta meta_nn{0, 1.f, 0.f};
     QIndex<NT> q_idx_nn{};
     RowLimit<NT> lim_nn{};
     if (has_nn) {
