@@ -125,7 +125,9 @@ int32_t ps_layout_plan(const ps_layout* layout, int32_t* num_items, const int32_
  * requests in ascending order for every prompt (group_req), then 0..R-1 (private-suffix items), then,
  * where visible lengths keep part of a sharing group out of a prefix chunk, the sub-lists of those
  * chunks.  The last field of an item is a bit set: bit 0 = private suffix, bit 1 = some row of the item
- * sees fewer tokens than the item's token end. */
+ * sees fewer tokens than the item's token end, bit 2 = a partial-prefill item of up to 256 rows, which a
+ * workgroup of the prefill kernel splits over its waves by rows (such items lead the item array and are
+ * not part of the schedules below). */
 int32_t ps_layout_request_list(const ps_layout* layout, int32_t* count, const int32_t** list);
 
 /* Schedule of the persistent matrix-core kernel for one launchable set of items (which: 0 = prefix items,
@@ -185,7 +187,9 @@ int32_t ps_decode_attention(const ps_layout* layout, const void* dev_tables, con
  * suffix; NULL restores full visibility.  Re-derives the split plan with the options last used (a request
  * gets partial states only for the prefix chunks it sees into), so earlier uploads of the table blob and the
  * sizes reported by ps_layout_device_bytes / ps_workspace_bytes are invalid afterwards.  Block tables and
- * refcounts do not change.  PS_ERR_INVALID_ARG: a length out of range; the layout is unchanged. */
+ * refcounts do not change.  Where the matrix-core kernels apply and a sharing group has more than 64 query
+ * rows per KV head (the new tokens of a context), the group goes out in items of up to 256 rows that run in the
+ * prefill kernel.  PS_ERR_INVALID_ARG: a length out of range; the layout is unchanged. */
 int32_t ps_layout_set_visible(ps_layout* layout, const int32_t* prefix_visible);
 
 /* ---- cache growth -------------------------------------------------------------------------------------

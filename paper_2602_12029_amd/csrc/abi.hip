@@ -58,8 +58,14 @@ int32_t launch_set(const ps_layout* lay, const psdev::AttnParams& p, const void*
     const ps_layout::schedule& s = set == WorkSet::kPrefix ? lay->sched_prefix
                                    : set == WorkSet::kSuffix ? lay->sched_suffix : lay->sched_all;
     const int32_t* t = static_cast<const int32_t*>(dev_tables);
-    rc = psdev::launch_mfma_attention(p, lay->geo, s.max_rows, s.occ, set != WorkSet::kSuffix && lay->any_masked,
-                                      reinterpret_cast<const ps_item*>(t + s.off_items), t + s.off_indptr, s.num_wg, st);
+    rc = PS_OK;
+    // the row-split prefix items (partial prefill) lead the item array and run one workgroup each
+    if (set != WorkSet::kSuffix && lay->num_rowsplit_items > 0)
+      rc = psdev::launch_prefill_attention(p, lay->geo, p.items, lay->num_rowsplit_items, st);
+    if (rc == PS_OK)
+      rc = psdev::launch_mfma_attention(p, lay->geo, s.max_rows, s.occ, set != WorkSet::kSuffix && lay->any_masked,
+                                        reinterpret_cast<const ps_item*>(t + s.off_items), t + s.off_indptr, s.num_wg,
+                                        st);
   } else {
     rc = psdev::launch_wave_attention(p, lay->geo, begin, end - begin, st);
   }

@@ -12,6 +12,9 @@ int32_t launch_wave_attention(const AttnParams& p, const ps_geometry& g, int ite
 // `masked`: the set holds items whose rows see different token counts (per-request visible prefix lengths).
 int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max_rows, int occ, bool masked,
                               const ps_item* wg_items, const int32_t* wg_indptr, int num_wg, hipStream_t st);
+// Partial prefill: one workgroup per row-split item (up to 256 query rows, split over the waves by rows).
+int32_t launch_prefill_attention(const AttnParams& p, const ps_geometry& g, const ps_item* items, int num_items,
+                                 hipStream_t st);
 // Cache writes: whole segments of one kind (0 = shared prefixes, 1 = private suffixes) from ragged contiguous
 // sources, and the one token per request reserved by the last ps_layout_append.
 int32_t launch_kv_ingest(const ps_layout* lay, const void* dev_tables, int which, const void* src_k, const void* src_v,

@@ -128,13 +128,18 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
           lay->req_list.insert(lay->req_list.end(), members.begin(), members.end());
         }
       }
+      // Partial prefill on the matrix cores: a sharing group with more rows than one 64-row item holds (the new
+      // tokens of a context) goes out in items of up to 256 rows, which the prefill kernel splits over its waves
+      // by rows, so that a K/V tile is fetched once per 256 rows instead of once per 64.
+      const bool row_split = limited && resolve(opt.prefix_variant) == PS_VARIANT_MFMA && int64_t(count) * group > 64;
+      const int32_t per_item = row_split ? std::max(1, 256 / group) : max_req;
       for (int32_t h = 0; h < g.num_kv_heads; ++h)
-        for (int32_t m0 = 0; m0 < count; m0 += max_req) {
+        for (int32_t m0 = 0; m0 < count; m0 += per_item) {
           ps_item it{};
           it.blk_off = lay->prefix_blk_indptr[p];
           it.tok_begin = int32_t(c * size);
           it.req_off = list0 + m0;
-          it.n_req = std::min(max_req, count - m0);
+          it.n_req = std::min(per_item, count - m0);
           int32_t v_max = 0, v_min = INT32_MAX;
           for (int32_t i = 0; i < it.n_req; ++i) {
             const int32_t v = visible_of(lay->req_list[size_t(it.req_off + i)]);
@@ -144,9 +149,9 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
           it.tok_end = int32_t(std::min<int64_t>(std::min<int64_t>(lay->prefix_len[p], (c + 1) * size), v_max));
           it.kv_head = h;
           it.split_local = c;
-          it.kind = v_min < it.tok_end ? kPsItemMasked : 0;
+          it.kind = (v_min < it.tok_end ? kPsItemMasked : 0) | (row_split ? kPsItemRowSplit : 0);
           if (it.kind & kPsItemMasked) lay->any_masked = true;
-          lay->max_rows_prefix = std::max(lay->max_rows_prefix, it.n_req * group);
+          if (!row_split) lay->max_rows_prefix = std::max(lay->max_rows_prefix, it.n_req * group);
           prefix_items.push_back(it);
         }
     }
@@ -170,8 +175,16 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
       }
   }
   auto by_cost = [](const ps_item& a, const ps_item& b) { return (a.tok_end - a.tok_begin) > (b.tok_end - b.tok_begin); };
-  std::stable_sort(prefix_items.begin(), prefix_items.end(), by_cost);
+  auto rs_first = [&](const ps_item& a, const ps_item& b) {   // row-split items lead, heaviest (tokens x rows) first
+    const bool ra = a.kind & kPsItemRowSplit, rb = b.kind & kPsItemRowSplit;
+    if (ra != rb) return ra;
+    if (ra) return int64_t(a.tok_end - a.tok_begin) * a.n_req > int64_t(b.tok_end - b.tok_begin) * b.n_req;
+    return by_cost(a, b);
+  };
+  std::stable_sort(prefix_items.begin(), prefix_items.end(), rs_first);
   std::stable_sort(suffix_items.begin(), suffix_items.end(), by_cost);
+  lay->num_rowsplit_items = 0;
+  for (const ps_item& it : prefix_items) lay->num_rowsplit_items += (it.kind & kPsItemRowSplit) ? 1 : 0;
   lay->num_prefix_items = int32_t(prefix_items.size());
   lay->items = std::move(prefix_items);
   lay->items.insert(lay->items.end(), suffix_items.begin(), suffix_items.end());
@@ -218,9 +231,10 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   const int n_items = int(lay->items.size());
   const bool pre_mfma = lay->prefix_variant == PS_VARIANT_MFMA, suf_mfma = lay->suffix_variant == PS_VARIANT_MFMA;
   packed pk_prefix, pk_suffix, pk_all;
-  if (pre_mfma) pk_prefix = pack(0, lay->num_prefix_items);
+  const int first_packed = lay->num_rowsplit_items;   // row-split items run in the prefill kernel, one workgroup each
+  if (pre_mfma) pk_prefix = pack(first_packed, lay->num_prefix_items);
   if (suf_mfma) pk_suffix = pack(lay->num_prefix_items, n_items);
-  if (pre_mfma && suf_mfma) pk_all = pack(0, n_items);
+  if (pre_mfma && suf_mfma) pk_all = pack(first_packed, n_items);
 
   // device blob: [block ids: prefix ++ suffix][request list: group_req ++ identity ++ per-chunk subsets][items]
   // [slot_base][visible][schedules]

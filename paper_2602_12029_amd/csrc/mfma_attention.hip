@@ -336,16 +336,17 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
             for (int j = 0; j < 4; ++j)
               if (tok0 + 16 * b + 4 * kg + j >= lim) s[b][j] = neg_inf;
         }
-        // row maximum in log2 units (the scales are positive, so a block's maximum scales like its scores)
+        // The softmax reference m_run follows the row maximum lazily: it moves (and the accumulators are rescaled)
+        // only when some score gets more than kLazy ahead of it, so probabilities stay below 2^kLazy instead of below 1
+        // -- the same result by shift invariance of softmax.  The test is local to the lane (its own 8 scores, in log2
+        // units; the scales are positive, so a block's maximum scales like its scores); only when it fires somewhere in
+        // the wave is the maximum of each row put together across the row's four lanes, which must agree on m_run.
+        // A row that has seen nothing yet has m_run = -inf and stays there until a score arrives.
         float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])) * sc_k[0],
                          fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])) * sc_k[1]);
-        mx = fmaxf(mx, lane_xor(mx, 16));
-        mx = fmaxf(mx, lane_xor(mx, 32));
-        // The running reference m_run follows the row maximum lazily: it moves (and the accumulators are rescaled)
-        // only when the maximum gets more than kLazy ahead of it, so probabilities stay below 2^kLazy instead of
-        // below 1 -- the same result by shift invariance of softmax, without a rescale on almost every tile.
-        // A row that has seen nothing yet (MASKED) has m_run = mx = -inf and stays there.
         if (__builtin_amdgcn_ballot_w64(mx > m_run[t] + kLazy) != 0) {
+          mx = fmaxf(mx, lane_xor(mx, 16));
+          mx = fmaxf(mx, lane_xor(mx, 32));
           const float m_new = (mx > m_run[t] + kLazy) ? mx : m_run[t];
           const float alpha = (m_new == m_run[t]) ? 1.f : fast_exp2(m_run[t] - m_new);   // -inf -> finite gives 0
           l_run[t] *= alpha;

@@ -1,0 +1,375 @@
+// Partial-prefill attention on the gfx950 matrix cores: many query rows per KV head against the cached context.
+//
+// When a context grows by a segment, only the new tokens are prefilled (System Design, execution pipeline step 1):
+// every new token is a query row on its context's shared KV, the token at position t seeing the first t + 1
+// tokens.  With G q heads per KV head a chunk of c new tokens is c * G rows per KV head -- hundreds, where a decode
+// step has a few dozen -- so the work is a dense contraction and the matrix cores, not HBM, are the bound.
+//
+// One workgroup (4 waves) takes one work item: a token range of one context and KV head, and up to 256 query rows
+// that see into it.  The rows are split over the waves, 64 each, and every wave walks the whole token range, so a
+// wave never shares anything with its neighbours: no barrier, no cross-wave merge.  The four waves read the same
+// K/V tiles at nearly the same time, so HBM (and mostly L2) sees each tile once per 256 rows.  A wave's query rows
+// are kept as ready-made MFMA B operands, 16 bytes per lane and piece, in a lane-private corner of LDS (every lane
+// reads back exactly what it wrote, so no synchronisation is involved; registers hold the accumulators and the two
+// tile buffers).
+//
+// Per wave and 32-token tile the math is that of the decode kernel (S^T = K Q^T, online softmax with a lazily
+// moving reference, O^T += V^T P^T; K straight into the A layout, V transposed in the lane), over four 16-row
+// tiles.  Tiles past what every row of the wave sees are skipped; the per-row limit is applied only to tiles that
+// reach past the shortest row.
+#include <type_traits>
+
+#include "device_common.h"
+#include "launch.h"
+
+namespace psdev {
+
+namespace {
+
+constexpr int kD = 128;
+constexpr int kNT = 4;            // 16-row tiles per wave
+constexpr int kTile = 32;         // tokens per tile
+constexpr float kLazy = 8.f;      // log2 units the row maximum may run ahead of the softmax reference before a rescale
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+template <int KVT>
+struct Tile;                      // raw K/V of one 32-token tile as loaded
+template <>
+struct Tile<PS_BF16> {
+  u32x4 k[2][4];                  // [block][k-step]: 8 bf16 of token (lane%16), d-chunk 4*step + lane/16
+  u32x4 v[8];                     // token i of this lane's 8 tokens, d columns 8*(lane%16)..+7
+};
+template <>
+struct Tile<PS_FP8_E4M3> {
+  u32x4 k[2][2];                  // [block][half]: 16 codes of token (lane%16), d 64*half + 16*(lane/16)..+15
+  u32x2 v[8];                     // 8 codes: token i, d columns 8*(lane%16)..+7
+};
+
+__device__ __forceinline__ bf16x8 bits_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// two e4m3 codes (a byte pair of w) -> two bf16, exactly (one v_cvt_scalef32_pk_bf16_fp8, scale 1)
+__device__ __forceinline__ uint32_t codes_to_bf16x2(uint32_t w, bool hi) {
+  const bf16x2 b = hi ? __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true)
+                      : __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false);
+  return __builtin_bit_cast(uint32_t, b);
+}
+__device__ __forceinline__ u32x4 codes_to_bf16x8(uint32_t lo, uint32_t hi) {
+  return u32x4{codes_to_bf16x2(lo, false), codes_to_bf16x2(lo, true), codes_to_bf16x2(hi, false),
+               codes_to_bf16x2(hi, true)};
+}
+
+// element offset of the 8 query values that meet K's k-step `step` in lane group kg (the contraction index is
+// permuted the same way in K as loaded and in Q)
+template <int KVT>
+__device__ __forceinline__ int q_piece(int step, int kg) {
+  if constexpr (KVT == PS_BF16) return 32 * step + 8 * kg;
+  return 64 * (step >> 1) + 16 * kg + 8 * (step & 1);
+}
+
+__device__ __forceinline__ int wave_max(int x) {
+#pragma unroll
+  for (int m = 1; m < 64; m <<= 1) x = max(x, __builtin_amdgcn_ds_bpermute(((int(threadIdx.x) & 63) ^ m) << 2, x));
+  return __builtin_amdgcn_readfirstlane(x);
+}
+
+}  // namespace
+
+template <int KVT>
+__global__ __launch_bounds__(256, 1) void prefill_attention_kernel(AttnParams p, const ps_item* __restrict__ items) {
+  __shared__ u32x4 sm_qb[4][kNT * 4][64];   // [wave][row tile * 4 + k-step][lane]: that lane's B operand
+  const ps_item* it = items + blockIdx.x;
+  const int blk_off = __builtin_amdgcn_readfirstlane(it->blk_off);
+  const int tok_begin = __builtin_amdgcn_readfirstlane(it->tok_begin);
+  const int tok_end = __builtin_amdgcn_readfirstlane(it->tok_end);
+  const int req_off = __builtin_amdgcn_readfirstlane(it->req_off);
+  const int n_req = __builtin_amdgcn_readfirstlane(it->n_req);
+  const int kv_head = __builtin_amdgcn_readfirstlane(it->kv_head);
+  const int split_local = __builtin_amdgcn_readfirstlane(it->split_local);
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
+  const int n = lane & 15;   // query row within a row tile / token within a block / d-chunk, by role
+  const int kg = lane >> 4;
+  const int G = p.group;
+  const int rows = n_req * G;
+  const int row_base = 64 * wave;
+  if (row_base >= rows) return;   // nothing shared between waves: a wave without rows simply leaves
+  const int nt_used = min(kNT, (rows - row_base + 15) >> 4);
+  const float neg_inf = -__builtin_inff();
+
+  // ---- this lane's query rows (row 16 t + n of the wave): request, visible length, and the row itself as the
+  // four B operands of S^T = K Q^T
+  int req_of[kNT], lim[kNT];
+  int lim_hi = 0, lim_lo = 0x7fffffff;
+#pragma unroll
+  for (int t = 0; t < kNT; ++t) {
+    const int row = row_base + 16 * t + n;
+    req_of[t] = -1;
+    lim[t] = 0;   // a padding row sees nothing
+    u32x4 piece[4] = {u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}};
+    if (row < rows) {
+      const int req = p.req_list[req_off + row / G];
+      req_of[t] = req;
+      lim[t] = min(tok_end, p.visible[req]);
+      const uint16_t* qrow = static_cast<const uint16_t*>(p.q) + (int64_t(req) * p.num_q_heads + kv_head * G + row % G) * kD;
+#pragma unroll
+      for (int st = 0; st < 4; ++st) piece[st] = *reinterpret_cast<const u32x4*>(qrow + q_piece<KVT>(st, kg));
+      lim_hi = max(lim_hi, lim[t]);
+      lim_lo = min(lim_lo, lim[t]);
+    }
+#pragma unroll
+    for (int st = 0; st < 4; ++st) sm_qb[wave][4 * t + st][lane] = piece[st];
+  }
+  const int see_end = wave_max(lim_hi);      // no row of this wave sees a token at or past this one
+  const int see_all = -wave_max(-lim_lo);    // every row of this wave sees every token before this one
+  if (see_end <= tok_begin) return;          // cannot happen for planned items; keeps the loop bounds honest
+  const int n_tiles = (see_end - tok_begin + kTile - 1) / kTile;
+
+  // ---- addressing (as in the decode kernel): block base in SGPRs, two loop-invariant VGPR offsets
+  const int sub_shift = __builtin_ctz(unsigned(p.block_size >> 4));
+  const int sub_mask = (p.block_size >> 4) - 1;
+  constexpr int kEsz = KVT == PS_BF16 ? 2 : 1;
+  const int tok_bytes = int(p.s_tok) * kEsz;
+  const int kv_bytes = int(p.s_kv) * kEsz;
+  const int k_lane_off = n * tok_bytes + kg * 16;
+  const int v_lane_off = 4 * kg * tok_bytes + n * (8 * kEsz);
+  const int64_t head_base = reinterpret_cast<int64_t>(p.kv) + int64_t(kv_head) * p.s_head * kEsz;
+  const int64_t blk_bytes = p.s_block * kEsz;
+  const int sub_bytes = 16 * tok_bytes;
+  const int sub0 = tok_begin >> 4;
+  const int sub_end = (see_end + 15) >> 4;
+
+  struct TileIds { int id[2]; float ksc[2], lvs[2]; };
+  auto fetch_ids = [&](int k) {    // block ids (and e4m3 scales) of the two 16-token blocks of tile k; wave-uniform
+    TileIds r;
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      // no branch around these loads (the index is clamped into the range instead), so that the counting of
+      // outstanding loads in the streaming loop stays exact; a block past the range is never fetched from
+      const int sub = min(sub0 + 2 * k + b, sub_end - 1);
+      r.id[b] = __builtin_amdgcn_readfirstlane(p.blk[blk_off + (sub >> sub_shift)]);
+      r.ksc[b] = 1.f;
+      r.lvs[b] = 0.f;
+      if constexpr (KVT == PS_FP8_E4M3) {
+        const float* sc = p.scales + (int64_t(r.id[b]) * p.num_kv_heads + kv_head) * 2;
+        r.ksc[b] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(sc[0])));
+        r.lvs[b] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(__builtin_amdgcn_logf(sc[1]))));
+      }
+    }
+    return r;
+  };
+  // every call issues the same 16 loads; a block past the range gets a zero-sized descriptor (zeros, no traffic)
+  auto load_tile = [&](Tile<KVT>& tr, const TileIds& ids, int k) {
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      const int sub = sub0 + 2 * k + b;
+      const bool valid = sub < sub_end;
+      const int64_t addr = head_base + int64_t(ids.id[b]) * blk_bytes + (sub & sub_mask) * sub_bytes;
+      const __amdgpu_buffer_rsrc_t rs =
+          __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(addr), 0, valid ? 0x7fffffff : 0, 0x00020000);
+      if constexpr (KVT == PS_BF16) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) tr.k[b][s] = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off + 64 * s, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          tr.v[4 * b + i] = __builtin_amdgcn_raw_buffer_load_b128(rs, v_lane_off, kv_bytes + i * tok_bytes, 0);
+      } else {
+#pragma unroll
+        for (int s = 0; s < 2; ++s) tr.k[b][s] = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off + 64 * s, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          tr.v[4 * b + i] = __builtin_amdgcn_raw_buffer_load_b64(rs, v_lane_off, kv_bytes + i * tok_bytes, 0);
+      }
+    }
+  };
+
+  float m_run[kNT], l_run[kNT];
+  f32x4 acc[kNT][8];
+#pragma unroll
+  for (int t = 0; t < kNT; ++t) {
+    m_run[t] = neg_inf;
+    l_run[t] = 0.f;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) acc[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  // limited_tag: std::true_type applies the per-row limits (and guards rows that have seen nothing yet);
+  // std::false_type promises that every row of the wave sees the whole tile
+  auto compute_tile = [&](Tile<KVT>& tr, const TileIds& ids, int k, auto limited_tag) {
+    constexpr bool kLimited = decltype(limited_tag)::value;
+    const int tok0 = tok_begin + kTile * k;
+    float sc_k[2], lvs[2], inv_v[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      sc_k[b] = p.scale_log2 * ids.ksc[b];
+      lvs[b] = ids.lvs[b];
+      inv_v[b] = KVT == PS_FP8_E4M3 ? fast_exp2(-lvs[b]) : 1.f;
+    }
+    bf16x8 ka[2][4];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+      if constexpr (KVT == PS_BF16) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) ka[b][s] = bits_bf16x8(tr.k[b][s]);
+      } else {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          ka[b][2 * h] = bits_bf16x8(codes_to_bf16x8(tr.k[b][h].x, tr.k[b][h].y));
+          ka[b][2 * h + 1] = bits_bf16x8(codes_to_bf16x8(tr.k[b][h].z, tr.k[b][h].w));
+        }
+      }
+    }
+    bf16x8 pb[kNT];
+#pragma unroll
+    for (int t = 0; t < kNT; ++t) {
+      bf16x8 qb[4];
+#pragma unroll
+      for (int st = 0; st < 4; ++st) qb[st] = bits_bf16x8(sm_qb[wave][4 * t + st][lane]);
+      f32x4 s[2];
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        s[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int st = 0; st < 4; ++st) s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[b][st], qb[st], s[b], 0, 0, 0);
+      }
+      if constexpr (kLimited) {
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (tok0 + 16 * b + 4 * kg + j >= lim[t]) s[b][j] = neg_inf;
+      }
+      // The softmax reference m_run follows the row maximum lazily: it moves (and the accumulators are rescaled)
+      // only when some score gets more than kLazy ahead of it, so probabilities stay below 2^kLazy instead of below 1
+      // -- the same result by shift invariance of softmax.  The test is local to the lane (its own 8 scores, in log2
+      // units; the scales are positive, so a block's maximum scales like its scores); only when it fires somewhere in
+      // the wave is the maximum of each row put together across the row's four lanes, which must agree on m_run.
+      // A row that has seen nothing yet has m_run = -inf and stays there until a score arrives.
+      float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])) * sc_k[0],
+                       fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])) * sc_k[1]);
+      if (__builtin_amdgcn_ballot_w64(mx > m_run[t] + kLazy) != 0) {
+        mx = fmaxf(mx, lane_xor(mx, 16));
+        mx = fmaxf(mx, lane_xor(mx, 32));
+        const float m_new = (mx > m_run[t] + kLazy) ? mx : m_run[t];
+        const float alpha = (m_new == m_run[t]) ? 1.f : fast_exp2(m_run[t] - m_new);   // -inf -> finite gives 0
+        l_run[t] *= alpha;
+#pragma unroll
+        for (int cc = 0; cc < 8; ++cc) acc[t][cc] *= alpha;
+        m_run[t] = m_new;
+      }
+      const float m_ref = (kLimited && m_run[t] == neg_inf) ? 0.f : m_run[t];
+#pragma unroll
+      for (int b = 0; b < 2; ++b) {
+        const float shift = lvs[b] - m_ref;
+        float lsum = 0.f;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float pw = fast_exp2(__builtin_fmaf(s[b][j], sc_k[b], shift));
+          lsum += pw;
+          pb[t][4 * b + j] = (__bf16)pw;
+        }
+        l_run[t] += (KVT == PS_FP8_E4M3) ? lsum * inv_v[b] : lsum;
+      }
+    }
+    u32x4 vr[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      if constexpr (KVT == PS_BF16) vr[i] = tr.v[i];
+      else vr[i] = codes_to_bf16x8(tr.v[i].x, tr.v[i].y);
+    }
+    if constexpr (kLimited) {      // slots past the item's range may hold anything: zero them
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int tok = tok0 + 16 * (i >> 2) + 4 * kg + (i & 3);
+        if (tok >= tok_end) vr[i] = u32x4{0, 0, 0, 0};
+      }
+    }
+#pragma unroll
+    for (int cc = 0; cc < 8; ++cc) {
+      uint32_t w[4];
+#pragma unroll
+      for (int i2 = 0; i2 < 4; ++i2) {
+        const uint32_t a = vr[2 * i2][cc >> 1], b = vr[2 * i2 + 1][cc >> 1];
+        w[i2] = __builtin_amdgcn_perm(b, a, (cc & 1) ? 0x07060302u : 0x05040100u);
+      }
+      const bf16x8 vt = bits_bf16x8(u32x4{w[0], w[1], w[2], w[3]});
+#pragma unroll
+      for (int t = 0; t < kNT; ++t) acc[t][cc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, pb[t], acc[t][cc], 0, 0, 0);
+    }
+  };
+  // ---- stream the token range: two tile buffers, the next tile's loads go out before the math of this one,
+  // block ids one tile further ahead.  First the tiles that every row of the wave sees whole (an even number of
+  // them, so the buffers keep their roles), without limits; then the rest with the per-row limits.
+  const int n_whole = max(0, (see_all - tok_begin) / kTile) & ~1;
+  Tile<KVT> buf[2];
+  TileIds ids_cur = fetch_ids(0);
+  load_tile(buf[0], ids_cur, 0);
+  TileIds ids_nxt = fetch_ids(1);
+  int k = 0;
+  for (; k < n_whole; k += 2) {
+    const TileIds ids_nn = fetch_ids(k + 2);
+    load_tile(buf[1], ids_nxt, k + 1);
+    compute_tile(buf[0], ids_cur, k, std::false_type{});
+    const TileIds ids_n3 = fetch_ids(k + 3);
+    load_tile(buf[0], ids_nn, k + 2);
+    compute_tile(buf[1], ids_nxt, k + 1, std::false_type{});
+    ids_cur = ids_nn;
+    ids_nxt = ids_n3;
+  }
+  for (; k < n_tiles; k += 2) {
+    const TileIds ids_nn = fetch_ids(k + 2);
+    load_tile(buf[1], ids_nxt, k + 1);
+    compute_tile(buf[0], ids_cur, k, std::true_type{});
+    const TileIds ids_n3 = fetch_ids(k + 3);
+    load_tile(buf[0], ids_nn, k + 2);
+    if (k + 1 < n_tiles) compute_tile(buf[1], ids_nxt, k + 1, std::true_type{});
+    ids_cur = ids_nn;
+    ids_nxt = ids_n3;
+  }
+
+  // ---- one partial state per row, straight from the accumulators: lane (n, kg) holds O[row n][32 kg + 8 j + cc]
+#pragma unroll
+  for (int t = 0; t < kNT; ++t) {
+    if (t < nt_used) {
+      float l = l_run[t];
+      l += lane_xor(l, 16);
+      l += lane_xor(l, 32);
+      if (req_of[t] >= 0) {
+        const float inv = l > 0.f ? 1.f / l : 0.f;
+        const int row = row_base + 16 * t + n;
+        const int h = kv_head * G + row % G;
+        const int64_t slot = int64_t(p.slot_base[req_of[t]]) + split_local;
+        float* o = p.ws_o + (slot * p.num_q_heads + h) * kD + 32 * kg;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          *reinterpret_cast<f32x4*>(o + 8 * j) =
+              f32x4{acc[t][0][j], acc[t][1][j], acc[t][2][j], acc[t][3][j]} * inv;
+          *reinterpret_cast<f32x4*>(o + 8 * j + 4) =
+              f32x4{acc[t][4][j], acc[t][5][j], acc[t][6][j], acc[t][7][j]} * inv;
+        }
+        if (kg == 0)
+          p.ws_lse[slot * p.num_q_heads + h] = l > 0.f ? (m_run[t] + __builtin_amdgcn_logf(l)) * kLn2 : neg_inf;
+      }
+    }
+  }
+}
+
+int32_t launch_prefill_attention(const AttnParams& p, const ps_geometry& g, const ps_item* items, int num_items,
+                                 hipStream_t st) {
+  if (num_items <= 0) return PS_OK;
+  const int spb = g.block_size / 16;
+  if (g.head_dim != kD || g.q_dtype != PS_BF16 || g.block_size % 16 != 0 || (spb & (spb - 1)) != 0)
+    return PS_ERR_UNSUPPORTED;
+  const dim3 grid(num_items), block(256);
+  if (g.kv_dtype == PS_BF16)
+    hipLaunchKernelGGL((prefill_attention_kernel<PS_BF16>), grid, block, 0, st, p, items);
+  else if (g.kv_dtype == PS_FP8_E4M3)
+    hipLaunchKernelGGL((prefill_attention_kernel<PS_FP8_E4M3>), grid, block, 0, st, p, items);
+  else
+    return PS_ERR_UNSUPPORTED;
+  return PS_OK;
+}
+
+}  // namespace psdev

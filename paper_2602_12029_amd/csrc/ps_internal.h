@@ -24,7 +24,8 @@ struct ps_item {
   int32_t split_local;  // partial-state slot of request r is slot_base[r] + split_local
   int32_t kind;         // bit 0: 0 prefix, 1 suffix; bit 1: some row of the item sees less than tok_end
 };
-constexpr int32_t kPsItemSuffix = 1, kPsItemMasked = 2;
+// bit 2: up to 256 rows, split over the four waves of a workgroup by rows instead of by tokens (partial prefill)
+constexpr int32_t kPsItemSuffix = 1, kPsItemMasked = 2, kPsItemRowSplit = 4;
 static_assert(sizeof(ps_item) == 32, "ps_item is 8 int32");
 
 struct ps_layout {
@@ -44,8 +45,9 @@ struct ps_layout {
   int32_t prefix_variant = PS_VARIANT_WAVE, suffix_variant = PS_VARIANT_WAVE;
   int32_t prefix_chunk = 0, suffix_chunk = 0;
   int32_t max_rows_prefix = 0;       // largest n_req * G over prefix items
-  std::vector<ps_item> items;        // prefix items first, then suffix items
-  int32_t num_prefix_items = 0;
+  std::vector<ps_item> items;        // row-split prefix items, then the other prefix items, then suffix items
+  int32_t num_rowsplit_items = 0;    // launched one workgroup each by the prefill kernel, outside the schedules
+  int32_t num_prefix_items = 0;      // row-split ones included
   std::vector<int32_t> slot_base;    // [R+1]
   int64_t num_slots = 0;
 

@@ -101,12 +101,13 @@ def _check_plan(w, lay, plan, visible=None):
     seen = np.asarray(w.prefix_len)[np.asarray(w.req_prompt)] if visible is None else np.asarray(visible)
     cover = {}                                             # (request, kv head) -> list of (kind, begin, end, slot)
     for blk_off, t0, t1, req_off, n_req, head, split, kind in items.tolist():
-        assert t1 > t0 >= 0 and n_req >= 1 and 0 <= head < g.num_kv_heads and 0 <= kind <= 3
+        assert t1 > t0 >= 0 and n_req >= 1 and 0 <= head < g.num_kv_heads and 0 <= kind <= 7
+        assert n_req * g.group <= (256 if kind & 4 else 64) or n_req == 1     # rows one item may carry
         assert t0 % g.block_size == 0
         reqs = req_list[req_off:req_off + n_req].tolist()
         assert len(reqs) == n_req
         if kind & 1:
-            assert n_req == 1 and not kind & 2
+            assert n_req == 1 and not kind & 6
             r = reqs[0]
             assert blk_off == nprefix_blk + t["suffix_blk_indptr"][r] and t1 <= w.suffix_len[r]
             cover.setdefault((r, head), []).append((1, t0, t1, split))
@@ -178,21 +179,31 @@ def test_visible_lengths_plan_invariants_and_errors():
 
 
 def test_causal_chunk_plan_skips_what_no_row_sees():
-    """A chunk of new tokens on one prompt, token i seeing cached + i + 1 tokens: row groups of 64 / G requests; a
-    group's items end at its last row's length, and fully visible ranges are not marked."""
+    """A chunk of new tokens on one prompt, token i seeing cached + i + 1 tokens.  Wavefront kernel: row groups of
+    64 / G requests; a group's items end at its last row's length, and fully visible ranges are not marked.
+    Matrix-core kernels: the group's 160 rows fit one row-split item per token range and KV head."""
     geo = wl.Geometry(8, 2, 128, 16, "bf16", "bf16")
     cached, chunk = 100, 40
     w = wl.make_workload("chunk", geo, chunk, [cached + chunk], [list(range(chunk))], [0] * chunk, seed=0)
     pool, lay, _, _ = _both(w)
     visible = np.arange(cached + 1, cached + chunk + 1)
-    B.ps_layout_replan(lay, B.plan_options(64, 32))
-    B.ps_layout_set_visible(lay, chunk, visible)
-    plan = B.ps_layout_plan(lay, chunk)
-    _check_plan(w, lay, plan, visible)
-    items = plan["items"]
-    assert sorted({(a, b) for a, b in items[:, 1:3].tolist()}) == [(0, 64), (64, 116), (64, 128), (128, 140)]
-    assert not (items[items[:, 2] <= 100][:, 7] & 2).any()                # the old cache is seen by every row
-    assert (np.diff(plan["slot_base"]) == np.ceil(visible / 64)).all()    # partial states only where a row sees in
+    for variant, ranges in ((B.PS_VARIANT_WAVE, [(0, 64), (64, 116), (64, 128), (128, 140)]),
+                            (B.PS_VARIANT_AUTO, [(0, 64), (64, 128), (128, 140)])):
+        B.ps_layout_replan(lay, B.plan_options(64, 32, variant, variant))
+        B.ps_layout_set_visible(lay, chunk, visible)
+        plan = B.ps_layout_plan(lay, chunk)
+        _check_plan(w, lay, plan, visible)
+        items = plan["items"]
+        assert sorted({(a, b) for a, b in items[:, 1:3].tolist()}) == ranges
+        assert not (items[items[:, 2] <= 100][:, 7] & 2).any()                # the old cache is seen by every row
+        assert (np.diff(plan["slot_base"]) == np.ceil(visible / 64)).all()    # partial states only where a row sees in
+        if variant == B.PS_VARIANT_AUTO:
+            assert len(items) == 3 * 2 and items[:, 7].tolist() == [4, 4, 6, 6, 2, 2]   # row-split items lead
+            assert items[items[:, 1] == 0][:, 4].tolist() == [40, 40]         # all 40 requests in one item per KV head
+            # the last range is seen by 12 requests = 48 rows: an ordinary item, the only kind in the schedule
+            assert B.ps_layout_schedule(lay, 0)["items"][:, 7].tolist() == [2, 2]
+        else:
+            assert not (items[:, 7] & 4).any()
     B.ps_layout_release(pool, lay)
     B.ps_pool_destroy(pool)
 
