@@ -221,44 +221,65 @@ __global__ __launch_bounds__(256, 1) void prefill_attention_kernel(AttnParams p,
         }
       }
     }
-    bf16x8 pb[kNT];
+    // Scores of all four row tiles first: eight independent accumulation chains (row tile x block), issued
+    // round-robin so that no matrix instruction waits for the one before it.
+    f32x4 s[kNT][2];
 #pragma unroll
-    for (int t = 0; t < kNT; ++t) {
-      bf16x8 qb[4];
+    for (int t = 0; t < kNT; ++t)
 #pragma unroll
-      for (int st = 0; st < 4; ++st) qb[st] = bits_bf16x8(sm_qb[wave][4 * t + st][lane]);
-      f32x4 s[2];
+      for (int b = 0; b < 2; ++b) s[t][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+    // (the lane index goes through an empty asm so that the query operands are read from LDS tile by tile: hoisted
+    // out of the streaming loop they would occupy 64 registers that the accumulators and tile buffers need)
+    int q_lane = lane;
+    asm volatile("" : "+v"(q_lane));
 #pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        s[b] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int st = 0; st < 4; ++st)
 #pragma unroll
-        for (int st = 0; st < 4; ++st) s[b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[b][st], qb[st], s[b], 0, 0, 0);
+      for (int t = 0; t < kNT; ++t) {
+        const bf16x8 qb = bits_bf16x8(sm_qb[wave][4 * t + st][q_lane]);
+#pragma unroll
+        for (int b = 0; b < 2; ++b) s[t][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[b][st], qb, s[t][b], 0, 0, 0);
       }
-      if constexpr (kLimited) {
+    if constexpr (kLimited) {
+#pragma unroll
+      for (int t = 0; t < kNT; ++t)
 #pragma unroll
         for (int b = 0; b < 2; ++b)
 #pragma unroll
           for (int j = 0; j < 4; ++j)
-            if (tok0 + 16 * b + 4 * kg + j >= lim[t]) s[b][j] = neg_inf;
-      }
-      // The softmax reference m_run follows the row maximum lazily: it moves (and the accumulators are rescaled)
-      // only when some score gets more than kLazy ahead of it, so probabilities stay below 2^kLazy instead of below 1
-      // -- the same result by shift invariance of softmax.  The test is local to the lane (its own 8 scores, in log2
-      // units; the scales are positive, so a block's maximum scales like its scores); only when it fires somewhere in
-      // the wave is the maximum of each row put together across the row's four lanes, which must agree on m_run.
-      // A row that has seen nothing yet has m_run = -inf and stays there until a score arrives.
-      float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])) * sc_k[0],
-                       fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])) * sc_k[1]);
-      if (__builtin_amdgcn_ballot_w64(mx > m_run[t] + kLazy) != 0) {
-        mx = fmaxf(mx, lane_xor(mx, 16));
-        mx = fmaxf(mx, lane_xor(mx, 32));
-        const float m_new = (mx > m_run[t] + kLazy) ? mx : m_run[t];
+            if (tok0 + 16 * b + 4 * kg + j >= lim[t]) s[t][b][j] = neg_inf;
+    }
+    // The softmax reference m_run follows the row maximum lazily: it moves (and the accumulators are rescaled)
+    // only when some score gets more than kLazy ahead of it, so probabilities stay below 2^kLazy instead of below 1
+    // -- the same result by shift invariance of softmax.  The test is local to the lane (its own scores, in log2
+    // units; the scales are positive, so a block's maximum scales like its scores) and one vote covers the four
+    // row tiles; only when it fires somewhere in the wave is the maximum of each row put together across the
+    // row's four lanes, which must agree on m_run.  A row that has seen nothing yet has m_run = -inf and stays
+    // there until a score arrives.
+    float mx[kNT];
+    bool ahead = false;
+#pragma unroll
+    for (int t = 0; t < kNT; ++t) {
+      mx[t] = fmaxf(fmaxf(fmaxf(s[t][0][0], s[t][0][1]), fmaxf(s[t][0][2], s[t][0][3])) * sc_k[0],
+                    fmaxf(fmaxf(s[t][1][0], s[t][1][1]), fmaxf(s[t][1][2], s[t][1][3])) * sc_k[1]);
+      ahead |= mx[t] > m_run[t] + kLazy;
+    }
+    if (__builtin_amdgcn_ballot_w64(ahead) != 0) {
+#pragma unroll
+      for (int t = 0; t < kNT; ++t) {
+        float row_mx = fmaxf(mx[t], lane_xor(mx[t], 16));
+        row_mx = fmaxf(row_mx, lane_xor(row_mx, 32));
+        const float m_new = (row_mx > m_run[t] + kLazy) ? row_mx : m_run[t];
         const float alpha = (m_new == m_run[t]) ? 1.f : fast_exp2(m_run[t] - m_new);   // -inf -> finite gives 0
         l_run[t] *= alpha;
 #pragma unroll
         for (int cc = 0; cc < 8; ++cc) acc[t][cc] *= alpha;
         m_run[t] = m_new;
       }
+    }
+    bf16x8 pb[kNT];
+#pragma unroll
+    for (int t = 0; t < kNT; ++t) {
       const float m_ref = (kLimited && m_run[t] == neg_inf) ? 0.f : m_run[t];
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
@@ -266,7 +287,7 @@ __global__ __launch_bounds__(256, 1) void prefill_attention_kernel(AttnParams p,
         float lsum = 0.f;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const float pw = fast_exp2(__builtin_fmaf(s[b][j], sc_k[b], shift));
+          const float pw = fast_exp2(__builtin_fmaf(s[t][b][j], sc_k[b], shift));
           lsum += pw;
           pb[t][4 * b + j] = (__bf16)pw;
         }
