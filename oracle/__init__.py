@@ -11,6 +11,9 @@ the Eq. 9 block-count / refcount invariants.  The cache-writing side (e4m3
 encoder, ingest, append, table growth; tests/test_oracle_kv_update.py) is pinned
 by the format table, an independently written quantiser, exact round trips,
 error bounds, order-of-arrival identities between append and ingest, scalar
-brute force and a hand-worked table.  No function here is unpinned.
+brute force and a hand-worked table.  The third sharing level (layout.build_layout_tree, a
+context several prompts begin with; tests/test_oracle_tree.py) is pinned by a hand-worked table, the
+block-count and refcount invariants, brute-force dense attention and bitwise identity with the
+two-level oracle on the flattened batch.  No function here is unpinned.
 """
 from . import attention, fp8, kv_update, layout  # noqa: F401

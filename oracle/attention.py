@@ -99,7 +99,8 @@ def merge_states(o_parts: np.ndarray, lse_parts: np.ndarray):
 
 
 def request_kv(kv, scales, kv_dtype, lay, r: int, prefix_visible=None):
-    """Concatenated (K, V) of request r: prefix of its prompt, then its own suffix.
+    """Concatenated (K, V) of request r: its prompt's root if there is one, the prefix of its prompt, then its
+    own suffix.
 
     prefix_visible[r] (optional) cuts the prefix to its first prefix_visible[r] tokens.  This is how a
     chunk of new prompt tokens is prefilled against the cache (System Design, execution pipeline step 1:
@@ -111,12 +112,18 @@ def request_kv(kv, scales, kv_dtype, lay, r: int, prefix_visible=None):
     seen = int(lay.prefix_len[p]) if prefix_visible is None else int(prefix_visible[r])
     if not 0 <= seen <= int(lay.prefix_len[p]):
         raise ValueError("visible prefix length out of range")
-    kp, vp = gather_segment(kv, scales, kv_dtype,
-                            lay.prefix_blk[lay.prefix_blk_indptr[p]:lay.prefix_blk_indptr[p + 1]], seen)
-    ks, vs = gather_segment(kv, scales, kv_dtype,
-                            lay.suffix_blk[lay.suffix_blk_indptr[r]:lay.suffix_blk_indptr[r + 1]],
-                            int(lay.suffix_len[r]))
-    return np.concatenate([kp, ks], axis=0), np.concatenate([vp, vs], axis=0)
+    parts = []
+    # a context several prompts have in common (a root, layout.build_layout_tree) comes first, whole
+    t = -1 if getattr(lay, "prompt_root", None) is None else int(lay.prompt_root[p])
+    if t >= 0:
+        parts.append(gather_segment(kv, scales, kv_dtype, lay.root_blk[lay.root_blk_indptr[t]:lay.root_blk_indptr[t + 1]],
+                                    int(lay.root_len[t])))
+    parts.append(gather_segment(kv, scales, kv_dtype,
+                                lay.prefix_blk[lay.prefix_blk_indptr[p]:lay.prefix_blk_indptr[p + 1]], seen))
+    parts.append(gather_segment(kv, scales, kv_dtype,
+                                lay.suffix_blk[lay.suffix_blk_indptr[r]:lay.suffix_blk_indptr[r + 1]],
+                                int(lay.suffix_len[r])))
+    return np.concatenate([k for k, _ in parts], axis=0), np.concatenate([v for _, v in parts], axis=0)
 
 
 def decode_attention(q_bits, q_dtype: str, kv, scales, kv_dtype: str, lay, requests=None, prefix_visible=None):

@@ -1,4 +1,5 @@
-"""Refcounted two-segment block table, reference policy (oracle side, test infrastructure).
+"""Refcounted block table (two segments, optionally a third shared level above), reference policy (oracle side,
+test infrastructure).
 
 Problem statement followed: a pool of fixed-size cached KV blocks (Background,
 "Multi-Model Inference and Prefix Caching"); every decode module starts from
@@ -63,6 +64,13 @@ class Layout:
     suffix_blk_indptr: np.ndarray   # [R+1]
     suffix_blk: np.ndarray
     released: bool = False
+    # third level (build_layout_tree): contexts several prompts have in common
+    root_len: np.ndarray = None            # [T]
+    prompt_root: np.ndarray = None         # [P], -1 = the prompt has no root
+    root_blk_indptr: np.ndarray = None     # [T+1]
+    root_blk: np.ndarray = None
+    root_group_indptr: np.ndarray = None   # [T+1]  root -> the requests of all its prompts, ascending
+    root_group_req: np.ndarray = None
 
 
 def build_layout(pool: BlockPool, block_size: int, prefix_len, req_prompt, req_model, suffix_len) -> Layout:
@@ -118,10 +126,81 @@ def build_layout(pool: BlockPool, block_size: int, prefix_len, req_prompt, req_m
                   np.asarray(group_req, np.int32), suffix_indptr, np.asarray(suffix_blk, np.int32))
 
 
+def build_layout_tree(pool: BlockPool, block_size: int, root_len, prompt_root, prefix_len, req_prompt, req_model,
+                      suffix_len) -> Layout:
+    """Three-level table: root -> prompt -> request.
+
+    Several prompts may begin with the same context (Background, "Multi-Model Inference and Prefix Caching": a common
+    system prompt or a shared document in front of each session's own history); that common part -- a *root* -- is
+    stored once, like a prompt's prefix is stored once for its models (Eq. 9 applied one level up).  The cache of
+    request r on prompt p with root t = prompt_root[p] is [root t ; prefix p ; suffix r]; prompt_root[p] = -1 means
+    the prompt has no root.
+
+    Policy: roots in ascending index take ceil(L/B) blocks each from the head of the free list, then prompts and
+    requests exactly as build_layout does.  A root block's refcount is the number of requests below the root; a
+    root's last block may be partially filled and stays shared and read-only; a prompt's own prefix starts in a
+    fresh block.  A root no prompt names is an error; a batch that does not fit leaves the pool untouched.
+    """
+    root_len = np.asarray(root_len, dtype=np.int64)
+    prompt_root = np.asarray(prompt_root, dtype=np.int64)
+    prefix_arr = np.asarray(prefix_len, dtype=np.int64)
+    suffix_arr = np.asarray(suffix_len, dtype=np.int64)
+    req_prompt_arr = np.asarray(req_prompt, dtype=np.int64)
+    num_t = len(root_len)
+    if len(prompt_root) != len(prefix_arr) or (root_len < 0).any():
+        raise LayoutError("one root index per prompt, root lengths >= 0")
+    if len(prompt_root) and (prompt_root.min() < -1 or prompt_root.max() >= num_t):
+        raise LayoutError("prompt names an unknown root")
+    if len(req_prompt_arr) and (req_prompt_arr.min() < 0 or req_prompt_arr.max() >= len(prefix_arr)):
+        raise LayoutError("request names an unknown prompt")
+    below = [[] for _ in range(num_t)]
+    for r, p in enumerate(req_prompt_arr):
+        if prompt_root[p] >= 0:
+            below[int(prompt_root[p])].append(r)
+    for t in range(num_t):
+        if not (prompt_root == t).any():
+            raise LayoutError("root without a prompt")
+    nb_root = (root_len + block_size - 1) // block_size
+    needed = int(nb_root.sum() + ((prefix_arr + block_size - 1) // block_size).sum()
+                 + ((suffix_arr + block_size - 1) // block_size).sum())
+    if needed > len(pool.free):
+        raise OutOfBlocks(f"need {needed} blocks, {len(pool.free)} free")
+    taken = []
+    root_indptr = np.zeros(num_t + 1, np.int32)
+    for t in range(num_t):
+        for _ in range(int(nb_root[t])):
+            taken.append(pool.free.popleft())
+        root_indptr[t + 1] = len(taken)
+    try:
+        lay = build_layout(pool, block_size, prefix_len, req_prompt, req_model, suffix_len)
+    except LayoutError:
+        pool.free.extendleft(reversed(taken))           # bad lower levels: hand the root blocks back, in order
+        raise
+    for t in range(num_t):
+        pool.refcount[taken[root_indptr[t]:root_indptr[t + 1]]] += len(below[t])
+    group_indptr = np.zeros(num_t + 1, np.int32)
+    group = []
+    for t in range(num_t):
+        group.extend(below[t])
+        group_indptr[t + 1] = len(group)
+    lay.root_len = root_len.astype(np.int32)
+    lay.prompt_root = prompt_root.astype(np.int32)
+    lay.root_blk_indptr = root_indptr
+    lay.root_blk = np.asarray(taken, np.int32)
+    lay.root_group_indptr = group_indptr
+    lay.root_group_req = np.asarray(group, np.int32)
+    return lay
+
+
 def release_layout(pool: BlockPool, lay: Layout) -> None:
     if lay.released:
         raise RefcountError("layout released twice")
     drop = np.zeros(pool.num_blocks, dtype=np.int64)
+    if lay.root_len is not None:
+        for t in range(len(lay.root_len)):
+            k = int(lay.root_group_indptr[t + 1] - lay.root_group_indptr[t])
+            for blk in lay.root_blk[lay.root_blk_indptr[t]:lay.root_blk_indptr[t + 1]]:
+                drop[blk] += k
     for p in range(len(lay.prefix_len)):
         k = int(lay.group_indptr[p + 1] - lay.group_indptr[p])
         for blk in lay.prefix_blk[lay.prefix_blk_indptr[p]:lay.prefix_blk_indptr[p + 1]]:

@@ -9,8 +9,14 @@ from oracle import layout as ol
 def oracle_setup(w: wl.Workload, free_order=None):
     """Oracle-side block tables and a pool filled through them."""
     pool = ol.BlockPool(w.num_blocks, w.free_order if free_order is None else free_order)
-    lay = ol.build_layout(pool, w.geometry.block_size, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
-    data = wl.fill_pool(w, lay.prefix_blk_indptr, lay.prefix_blk, lay.suffix_blk_indptr, lay.suffix_blk)
+    if w.num_roots:
+        lay = ol.build_layout_tree(pool, w.geometry.block_size, w.root_len, w.prompt_root, w.prefix_len, w.req_prompt,
+                                   w.req_model, w.suffix_len)
+        data = wl.fill_pool(w, lay.prefix_blk_indptr, lay.prefix_blk, lay.suffix_blk_indptr, lay.suffix_blk,
+                            lay.root_blk_indptr, lay.root_blk)
+    else:
+        lay = ol.build_layout(pool, w.geometry.block_size, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
+        data = wl.fill_pool(w, lay.prefix_blk_indptr, lay.prefix_blk, lay.suffix_blk_indptr, lay.suffix_blk)
     return pool, lay, data
 
 

@@ -16,7 +16,9 @@ from .generate import (  # noqa: F401
     e4m3_encode,
     fill_pool,
     ideal_bytes,
+    make_tree_workload,
     make_workload,
     named_chunk_prefill,
+    named_tree_workload,
     named_workload,
 )

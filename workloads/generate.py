@@ -12,7 +12,7 @@ PCG64 streams keyed by (seed, tag, index), so every item can be regenerated on
 its own and in any order.  Draw tags: 1 lengths, 2 membership, 3 free order,
 4 Q, 5 prefix K/V (index = prompt), 6 suffix K/V (index = request), 7 / 8 unquantised
 prefix / suffix K/V as a worker hands them over, 9 the K/V of the token each request
-appends in a decode step (index = step).
+appends in a decode step (index = step), 10 root K/V (index = root).
 
 Storage formats: 'f32' -> float32, 'bf16' -> uint16 bit patterns (fp32 draws
 rounded to nearest-even), 'fp8_e4m3' -> uint8 OCP e4m3fn codes plus one fp32
@@ -108,6 +108,13 @@ class Workload:
     num_blocks: int                   # size of the physical pool
     free_order: np.ndarray            # int32 [num_blocks], a permutation
     _cache: Dict = field(default_factory=dict, repr=False)
+    # optional third level: contexts that several prompts begin with (make_tree_workload)
+    root_len: np.ndarray = field(default_factory=lambda: np.zeros(0, np.int32))   # int32 [T]
+    prompt_root: Optional[np.ndarray] = None                                      # int32 [P], -1 = no root
+
+    @property
+    def num_roots(self) -> int:
+        return int(self.root_len.shape[0])
 
     @property
     def num_prompts(self) -> int:
@@ -120,7 +127,8 @@ class Workload:
     def blocks_needed(self) -> int:
         b = self.geometry.block_size
         return int(((self.prefix_len.astype(np.int64) + b - 1) // b).sum()
-                   + ((self.suffix_len.astype(np.int64) + b - 1) // b).sum())
+                   + ((self.suffix_len.astype(np.int64) + b - 1) // b).sum()
+                   + ((self.root_len.astype(np.int64) + b - 1) // b).sum())
 
     # ---- stored bits -----------------------------------------------------
     def _normal(self, tag: int, index: int, shape) -> np.ndarray:
@@ -150,6 +158,9 @@ class Workload:
 
     def suffix_kv(self, request: int) -> Segment:
         return self._segment(6, request, int(self.suffix_len[request]))
+
+    def root_kv(self, root: int) -> Segment:
+        return self._segment(10, root, int(self.root_len[root]))
 
     # ---- unquantised sources (what a prefill or decode worker hands over) ----
     def _source(self, tag: int, index: int, tokens: int):
@@ -201,7 +212,8 @@ class PoolData:
     scales: Optional[np.ndarray]
 
 
-def fill_pool(w: Workload, prefix_blk_indptr, prefix_blk, suffix_blk_indptr, suffix_blk) -> PoolData:
+def fill_pool(w: Workload, prefix_blk_indptr, prefix_blk, suffix_blk_indptr, suffix_blk, root_blk_indptr=None,
+              root_blk=None) -> PoolData:
     """Scatter every segment's stored bits into the pool at the blocks a block table names.
 
     The tables come from whichever layout builder is under test; this routine
@@ -235,13 +247,18 @@ def fill_pool(w: Workload, prefix_blk_indptr, prefix_blk, suffix_blk_indptr, suf
         put(w.prefix_kv(p), prefix_blk[prefix_blk_indptr[p]:prefix_blk_indptr[p + 1]])
     for r in range(w.num_requests):
         put(w.suffix_kv(r), suffix_blk[suffix_blk_indptr[r]:suffix_blk_indptr[r + 1]])
+    if w.num_roots:
+        root_blk = np.asarray(root_blk)
+        for t in range(w.num_roots):
+            put(w.root_kv(t), root_blk[root_blk_indptr[t]:root_blk_indptr[t + 1]])
     return PoolData(kv, scales)
 
 
 def ideal_bytes(w: Workload) -> int:
     """HBM bytes an ideal kernel moves: shared KV once + private KV (+ fp8 scales) + Q + O."""
     g = w.geometry
-    total = int(w.prefix_len.astype(np.int64).sum() + w.suffix_len.astype(np.int64).sum()) * g.token_bytes
+    total = int(w.prefix_len.astype(np.int64).sum() + w.suffix_len.astype(np.int64).sum()
+                + w.root_len.astype(np.int64).sum()) * g.token_bytes
     if g.kv_dtype == "fp8_e4m3":
         total += w.blocks_needed() * g.num_kv_heads * 2 * 4
     total += 2 * w.num_requests * g.num_q_heads * g.head_dim * ELEM_BYTES[g.q_dtype]
@@ -273,6 +290,40 @@ def make_workload(name: str, geometry: Geometry, num_models: int, prefix_len: Se
     w.num_blocks = int(np.ceil(pool_factor * needed)) if needed else 0
     w.free_order = _rng(seed, 3).permutation(w.num_blocks).astype(np.int32)
     return w
+
+
+def make_tree_workload(name: str, geometry: Geometry, num_models: int, root_len: Sequence[int],
+                       prompt_root: Sequence[int], prefix_len: Sequence[int], membership: Sequence[Sequence[int]],
+                       suffix_len: Sequence[int], pool_factor: float = 1.0, seed: int = 0) -> Workload:
+    """A workload with a third level: root_len[t] tokens that every prompt p with prompt_root[p] = t begins with (a
+    common system prompt or shared document in front of each session's own context); prefix_len[p] is then the
+    prompt's own part.  prompt_root[p] = -1: no root."""
+    w = make_workload(name, geometry, num_models, prefix_len, membership, suffix_len, pool_factor, seed)
+    w.root_len = np.asarray(root_len, np.int32)
+    w.prompt_root = np.asarray(prompt_root, np.int32)
+    if w.prompt_root.shape != w.prefix_len.shape:
+        raise ValueError("one root index per prompt")
+    needed = w.blocks_needed()
+    w.num_blocks = int(np.ceil(pool_factor * needed)) if needed else 0
+    w.free_order = _rng(seed, 3).permutation(w.num_blocks).astype(np.int32)
+    return w
+
+
+def named_tree_workload(name: str, seed: int = 0) -> Workload:
+    """Three-level stand-ins for multi-agent sessions that all start from one system prompt / tool description:
+
+    tree_tiny  1 root of 40 tokens under 2 of 3 prompts, fp32, 4 q / 2 kv heads, d 64
+    tree_b8    1 root of 2048 tokens under 32 sessions, each session 2048 own tokens shared by M = 4 models,
+               suffix U[1,512], 32/8 heads, d 128, bf16 (the 8B-shaped batch with half of every prefix in common)
+    """
+    if name == "tree_tiny":
+        return make_tree_workload(name, Geometry(4, 2, 64, 16, "f32", "f32"), 2, [40], [0, -1, 0], [24, 50, 7],
+                                  [[0, 1], [0], [1]], [3, 0, 9, 20], 1.0, seed)
+    if name == "tree_b8":
+        suffix = _rng(seed, 1).integers(1, 513, 128)
+        return make_tree_workload(name, Geometry(32, 8, 128, 16, "bf16", "bf16"), 4, [2048], [0] * 32, [2048] * 32,
+                                  [[0, 1, 2, 3]] * 32, suffix, 1.0, seed)
+    raise ValueError(name)
 
 
 def chunk_prefill_workload(name: str, geometry: Geometry, cached_len: Sequence[int], chunk_len: Sequence[int],
