@@ -95,6 +95,25 @@ int32_t ps_kv_layout(ps_pool* pool, const ps_geometry* geometry,
                      int32_t num_prompts, const int32_t* prefix_len,
                      int32_t num_requests, const int32_t* req_prompt, const int32_t* req_model,
                      const int32_t* suffix_len, ps_layout** out);
+/* ps_kv_layout_tree: the same table with a third sharing level.  Several prompts may begin with one context
+ * (Background, "Multi-Model Inference and Prefix Caching": a common system prompt or a shared document in front of
+ * each session's own history); such a root is stored once, as a prompt's prefix is stored once for its models (Eq. 9
+ * applied one level up).  Host inputs as above plus root_len[num_roots] and prompt_root[P] (index of the root prompt
+ * p begins with, -1 = none); prefix_len[p] is then the prompt's own part, and request r on prompt p attends over
+ * [root ; prefix p ; suffix r].  Policy: roots in ascending index take ceil(L/B) blocks each first, then prompts and
+ * requests as in ps_kv_layout; a root block's refcount rises by the number of requests below the root; a root's
+ * partially filled last block stays shared and read-only, and a prompt's own prefix starts in a fresh block.
+ * num_roots = 0 is ps_kv_layout.  Additional errors: PS_ERR_INVALID_ARG for a root index out of range or a root no
+ * prompt begins with.  A request's partial states are numbered root splits, prefix splits, suffix splits. */
+int32_t ps_kv_layout_tree(ps_pool* pool, const ps_geometry* geometry, int32_t num_roots, const int32_t* root_len,
+                          int32_t num_prompts, const int32_t* prompt_root, const int32_t* prefix_len,
+                          int32_t num_requests, const int32_t* req_prompt, const int32_t* req_model,
+                          const int32_t* suffix_len, ps_layout** out);
+/* Host views of the root level (valid until release; any output pointer may be NULL): root_blk_indptr[T+1],
+ * root_blk[..], root_group_indptr[T+1], root_group_req[..] (the requests below a root, ascending). */
+int32_t ps_layout_root_tables(const ps_layout* layout, int32_t* num_roots, const int32_t** root_blk_indptr,
+                              const int32_t** root_blk, const int32_t** root_group_indptr,
+                              const int32_t** root_group_req);
 /* Drops the batch's references (blocks reaching zero join the free-list tail in ascending id) and
  * destroys the layout.  PS_ERR_REFCOUNT leaves pool and layout unchanged. */
 int32_t ps_layout_release(ps_pool* pool, ps_layout* layout);
@@ -115,19 +134,20 @@ int32_t ps_layout_lengths(const ps_layout* layout, const int32_t** prefix_len, c
  * layout's table blob and the sizes reported below. */
 int32_t ps_layout_replan(ps_layout* layout, const ps_plan_options* options);
 /* Plan introspection (host, valid until the next replan/release).  items is int32[num_items][8]:
- * {first block index in the concatenated (prefix ++ suffix) block array, token begin, token end,
+ * {first block index in the concatenated (prefix ++ suffix ++ root) block array, token begin, token end,
  *  first index into the request list, number of requests, kv head, split index within the request's
  *  partial states, 0 = prefix / 1 = suffix}.  slot_base is int32[R+1]: request r owns partial-state
  * slots [slot_base[r], slot_base[r+1]), prefix splits first. */
 int32_t ps_layout_plan(const ps_layout* layout, int32_t* num_items, const int32_t** items,
                        const int32_t** slot_base, int32_t* prefix_variant, int32_t* suffix_variant);
 /* The request list the items index into (host view, valid until the next replan/release): a prompt's
- * requests in ascending order for every prompt (group_req), then 0..R-1 (private-suffix items), then,
- * where visible lengths keep part of a sharing group out of a prefix chunk, the sub-lists of those
+ * requests in ascending order for every prompt (group_req), then 0..R-1 (private-suffix items), then
+ * root_group_req, then, where visible lengths keep part of a sharing group out of a prefix chunk, the sub-lists of those
  * chunks.  The last field of an item is a bit set: bit 0 = private suffix, bit 1 = some row of the item
- * sees fewer tokens than the item's token end, bit 2 = a partial-prefill item of up to 256 rows, which a
- * workgroup of the prefill kernel splits over its waves by rows (such items lead the item array and are
- * not part of the schedules below). */
+ * sees fewer tokens than the item's token end, bit 2 = an item of up to 256 rows (the new tokens of a
+ * context in a partial prefill, the requests below a root), which a workgroup of the prefill kernel splits
+ * over its waves by rows (such items lead the item array and are not part of the schedules below), bit 3 =
+ * a root segment. */
 int32_t ps_layout_request_list(const ps_layout* layout, int32_t* count, const int32_t** list);
 
 /* Schedule of the persistent matrix-core kernel for one launchable set of items (which: 0 = prefix items,
@@ -220,7 +240,7 @@ int32_t ps_kv_append(const ps_layout* layout, const void* dev_tables, const void
                      void* kv_pool, float* kv_scales, void* stream);
 
 /* ps_kv_ingest (device, asynchronous): stores whole segments handed over as contiguous tensors.  which: 0 =
- * every prompt's shared prefix, 1 = every request's private suffix.  src_k, src_v: device, token-major
+ * every prompt's shared prefix, 1 = every request's private suffix, 2 = every root.  src_k, src_v: device, token-major
  * [T][Hkv][d] with T = the sum of the segment lengths of that kind, segments back to back in index order;
  * element (t, h, c) at t * src_stride_tok + h * src_stride_head + c (strides in elements, multiples of 16
  * bytes, base pointers 16-byte aligned); bf16 for bf16 and e4m3 pools, float32 for float32 pools.  Token j of

@@ -25,7 +25,7 @@ EXPORTS = [
     "ps_layout_schedule", "ps_layout_device_bytes", "ps_layout_upload", "ps_workspace_bytes", "ps_workspace_layout",
     "ps_prefix_attention", "ps_suffix_attention", "ps_prefix_suffix_attention", "ps_merge_states", "ps_decode_attention",
     "ps_layout_lengths", "ps_layout_append", "ps_kv_append", "ps_kv_ingest",
-    "ps_layout_set_visible", "ps_layout_request_list",
+    "ps_layout_set_visible", "ps_layout_request_list", "ps_kv_layout_tree", "ps_layout_root_tables",
     "ps_strerror", "ps_last_hip_error",
 ]
 
@@ -156,6 +156,33 @@ def ps_kv_layout(pool, geo: ps_geometry, prefix_len, req_prompt, req_model, suff
     st = _lib().ps_kv_layout(pool, C.byref(geo), C.c_int32(pl.size), plp, C.c_int32(rp.size), rpp, rmp, slp, C.byref(out))
     _check(st, "ps_kv_layout")
     return out
+
+
+def ps_kv_layout_tree(pool, geo: ps_geometry, root_len, prompt_root, prefix_len, req_prompt, req_model, suffix_len):
+    """Three-level table: roots (contexts several prompts begin with), prompts, requests."""
+    rl, rlp = _i32(root_len)
+    pr, prp = _i32(prompt_root)
+    pl, plp = _i32(prefix_len)
+    rp, rpp = _i32(req_prompt)
+    rm, rmp = _i32(req_model)
+    sl, slp = _i32(suffix_len)
+    if not (rp.shape == rm.shape == sl.shape) or pr.shape != pl.shape:
+        raise ValueError("array lengths do not match")
+    out = C.c_void_p()
+    st = _lib().ps_kv_layout_tree(pool, C.byref(geo), C.c_int32(rl.size), rlp, C.c_int32(pl.size), prp, plp,
+                                  C.c_int32(rp.size), rpp, rmp, slp, C.byref(out))
+    _check(st, "ps_kv_layout_tree")
+    return out
+
+
+def ps_layout_root_tables(layout) -> dict:
+    n = C.c_int32()
+    ptrs = [_I32P() for _ in range(4)]
+    _check(_lib().ps_layout_root_tables(layout, C.byref(n), *[C.byref(p) for p in ptrs]), "ps_layout_root_tables")
+    bi = _view(ptrs[0], n.value + 1)
+    gi = _view(ptrs[2], n.value + 1)
+    return {"root_blk_indptr": bi, "root_blk": _view(ptrs[1], int(bi[-1])),
+            "root_group_indptr": gi, "root_group_req": _view(ptrs[3], int(gi[-1]))}
 
 
 def ps_layout_release(pool, layout):

@@ -131,9 +131,9 @@ int32_t ps_prefix_suffix_attention(const ps_layout* lay, const void* dev_tables,
 
 int32_t ps_kv_ingest(const ps_layout* lay, const void* dev_tables, int32_t which, const void* src_k, const void* src_v,
                      int64_t src_stride_tok, int64_t src_stride_head, void* kv_pool, float* kv_scales, void* stream) {
-  if (!lay || !dev_tables || which < 0 || which > 1) return PS_ERR_INVALID_ARG;
+  if (!lay || !dev_tables || which < 0 || which > 2) return PS_ERR_INVALID_ARG;
   const ps_geometry& g = lay->geo;
-  const size_t entries = which ? lay->suffix_blk.size() : lay->prefix_blk.size();
+  const size_t entries = which == 0 ? lay->prefix_blk.size() : (which == 1 ? lay->suffix_blk.size() : lay->root_blk.size());
   if (entries == 0) return PS_OK;
   if (!src_k || !src_v || !kv_pool || (g.kv_dtype == PS_FP8_E4M3 && !kv_scales)) return PS_ERR_INVALID_ARG;
   const int64_t esz = g.kv_dtype == PS_F32 ? 4 : 2;   // source element: float32 for float32 pools, else bf16

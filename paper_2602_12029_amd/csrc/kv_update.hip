@@ -246,8 +246,10 @@ int32_t launch_kv_ingest(const ps_layout* lay, const void* dev_tables, int which
                          int64_t src_s_tok, int64_t src_s_head, void* kv, float* scales, hipStream_t st) {
   const ps_geometry& g = lay->geo;
   const int n_prefix = int(lay->prefix_blk.size());
-  const int entry0 = which ? n_prefix : 0;
-  const int num_entries = which ? int(lay->suffix_blk.size()) : n_prefix;
+  const int n_suffix = int(lay->suffix_blk.size());
+  // entries follow the concatenated block array: prefixes, suffixes, roots
+  const int entry0 = which == 0 ? 0 : (which == 1 ? n_prefix : n_prefix + n_suffix);
+  const int num_entries = which == 0 ? n_prefix : (which == 1 ? n_suffix : int(lay->root_blk.size()));
   if (num_entries == 0) return PS_OK;
   const int64_t tiles = int64_t(num_entries) * g.num_kv_heads * 2;
   const int64_t grid64 = (tiles + 3) / 4;

@@ -61,6 +61,7 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   int64_t total = 0;
   for (int32_t l : lay->prefix_len) total += l;
   for (int32_t l : lay->suffix_len) total += l;
+  for (int32_t l : lay->root_len) total += l;
   total *= g.num_kv_heads;
   // aim for about one full-size chunk per compute unit: long items amortise the per-item merge and keep
   // the number of partial states (workspace traffic) low; the many small suffix items fill the gaps
@@ -98,7 +99,7 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   // length among its rows, and it is marked where some row sees less than that.
   const bool limited = !lay->visible.empty();
   auto visible_of = [&](int32_t r) { return limited ? lay->visible[size_t(r)] : lay->prefix_len[size_t(lay->req_prompt[size_t(r)])]; };
-  std::vector<int32_t> nsplit_prefix(R), nsplit_suffix(R);
+  std::vector<int32_t> nsplit_root(R, 0), nsplit_prefix(R), nsplit_suffix(R);
   std::vector<ps_item> prefix_items, suffix_items;
   const int32_t max_req = std::max(1, 64 / group);
   const int32_t total_prefix_blocks = int32_t(lay->prefix_blk.size());
@@ -106,6 +107,34 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   lay->any_masked = false;
   lay->req_list.assign(lay->group_req.begin(), lay->group_req.end());
   for (int32_t r = 0; r < R; ++r) lay->req_list.push_back(r);
+  lay->req_list.insert(lay->req_list.end(), lay->root_group_req.begin(), lay->root_group_req.end());
+  const bool prefix_mfma = resolve(opt.prefix_variant) == PS_VARIANT_MFMA;
+  // Root segments: read whole by every request below the root (all models of all its prompts), so the sharing group
+  // is large; on the matrix cores a group of more than 64 rows goes out in row-split items like a prefill chunk.
+  const int32_t root_blk0 = int32_t(lay->prefix_blk.size() + lay->suffix_blk.size());   // roots close the block array
+  for (int32_t t = 0; t < lay->num_roots; ++t) {
+    int32_t n = 0;
+    const int64_t size = chunking(lay->root_len[size_t(t)], prefix_chunk, &n);
+    const int32_t g0 = lay->root_group_indptr[size_t(t)], count = lay->root_group_indptr[size_t(t) + 1] - g0;
+    for (int32_t i = 0; i < count; ++i) nsplit_root[size_t(lay->root_group_req[size_t(g0 + i)])] = n;
+    const bool row_split = prefix_mfma && int64_t(count) * group > 64;
+    const int32_t per_item = row_split ? std::max(1, 256 / group) : max_req;
+    for (int32_t c = 0; c < n; ++c)
+      for (int32_t h = 0; h < g.num_kv_heads; ++h)
+        for (int32_t m0 = 0; m0 < count; m0 += per_item) {
+          ps_item it{};
+          it.blk_off = root_blk0 + lay->root_blk_indptr[size_t(t)];
+          it.tok_begin = int32_t(c * size);
+          it.tok_end = int32_t(std::min<int64_t>(lay->root_len[size_t(t)], (c + 1) * size));
+          it.req_off = 2 * R + g0 + m0;
+          it.n_req = std::min(per_item, count - m0);
+          it.kv_head = h;
+          it.split_local = c;
+          it.kind = kPsItemRoot | (row_split ? kPsItemRowSplit : 0);
+          if (!row_split) lay->max_rows_prefix = std::max(lay->max_rows_prefix, it.n_req * group);
+          prefix_items.push_back(it);
+        }
+  }
   std::vector<int32_t> members;
   for (int32_t p = 0; p < P; ++p) {
     int32_t n = 0;
@@ -131,7 +160,7 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
       // Partial prefill on the matrix cores: a sharing group with more rows than one 64-row item holds (the new
       // tokens of a context) goes out in items of up to 256 rows, which the prefill kernel splits over its waves
       // by rows, so that a K/V tile is fetched once per 256 rows instead of once per 64.
-      const bool row_split = limited && resolve(opt.prefix_variant) == PS_VARIANT_MFMA && int64_t(count) * group > 64;
+      const bool row_split = limited && prefix_mfma && int64_t(count) * group > 64;
       const int32_t per_item = row_split ? std::max(1, 256 / group) : max_req;
       for (int32_t h = 0; h < g.num_kv_heads; ++h)
         for (int32_t m0 = 0; m0 < count; m0 += per_item) {
@@ -148,7 +177,7 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
           }
           it.tok_end = int32_t(std::min<int64_t>(std::min<int64_t>(lay->prefix_len[p], (c + 1) * size), v_max));
           it.kv_head = h;
-          it.split_local = c;
+          it.split_local = c;   // the root's splits are added below, once every request's count is known
           it.kind = (v_min < it.tok_end ? kPsItemMasked : 0) | (row_split ? kPsItemRowSplit : 0);
           if (it.kind & kPsItemMasked) lay->any_masked = true;
           if (!row_split) lay->max_rows_prefix = std::max(lay->max_rows_prefix, it.n_req * group);
@@ -169,11 +198,15 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
         it.req_off = R + r;  // identity part of the request list
         it.n_req = 1;
         it.kv_head = h;
-        it.split_local = nsplit_prefix[size_t(r)] + c;
+        it.split_local = nsplit_root[size_t(r)] + nsplit_prefix[size_t(r)] + c;
         it.kind = kPsItemSuffix;
         suffix_items.push_back(it);
       }
   }
+  // a request's partial states: root splits, then prefix splits, then suffix splits (every request of a prefix item
+  // is on the same prompt, hence below the same root)
+  for (ps_item& it : prefix_items)
+    if (!(it.kind & kPsItemRoot)) it.split_local += nsplit_root[size_t(lay->req_list[size_t(it.req_off)])];
   auto by_cost = [](const ps_item& a, const ps_item& b) { return (a.tok_end - a.tok_begin) > (b.tok_end - b.tok_begin); };
   auto rs_first = [&](const ps_item& a, const ps_item& b) {   // row-split items lead, heaviest (tokens x rows) first
     const bool ra = a.kind & kPsItemRowSplit, rb = b.kind & kPsItemRowSplit;
@@ -192,7 +225,7 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   lay->slot_base.assign(R + 1, 0);
   int64_t slots = 0;
   for (int32_t r = 0; r < R; ++r) {
-    slots += nsplit_prefix[r] + nsplit_suffix[r];
+    slots += nsplit_root[r] + nsplit_prefix[r] + nsplit_suffix[r];
     if (slots > INT32_MAX) return PS_ERR_INVALID_ARG;
     lay->slot_base[r + 1] = int32_t(slots);
   }
@@ -236,12 +269,13 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   if (suf_mfma) pk_suffix = pack(lay->num_prefix_items, n_items);
   if (pre_mfma && suf_mfma) pk_all = pack(first_packed, n_items);
 
-  // device blob: [block ids: prefix ++ suffix][request list: group_req ++ identity ++ per-chunk subsets][items]
+  // device blob: [block ids: prefix ++ suffix ++ root][request list: group_req ++ identity ++ root groups ++ per-chunk
+  // subsets][items]
   // [slot_base][visible][schedules]
   // [per-block source offsets and valid counts][destinations of the last append]
   auto pad4 = [](int64_t n) { return (n + 3) / 4 * 4; };
   lay->off_blk = 0;
-  lay->off_req = pad4(lay->off_blk + int64_t(lay->prefix_blk.size() + lay->suffix_blk.size()));
+  lay->off_req = pad4(lay->off_blk + int64_t(lay->prefix_blk.size() + lay->suffix_blk.size() + lay->root_blk.size()));
   lay->off_items = pad4(lay->off_req + int64_t(lay->req_list.size()));
   lay->off_slot = pad4(lay->off_items + 8 * int64_t(lay->items.size()));
   lay->off_visible = pad4(lay->off_slot + R + 1);
@@ -261,7 +295,7 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   place(lay->sched_suffix, pk_suffix);
   place(lay->sched_all, pk_all);
   // per-block directory for the cache-writing kernels
-  const int64_t num_blk_entries = int64_t(lay->prefix_blk.size() + lay->suffix_blk.size());
+  const int64_t num_blk_entries = int64_t(lay->prefix_blk.size() + lay->suffix_blk.size() + lay->root_blk.size());
   lay->off_ent_tok0 = words;
   lay->off_ent_valid = pad4(lay->off_ent_tok0 + num_blk_entries);
   lay->off_dest = pad4(lay->off_ent_valid + num_blk_entries);
@@ -284,7 +318,8 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
       return true;
     };
     if (!fill_entries(lay->prefix_blk_indptr, lay->prefix_len, 0) ||
-        !fill_entries(lay->suffix_blk_indptr, lay->suffix_len, total_prefix_blocks))
+        !fill_entries(lay->suffix_blk_indptr, lay->suffix_len, total_prefix_blocks) ||
+        (lay->num_roots && !fill_entries(lay->root_blk_indptr, lay->root_len, root_blk0)))
       return PS_ERR_INVALID_ARG;
     lay->append_dest.resize(size_t(R), -1);
     std::copy(lay->append_dest.begin(), lay->append_dest.end(), b + lay->off_dest);
@@ -299,6 +334,7 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   fill(lay->sched_all, pk_all);
   std::copy(lay->prefix_blk.begin(), lay->prefix_blk.end(), b + lay->off_blk);
   std::copy(lay->suffix_blk.begin(), lay->suffix_blk.end(), b + lay->off_blk + lay->prefix_blk.size());
+  std::copy(lay->root_blk.begin(), lay->root_blk.end(), b + lay->off_blk + root_blk0);
   std::copy(lay->req_list.begin(), lay->req_list.end(), b + lay->off_req);
   for (int32_t r = 0; r < R; ++r) b[lay->off_visible + r] = visible_of(r);
   if (!lay->items.empty()) std::memcpy(b + lay->off_items, lay->items.data(), lay->items.size() * sizeof(ps_item));
@@ -355,12 +391,14 @@ int32_t ps_pool_refcounts(const ps_pool* pool, const int32_t** refcount) {
   return PS_OK;
 }
 
-int32_t ps_kv_layout(ps_pool* pool, const ps_geometry* geometry, int32_t num_prompts, const int32_t* prefix_len,
-                     int32_t num_requests, const int32_t* req_prompt, const int32_t* req_model,
-                     const int32_t* suffix_len, ps_layout** out) {
-  if (!pool || !geometry || !out || num_prompts < 0 || num_requests < 0) return PS_ERR_INVALID_ARG;
+int32_t ps_kv_layout_tree(ps_pool* pool, const ps_geometry* geometry, int32_t num_roots, const int32_t* root_len,
+                          int32_t num_prompts, const int32_t* prompt_root, const int32_t* prefix_len,
+                          int32_t num_requests, const int32_t* req_prompt, const int32_t* req_model,
+                          const int32_t* suffix_len, ps_layout** out) {
+  if (!pool || !geometry || !out || num_roots < 0 || num_prompts < 0 || num_requests < 0) return PS_ERR_INVALID_ARG;
   if ((num_prompts && !prefix_len) || (num_requests && (!req_prompt || !req_model || !suffix_len)))
     return PS_ERR_INVALID_ARG;
+  if (num_roots && (!root_len || !prompt_root)) return PS_ERR_INVALID_ARG;
   if (int32_t st = check_geometry(*geometry)) return st;
   const int32_t B = geometry->block_size;
 
@@ -372,7 +410,21 @@ int32_t ps_kv_layout(ps_pool* pool, const ps_geometry* geometry, int32_t num_pro
     if (!seen.insert({req_prompt[r], req_model[r]}).second) return PS_ERR_INVALID_ARG;
     ++members_count[size_t(req_prompt[r])];
   }
+  // requests below every root: all requests of the prompts that begin with it
+  std::vector<int32_t> below_count(size_t(num_roots), 0), root_prompts(size_t(num_roots), 0);
+  for (int32_t p = 0; p < num_prompts && num_roots; ++p) {
+    const int32_t t = prompt_root[p];
+    if (t < -1 || t >= num_roots) return PS_ERR_INVALID_ARG;
+    if (t >= 0) {
+      below_count[size_t(t)] += members_count[size_t(p)];
+      ++root_prompts[size_t(t)];
+    }
+  }
   int64_t needed = 0;
+  for (int32_t t = 0; t < num_roots; ++t) {
+    if (root_len[t] < 0 || root_prompts[size_t(t)] == 0) return PS_ERR_INVALID_ARG;
+    needed += ceil_div(root_len[t], B);
+  }
   for (int32_t p = 0; p < num_prompts; ++p) {
     if (prefix_len[p] < 0 || members_count[size_t(p)] == 0) return PS_ERR_INVALID_ARG;
     needed += ceil_div(prefix_len[p], B);
@@ -389,14 +441,30 @@ int32_t ps_kv_layout(ps_pool* pool, const ps_geometry* geometry, int32_t num_pro
   lay->suffix_len.assign(suffix_len, suffix_len + num_requests);
   lay->req_prompt.assign(req_prompt, req_prompt + num_requests);
   lay->req_model.assign(req_model, req_model + num_requests);
+  lay->num_roots = num_roots;
+  if (num_roots) {
+    lay->root_len.assign(root_len, root_len + num_roots);
+    lay->prompt_root.assign(prompt_root, prompt_root + num_prompts);
+  }
 
-  // sharing groups: a prompt's requests in ascending request index
+  // sharing groups: a prompt's requests in ascending request index; a root's likewise
   lay->group_indptr.assign(size_t(num_prompts) + 1, 0);
   for (int32_t p = 0; p < num_prompts; ++p) lay->group_indptr[size_t(p) + 1] = lay->group_indptr[size_t(p)] + members_count[size_t(p)];
   lay->group_req.assign(size_t(num_requests), 0);
   {
     std::vector<int32_t> cursor(lay->group_indptr.begin(), lay->group_indptr.end() - 1);
     for (int32_t r = 0; r < num_requests; ++r) lay->group_req[size_t(cursor[size_t(req_prompt[r])]++)] = r;
+  }
+  lay->root_group_indptr.assign(size_t(num_roots) + 1, 0);
+  for (int32_t t = 0; t < num_roots; ++t)
+    lay->root_group_indptr[size_t(t) + 1] = lay->root_group_indptr[size_t(t)] + below_count[size_t(t)];
+  lay->root_group_req.assign(size_t(lay->root_group_indptr.back()), 0);
+  if (num_roots) {
+    std::vector<int32_t> cursor(lay->root_group_indptr.begin(), lay->root_group_indptr.end() - 1);
+    for (int32_t r = 0; r < num_requests; ++r) {
+      const int32_t t = prompt_root[req_prompt[r]];
+      if (t >= 0) lay->root_group_req[size_t(cursor[size_t(t)]++)] = r;
+    }
   }
 
   auto take = [&](int32_t refs) {
@@ -405,6 +473,12 @@ int32_t ps_kv_layout(ps_pool* pool, const ps_geometry* geometry, int32_t num_pro
     pool->refcount[size_t(blk)] += refs;
     return blk;
   };
+  lay->root_blk_indptr.assign(size_t(num_roots) + 1, 0);
+  for (int32_t t = 0; t < num_roots; ++t) {
+    const int64_t n = ceil_div(root_len[t], B);
+    for (int64_t i = 0; i < n; ++i) lay->root_blk.push_back(take(below_count[size_t(t)]));
+    lay->root_blk_indptr[size_t(t) + 1] = int32_t(lay->root_blk.size());
+  }
   lay->prefix_blk_indptr.assign(size_t(num_prompts) + 1, 0);
   for (int32_t p = 0; p < num_prompts; ++p) {
     const int64_t n = ceil_div(prefix_len[p], B);
@@ -427,9 +501,36 @@ int32_t ps_kv_layout(ps_pool* pool, const ps_geometry* geometry, int32_t num_pro
   return PS_OK;
 }
 
+int32_t ps_kv_layout(ps_pool* pool, const ps_geometry* geometry, int32_t num_prompts, const int32_t* prefix_len,
+                     int32_t num_requests, const int32_t* req_prompt, const int32_t* req_model,
+                     const int32_t* suffix_len, ps_layout** out) {
+  return ps_kv_layout_tree(pool, geometry, 0, nullptr, num_prompts, nullptr, prefix_len, num_requests, req_prompt,
+                           req_model, suffix_len, out);
+}
+
+int32_t ps_layout_root_tables(const ps_layout* lay, int32_t* num_roots, const int32_t** root_blk_indptr,
+                              const int32_t** root_blk, const int32_t** root_group_indptr,
+                              const int32_t** root_group_req) {
+  if (!lay) return PS_ERR_INVALID_ARG;
+  if (num_roots) *num_roots = lay->num_roots;
+  if (root_blk_indptr) *root_blk_indptr = lay->root_blk_indptr.data();
+  if (root_blk) *root_blk = lay->root_blk.data();
+  if (root_group_indptr) *root_group_indptr = lay->root_group_indptr.data();
+  if (root_group_req) *root_group_req = lay->root_group_req.data();
+  return PS_OK;
+}
+
 int32_t ps_layout_release(ps_pool* pool, ps_layout* lay) {
   if (!pool || !lay) return PS_ERR_INVALID_ARG;
   std::vector<int64_t> drop(size_t(pool->num_blocks), 0);
+  for (int32_t t = 0; t < lay->num_roots; ++t) {
+    const int32_t k = lay->root_group_indptr[size_t(t) + 1] - lay->root_group_indptr[size_t(t)];
+    for (int32_t i = lay->root_blk_indptr[size_t(t)]; i < lay->root_blk_indptr[size_t(t) + 1]; ++i) {
+      const int32_t b = lay->root_blk[size_t(i)];
+      if (b < 0 || b >= pool->num_blocks) return PS_ERR_REFCOUNT;
+      drop[size_t(b)] += k;
+    }
+  }
   for (int32_t p = 0; p < lay->num_prompts; ++p) {
     const int32_t k = lay->group_indptr[size_t(p) + 1] - lay->group_indptr[size_t(p)];
     for (int32_t i = lay->prefix_blk_indptr[size_t(p)]; i < lay->prefix_blk_indptr[size_t(p) + 1]; ++i) {

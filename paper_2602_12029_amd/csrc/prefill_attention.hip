@@ -87,6 +87,8 @@ __global__ __launch_bounds__(256, 1) void prefill_attention_kernel(AttnParams p,
   const int n_req = __builtin_amdgcn_readfirstlane(it->n_req);
   const int kv_head = __builtin_amdgcn_readfirstlane(it->kv_head);
   const int split_local = __builtin_amdgcn_readfirstlane(it->split_local);
+  // visible lengths apply to a prompt's own prefix, and only where the plan found a row that sees less
+  const bool limited = (__builtin_amdgcn_readfirstlane(it->kind) & kPsItemMasked) != 0;
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
@@ -112,7 +114,7 @@ __global__ __launch_bounds__(256, 1) void prefill_attention_kernel(AttnParams p,
     if (row < rows) {
       const int req = p.req_list[req_off + row / G];
       req_of[t] = req;
-      lim[t] = min(tok_end, p.visible[req]);
+      lim[t] = limited ? min(tok_end, p.visible[req]) : tok_end;
       const uint16_t* qrow = static_cast<const uint16_t*>(p.q) + (int64_t(req) * p.num_q_heads + kv_head * G + row % G) * kD;
 #pragma unroll
       for (int st = 0; st < 4; ++st) piece[st] = *reinterpret_cast<const u32x4*>(qrow + q_piece<KVT>(st, kg));

@@ -25,7 +25,8 @@ struct ps_item {
   int32_t kind;         // bit 0: 0 prefix, 1 suffix; bit 1: some row of the item sees less than tok_end
 };
 // bit 2: up to 256 rows, split over the four waves of a workgroup by rows instead of by tokens (partial prefill)
-constexpr int32_t kPsItemSuffix = 1, kPsItemMasked = 2, kPsItemRowSplit = 4;
+// bit 3: a root segment (a context several prompts begin with), read by every request below the root
+constexpr int32_t kPsItemSuffix = 1, kPsItemMasked = 2, kPsItemRowSplit = 4, kPsItemRoot = 8;
 static_assert(sizeof(ps_item) == 32, "ps_item is 8 int32");
 
 struct ps_layout {
@@ -33,11 +34,14 @@ struct ps_layout {
   int32_t num_prompts = 0, num_requests = 0;
   std::vector<int32_t> prefix_len, suffix_len, req_prompt, req_model;
   std::vector<int32_t> prefix_blk_indptr, prefix_blk, group_indptr, group_req, suffix_blk_indptr, suffix_blk;
+  // optional third level: roots (contexts several prompts begin with); prompt_root[p] = -1: none
+  int32_t num_roots = 0;
+  std::vector<int32_t> root_len, prompt_root, root_blk_indptr, root_blk, root_group_indptr, root_group_req;
   // per request: how many leading tokens of its prompt's prefix it attends to; empty = all of them
   std::vector<int32_t> visible;
   bool any_masked = false;           // the plan holds an item with kPsItemMasked
-  // request list the items index into: group_req, then the identity list (suffix items), then the subsets of a
-  // sharing group that see into a prefix chunk (only where visible lengths cut a group)
+  // request list the items index into: group_req, then the identity list (suffix items), then root_group_req,
+  // then the subsets of a sharing group that see into a prefix chunk (only where visible lengths cut a group)
   std::vector<int32_t> req_list;
 
   // split plan
@@ -45,9 +49,9 @@ struct ps_layout {
   int32_t prefix_variant = PS_VARIANT_WAVE, suffix_variant = PS_VARIANT_WAVE;
   int32_t prefix_chunk = 0, suffix_chunk = 0;
   int32_t max_rows_prefix = 0;       // largest n_req * G over prefix items
-  std::vector<ps_item> items;        // row-split prefix items, then the other prefix items, then suffix items
+  std::vector<ps_item> items;        // row-split shared items, then the other shared (root, prefix) items, then suffix items
   int32_t num_rowsplit_items = 0;    // launched one workgroup each by the prefill kernel, outside the schedules
-  int32_t num_prefix_items = 0;      // row-split ones included
+  int32_t num_prefix_items = 0;      // all shared items: root and prefix, row-split ones included
   std::vector<int32_t> slot_base;    // [R+1]
   int64_t num_slots = 0;
 

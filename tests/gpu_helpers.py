@@ -51,9 +51,15 @@ class GpuCase:
         g = w.geometry
         self.geo = B.geometry(g.num_q_heads, g.num_kv_heads, g.head_dim, g.block_size, g.q_dtype, g.kv_dtype)
         self.pool = B.ps_pool_create(w.num_blocks, w.free_order)
-        self.layout = B.ps_kv_layout(self.pool, self.geo, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
+        if w.num_roots:
+            self.layout = B.ps_kv_layout_tree(self.pool, self.geo, w.root_len, w.prompt_root, w.prefix_len, w.req_prompt,
+                                              w.req_model, w.suffix_len)
+        else:
+            self.layout = B.ps_kv_layout(self.pool, self.geo, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
         self.opool, self.olay, self.data = oracle_setup(w)
         t = B.ps_layout_tables(self.layout, w.num_prompts, w.num_requests)
+        if w.num_roots:
+            t.update(B.ps_layout_root_tables(self.layout))
         for key in t:                                      # index work is bit-exact, so one pool serves both sides
             assert np.array_equal(t[key], getattr(self.olay, key)), key
         self.q_bits = w.q_bits()

@@ -27,9 +27,14 @@ def _both(w, geo=None):
     g = w.geometry
     geo = geo or B.geometry(g.num_q_heads, g.num_kv_heads, g.head_dim, g.block_size, g.q_dtype, g.kv_dtype)
     pool = B.ps_pool_create(w.num_blocks, w.free_order)
-    lay = B.ps_kv_layout(pool, geo, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
     opool = ol.BlockPool(w.num_blocks, w.free_order)
-    olay = ol.build_layout(opool, g.block_size, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
+    if w.num_roots:
+        lay = B.ps_kv_layout_tree(pool, geo, w.root_len, w.prompt_root, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
+        olay = ol.build_layout_tree(opool, g.block_size, w.root_len, w.prompt_root, w.prefix_len, w.req_prompt,
+                                    w.req_model, w.suffix_len)
+    else:
+        lay = B.ps_kv_layout(pool, geo, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
+        olay = ol.build_layout(opool, g.block_size, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
     return pool, lay, opool, olay
 
 
@@ -98,15 +103,27 @@ def _check_plan(w, lay, plan, visible=None):
     req_list = B.ps_layout_request_list(lay)
     R = w.num_requests
     assert np.array_equal(req_list[:R], t["group_req"]) and np.array_equal(req_list[R:2 * R], np.arange(R))
+    rt = B.ps_layout_root_tables(lay)
+    nsuffix_blk = int(t["suffix_blk_indptr"][-1])
+    assert np.array_equal(req_list[2 * R:2 * R + len(rt["root_group_req"])], rt["root_group_req"])
+    root_of = [int(w.prompt_root[w.req_prompt[r]]) if w.num_roots else -1 for r in range(R)]
     seen = np.asarray(w.prefix_len)[np.asarray(w.req_prompt)] if visible is None else np.asarray(visible)
     cover = {}                                             # (request, kv head) -> list of (kind, begin, end, slot)
     for blk_off, t0, t1, req_off, n_req, head, split, kind in items.tolist():
-        assert t1 > t0 >= 0 and n_req >= 1 and 0 <= head < g.num_kv_heads and 0 <= kind <= 7
+        assert t1 > t0 >= 0 and n_req >= 1 and 0 <= head < g.num_kv_heads and 0 <= kind <= 15
         assert n_req * g.group <= (256 if kind & 4 else 64) or n_req == 1     # rows one item may carry
         assert t0 % g.block_size == 0
         reqs = req_list[req_off:req_off + n_req].tolist()
         assert len(reqs) == n_req
-        if kind & 1:
+        if kind & 8:                                                     # a root segment: everybody below sees all of it
+            assert not kind & 3
+            roots = {root_of[r] for r in reqs}
+            assert len(roots) == 1 and min(roots) >= 0
+            root = roots.pop()
+            assert blk_off == nprefix_blk + nsuffix_blk + rt["root_blk_indptr"][root] and t1 <= w.root_len[root]
+            for r in reqs:
+                cover.setdefault((r, head), []).append((-1, t0, t1, split))
+        elif kind & 1:
             assert n_req == 1 and not kind & 6
             r = reqs[0]
             assert blk_off == nprefix_blk + t["suffix_blk_indptr"][r] and t1 <= w.suffix_len[r]
@@ -125,7 +142,8 @@ def _check_plan(w, lay, plan, visible=None):
         for head in range(g.num_kv_heads):
             chunks = sorted(cover.get((r, head), []), key=lambda c: c[3])
             assert [c[3] for c in chunks] == list(range(nslots))           # every slot written exactly once
-            for kind, length in ((0, int(seen[r])), (1, int(w.suffix_len[r]))):
+            root_len = int(w.root_len[root_of[r]]) if root_of[r] >= 0 else 0
+            for kind, length in ((-1, root_len), (0, int(seen[r])), (1, int(w.suffix_len[r]))):
                 spans = sorted((c[1], c[2]) for c in chunks if c[0] == kind)
                 pos = 0
                 for a, b in spans:
@@ -133,7 +151,7 @@ def _check_plan(w, lay, plan, visible=None):
                     pos = b
                 assert pos == length
             kinds = [c[0] for c in chunks]
-            assert kinds == sorted(kinds)                                   # prefix splits first
+            assert kinds == sorted(kinds)                                   # root splits, prefix splits, suffix splits
 
 
 def test_visible_lengths_plan_invariants_and_errors():
@@ -405,5 +423,89 @@ def test_append_keeps_the_plan_options():
     assert (after[after[:, 7] == 0][:, 2] - after[after[:, 7] == 0][:, 1]).max() == 1024
     assert (after[after[:, 7] == 1][:, 2] - after[after[:, 7] == 1][:, 1]).max() <= 64
     assert len(after) >= len(before)
+    B.ps_layout_release(pool, lay)
+    B.ps_pool_destroy(pool)
+
+
+TREE_KEYS = ("root_blk_indptr", "root_blk", "root_group_indptr", "root_group_req")
+
+
+def test_tree_hand_worked_instance():
+    g = json.load(open(os.path.join(ROOT, "tests", "golden", "layout_tree_small.json")))
+    geo = B.geometry(4, 2, 64, g["block_size"], "f32", "f32")
+    pool = B.ps_pool_create(g["num_blocks"], g["free_order"])
+    lay = B.ps_kv_layout_tree(pool, geo, g["root_len"], g["prompt_root"], g["prefix_len"], g["req_prompt"], g["req_model"],
+                              g["suffix_len"])
+    t = dict(B.ps_layout_tables(lay, 3, 4), **B.ps_layout_root_tables(lay))
+    e = g["expect"]
+    for key in t:
+        assert t[key].tolist() == e[key], key
+    assert B.ps_pool_refcounts(pool, 12).tolist() == e["refcount"]
+    assert B.ps_pool_free_list(pool).tolist() == e["free_after_build"]
+    B.ps_layout_release(pool, lay)
+    assert B.ps_pool_free_list(pool).tolist() == e["free_after_release"]
+    assert not B.ps_pool_refcounts(pool, 12).any()
+    B.ps_pool_destroy(pool)
+
+
+def test_tree_random_batches_against_oracle_policy_and_plan_invariants():
+    rng = np.random.default_rng(33)
+    for trial in range(20):
+        bsz = int(rng.choice([4, 16, 48]))
+        num_t = int(rng.integers(1, 4))
+        num_p = int(rng.integers(num_t, num_t + 4))
+        num_m = int(rng.integers(1, 5))
+        prompt_root = np.concatenate([np.arange(num_t), rng.integers(-1, num_t, num_p - num_t)])   # every root is used
+        rng.shuffle(prompt_root)
+        membership = [sorted(rng.choice(num_m, size=int(rng.integers(1, num_m + 1)), replace=False).tolist())
+                      for _ in range(num_p)]
+        nreq = sum(len(m) for m in membership)
+        geo = wl.Geometry(8, 2, 64, bsz, "f32", "f32")
+        w = wl.make_tree_workload("t", geo, num_m, rng.integers(0, 150, num_t), prompt_root, rng.integers(0, 200, num_p),
+                                  membership, rng.integers(0, 70, nreq), pool_factor=float(rng.uniform(1.0, 2.0)), seed=trial)
+        pool, lay, opool, olay = _both(w)
+        t = dict(B.ps_layout_tables(lay, w.num_prompts, w.num_requests), **B.ps_layout_root_tables(lay))
+        for key in t:
+            assert np.array_equal(t[key], getattr(olay, key)), (trial, key)
+        assert np.array_equal(B.ps_pool_refcounts(pool, w.num_blocks), opool.refcount)
+        for pc, sc in ((0, 0), (32, 16), (64, 4096)):
+            B.ps_layout_replan(lay, B.plan_options(pc, sc))
+            _check_plan(w, lay, B.ps_layout_plan(lay, w.num_requests))
+        if trial % 4 == 0:                                   # visible lengths cut the prompts' own prefixes, never a root
+            visible = rng.integers(0, np.asarray(w.prefix_len)[np.asarray(w.req_prompt)] + 1)
+            B.ps_layout_set_visible(lay, w.num_requests, visible)
+            _check_plan(w, lay, B.ps_layout_plan(lay, w.num_requests), visible)
+        B.ps_layout_release(pool, lay)
+        ol.release_layout(opool, olay)
+        assert np.array_equal(B.ps_pool_free_list(pool), np.array(opool.free, np.int32))
+        B.ps_pool_destroy(pool)
+
+
+def test_tree_errors_leave_the_pool_untouched():
+    geo = B.geometry(4, 2, 64, 4, "f32", "f32")
+    pool = B.ps_pool_create(4, [3, 1, 0, 2])
+    cases = [([9], [0], [4], [0], [0], [1], B.PS_ERR_OOM),               # needs 3 + 1 + 1 blocks
+             ([4], [1], [4], [0], [0], [1], B.PS_ERR_INVALID_ARG),       # unknown root
+             ([4, 4], [0], [4], [0], [0], [1], B.PS_ERR_INVALID_ARG),    # a root no prompt begins with
+             ([-1], [0], [4], [0], [0], [1], B.PS_ERR_INVALID_ARG)]      # negative root length
+    for root_len, prompt_root, prefix, rp, rm, sl, status in cases:
+        with pytest.raises(B.PsError) as e:
+            B.ps_kv_layout_tree(pool, geo, root_len, prompt_root, prefix, rp, rm, sl)
+        assert e.value.status == status
+        assert B.ps_pool_free_list(pool).tolist() == [3, 1, 0, 2] and not B.ps_pool_refcounts(pool, 4).any()
+    B.ps_pool_destroy(pool)
+
+
+def test_root_groups_go_to_row_split_items_on_the_matrix_cores():
+    w = wl.named_tree_workload("tree_b8")
+    pool, lay, _, _ = _both(w)
+    plan = B.ps_layout_plan(lay, w.num_requests)
+    _check_plan(w, lay, plan)
+    items = plan["items"]
+    roots = items[items[:, 7] & 8 != 0]
+    assert len(roots) and (roots[:, 7] == 12).all() and roots[:, 4].max() == 64     # 128 requests x 4 heads: 2 x 256 rows
+    assert (items[:len(roots), 7] & 4).all()                                        # row-split items lead the array
+    sch = B.ps_layout_schedule(lay, 2)
+    assert not (sch["items"][:, 7] & 4).any() and len(sch["items"]) == len(items) - len(roots)
     B.ps_layout_release(pool, lay)
     B.ps_pool_destroy(pool)

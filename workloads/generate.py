@@ -12,7 +12,7 @@ PCG64 streams keyed by (seed, tag, index), so every item can be regenerated on
 its own and in any order.  Draw tags: 1 lengths, 2 membership, 3 free order,
 4 Q, 5 prefix K/V (index = prompt), 6 suffix K/V (index = request), 7 / 8 unquantised
 prefix / suffix K/V as a worker hands them over, 9 the K/V of the token each request
-appends in a decode step (index = step), 10 root K/V (index = root).
+appends in a decode step (index = step), 10 root K/V (index = root), 11 unquantised root K/V.
 
 Storage formats: 'f32' -> float32, 'bf16' -> uint16 bit patterns (fp32 draws
 rounded to nearest-even), 'fp8_e4m3' -> uint8 OCP e4m3fn codes plus one fp32
@@ -181,6 +181,9 @@ class Workload:
 
     def suffix_source(self, request: int):
         return self._source(8, request, int(self.suffix_len[request]))
+
+    def root_source(self, root: int):
+        return self._source(11, root, int(self.root_len[root]))
 
     def step_tokens(self, step: int):
         """K, V [R, Hkv, d] of the one token every request appends in decode step `step`."""
