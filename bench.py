@@ -28,7 +28,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="b8", help="tiny | b8 | long | mixed | fp8_70b")
+    ap.add_argument("--workload", default="b8",
+                    help="tiny | b8 | long | mixed | fp8_70b; tree_tiny | tree_b8 (a context common to all sessions, stored "
+                         "once as a third sharing level)")
     ap.add_argument("--path", default="decode", choices=["decode", "ingest", "prefill"],
                     help="decode: the attention step (the headline metric); ingest: hand-off of the batch's KV into "
                          "the paged pool (ps_kv_ingest over every prefix and suffix), a step = one whole hand-off; "
@@ -81,7 +83,11 @@ def cpu_baseline(w, lay_tables, data, seconds):
     import workloads as wl
     g = w.geometry
     opool = ol.BlockPool(w.num_blocks, w.free_order)
-    olay = ol.build_layout(opool, g.block_size, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
+    if w.num_roots:
+        olay = ol.build_layout_tree(opool, g.block_size, w.root_len, w.prompt_root, w.prefix_len, w.req_prompt,
+                                    w.req_model, w.suffix_len)
+    else:
+        olay = ol.build_layout(opool, g.block_size, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
     q_bits = w.q_bits()
     done_req, done_bytes = 0, 0
     wall0, cpu0 = time.perf_counter(), time.process_time()
@@ -92,6 +98,8 @@ def cpu_baseline(w, lay_tables, data, seconds):
         done_req += len(reqs)
         nblk = -(-int(w.prefix_len[p]) // g.block_size) + sum(-(-int(w.suffix_len[r]) // g.block_size) for r in reqs)
         done_bytes += (int(w.prefix_len[p]) + int(w.suffix_len[reqs].sum())) * g.token_bytes
+        if w.num_roots and w.prompt_root[p] >= 0 and prompts < w.num_prompts:      # a root counts once per pass
+            done_bytes += int(w.root_len[w.prompt_root[p]]) * g.token_bytes // max(1, int((w.prompt_root == w.prompt_root[p]).sum()))
         done_bytes += 2 * len(reqs) * g.num_q_heads * g.head_dim * wl.generate.ELEM_BYTES[g.q_dtype]
         if g.kv_dtype == "fp8_e4m3":
             done_bytes += nblk * g.num_kv_heads * 8
@@ -380,18 +388,24 @@ def main():
         sys.exit("bench.py: no GPU visible")
     dev = "cuda:0"
     variant = {"auto": B.PS_VARIANT_AUTO, "wave": B.PS_VARIANT_WAVE, "mfma": B.PS_VARIANT_MFMA}
-    w = wl.named_workload(args.workload, args.seed, args.models or None)
+    tree = args.workload.startswith("tree")
+    w = wl.named_tree_workload(args.workload, args.seed) if tree else wl.named_workload(args.workload, args.seed, args.models or None)
     g = w.geometry
     geo = B.geometry(g.num_q_heads, g.num_kv_heads, g.head_dim, g.block_size, g.q_dtype, g.kv_dtype)
     pool = B.ps_pool_create(w.num_blocks, w.free_order)
     t_lay0 = time.perf_counter()
-    layout = B.ps_kv_layout(pool, geo, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
+    if tree:
+        layout = B.ps_kv_layout_tree(pool, geo, w.root_len, w.prompt_root, w.prefix_len, w.req_prompt, w.req_model,
+                                     w.suffix_len)
+    else:
+        layout = B.ps_kv_layout(pool, geo, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
     B.ps_layout_replan(layout, B.plan_options(args.prefix_chunk, args.suffix_chunk, variant[args.prefix_variant],
                                               variant[args.suffix_variant]))
     t_layout_ms = (time.perf_counter() - t_lay0) * 1e3
     tables = B.ps_layout_tables(layout, w.num_prompts, w.num_requests)
+    roots = B.ps_layout_root_tables(layout)
     data = wl.fill_pool(w, tables["prefix_blk_indptr"], tables["prefix_blk"], tables["suffix_blk_indptr"],
-                        tables["suffix_blk"])
+                        tables["suffix_blk"], roots["root_blk_indptr"], roots["root_blk"])
     q = to_device(w.q_bits(), g.q_dtype, dev)
     kv0 = to_device(data.kv, g.kv_dtype, dev)
     copies = [kv0] + [kv0.clone() for _ in range(max(0, args.copies - 1))]
@@ -455,7 +469,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if g.kv_dtype == "bf16" else ("fp8_e4m3 KV / bf16 Q" if g.kv_dtype == "fp8_e4m3" else "f32"),
         "data": "synthetic",
-        "config": {"workload": args.workload, "models": w.num_models, "prompts": w.num_prompts,
+        "config": {"workload": args.workload, "roots": w.num_roots, "models": w.num_models, "prompts": w.num_prompts,
                    "requests": w.num_requests, "q_heads": g.num_q_heads, "kv_heads": g.num_kv_heads,
                    "head_dim": g.head_dim, "block_size": g.block_size, "ideal_bytes": ideal,
                    "pool_copies": len(copies), "plan_items": int(plan["items"].shape[0]),

@@ -110,14 +110,17 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   lay->req_list.insert(lay->req_list.end(), lay->root_group_req.begin(), lay->root_group_req.end());
   const bool prefix_mfma = resolve(opt.prefix_variant) == PS_VARIANT_MFMA;
   // Root segments: read whole by every request below the root (all models of all its prompts), so the sharing group
-  // is large; on the matrix cores a group of more than 64 rows goes out in row-split items like a prefill chunk.
+  // is large.  In a decode batch it goes out in ordinary items of at most 64 rows, packed into the one persistent
+  // launch with everything else (the root's K/V is then fetched once per 64 rows, mostly from the last-level cache;
+  // a separate launch for a handful of root items would leave most of the chip idle while it runs).  In a
+  // partial-prefill batch (visible lengths set) large groups go to the prefill kernel, roots included.
   const int32_t root_blk0 = int32_t(lay->prefix_blk.size() + lay->suffix_blk.size());   // roots close the block array
   for (int32_t t = 0; t < lay->num_roots; ++t) {
     int32_t n = 0;
     const int64_t size = chunking(lay->root_len[size_t(t)], prefix_chunk, &n);
     const int32_t g0 = lay->root_group_indptr[size_t(t)], count = lay->root_group_indptr[size_t(t) + 1] - g0;
     for (int32_t i = 0; i < count; ++i) nsplit_root[size_t(lay->root_group_req[size_t(g0 + i)])] = n;
-    const bool row_split = prefix_mfma && int64_t(count) * group > 64;
+    const bool row_split = limited && prefix_mfma && int64_t(count) * group > 64;
     const int32_t per_item = row_split ? std::max(1, 256 / group) : max_req;
     for (int32_t c = 0; c < n; ++c)
       for (int32_t h = 0; h < g.num_kv_heads; ++h)

@@ -496,15 +496,24 @@ def test_tree_errors_leave_the_pool_untouched():
     B.ps_pool_destroy(pool)
 
 
-def test_root_groups_go_to_row_split_items_on_the_matrix_cores():
+def test_root_groups_stay_in_the_persistent_launch_unless_the_batch_is_a_prefill():
     w = wl.named_tree_workload("tree_b8")
     pool, lay, _, _ = _both(w)
     plan = B.ps_layout_plan(lay, w.num_requests)
     _check_plan(w, lay, plan)
     items = plan["items"]
     roots = items[items[:, 7] & 8 != 0]
-    assert len(roots) and (roots[:, 7] == 12).all() and roots[:, 4].max() == 64     # 128 requests x 4 heads: 2 x 256 rows
-    assert (items[:len(roots), 7] & 4).all()                                        # row-split items lead the array
+    assert len(roots) and (roots[:, 7] == 8).all() and roots[:, 4].max() == 16      # 128 requests x 4 heads: 8 x 64 rows
+    sch = B.ps_layout_schedule(lay, 2)
+    assert len(sch["items"]) == len(items)                                          # one launch holds everything
+    # with visible lengths set (a partial-prefill batch) groups of more than 64 rows go to the prefill kernel
+    visible = np.asarray(w.prefix_len)[np.asarray(w.req_prompt)] - 1
+    B.ps_layout_set_visible(lay, w.num_requests, visible)
+    plan = B.ps_layout_plan(lay, w.num_requests)
+    _check_plan(w, lay, plan, visible)
+    items = plan["items"]
+    roots = items[items[:, 7] & 8 != 0]
+    assert (roots[:, 7] == 12).all() and roots[:, 4].max() == 64 and (items[:len(roots), 7] & 4).all()
     sch = B.ps_layout_schedule(lay, 2)
     assert not (sch["items"][:, 7] & 4).any() and len(sch["items"]) == len(items) - len(roots)
     B.ps_layout_release(pool, lay)
