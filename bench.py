@@ -31,11 +31,15 @@ def parse():
     ap.add_argument("--workload", default="b8",
                     help="tiny | b8 | long | mixed | fp8_70b; tree_tiny | tree_b8 (a context common to all sessions, stored "
                          "once as a third sharing level)")
-    ap.add_argument("--path", default="decode", choices=["decode", "ingest", "prefill"],
+    ap.add_argument("--stage-image", default="device", choices=["device", "host"],
+                    help="--path stage: where the staging image lives (device memory: the kernels' own rate; pinned "
+                         "host memory: the rate across PCIe)")
+    ap.add_argument("--path", default="decode", choices=["decode", "ingest", "prefill", "stage"],
                     help="decode: the attention step (the headline metric); ingest: hand-off of the batch's KV into "
                          "the paged pool (ps_kv_ingest over every prefix and suffix), a step = one whole hand-off; "
                          "prefill: attention of newly appended context tokens against the cached context "
-                         "(workloads prefill_b8 | prefill_fp8 | prefill_tiny)")
+                         "(workloads prefill_b8 | prefill_fp8 | prefill_tiny); stage: a step copies every KV block of "
+                         "the batch to a staging image and back (ps_kv_stage_out + ps_kv_stage_in)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--models", type=int, default=0, help="override the number of decode models M (b8, long, fp8_70b)")
     ap.add_argument("--copies", type=int, default=3, help="distinct KV pool copies rotated between steps")
@@ -253,6 +257,95 @@ def main_ingest(args):
 PEAK_MFMA_BF16_TFLOPS = 2500.0
 
 
+def main_stage(args):
+    """--path stage: one step = ps_kv_stage_out of the whole batch followed by ps_kv_stage_in."""
+    import torch
+    import workloads as wl
+    from oracle import layout as ol
+    from oracle import staging as ost
+    from paper_2602_12029_amd import binding as B
+    from paper_2602_12029_amd.runtime import DecodeBatch, to_device
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    dev = "cuda:0"
+    w = wl.named_workload(args.workload, args.seed, args.models or None)
+    g = w.geometry
+    geo = B.geometry(g.num_q_heads, g.num_kv_heads, g.head_dim, g.block_size, g.q_dtype, g.kv_dtype)
+    pool = B.ps_pool_create(w.num_blocks, w.free_order)
+    layout = B.ps_kv_layout(pool, geo, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
+    nelem = w.num_blocks * g.num_kv_heads * 2 * g.block_size * g.head_dim
+    torch_dtype = {"f32": torch.float32, "bf16": torch.bfloat16, "fp8_e4m3": torch.uint8}[g.kv_dtype]
+    kv = torch.zeros(nelem, dtype=torch_dtype, device=dev)
+    scales = torch.ones((w.num_blocks, g.num_kv_heads, 2), dtype=torch.float32, device=dev) if g.kv_dtype == "fp8_e4m3" else None
+    q = to_device(w.q_bits(), g.q_dtype, dev)
+    batch = DecodeBatch(layout, geo, w.num_requests, q, kv, scales)
+    block_bytes, _, total = B.ps_stage_layout(layout)
+    host = args.stage_image == "host"
+    images = [torch.zeros(total, dtype=torch.uint8, pin_memory=True) if host else torch.zeros(total, dtype=torch.uint8, device=dev)
+              for _ in range(2)]
+    stream = int(torch.cuda.current_stream().cuda_stream)
+
+    def step(i, ev=None, slot=0):
+        if ev is not None:
+            ev.record(slot, 0, stream)
+        batch.stage_out(images[i % 2])
+        if ev is not None:
+            ev.record(slot, 1, stream)
+        batch.stage_in(images[(i + 1) % 2])
+
+    if args.calibrate_copy:
+        calibrate_copy(dev)
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev = None if args.no_events else HipEvents(args.steps)
+    every = max(1, args.event_every)
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i, ev if (ev is not None and i % every == 0) else None, i)
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    nblk = w.blocks_needed()
+    image_bytes = nblk * block_bytes + (nblk * g.num_kv_heads * 8 if g.kv_dtype == "fp8_e4m3" else 0)
+    moved = 4 * image_bytes                                     # out: read + write, in: read + write
+    roofline = {"bound": "hbm", "kernel": "stage_out (pool -> image)", "achieved": None, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": None, "traffic": None}
+    if ev is not None:
+        k_ms = float(np.mean([ev.elapsed_ms(i) for i in range(0, args.steps, every)]))
+        roofline.update(achieved=2 * image_bytes / (k_ms * 1e-3) / 1e9, kernel_ms=k_ms, algorithmic_bytes=2 * image_bytes)
+        roofline["frac"] = roofline["achieved"] / PEAK_HBM_GBS
+    value = moved / (ms_per_step * 1e-3) / 1e9
+    line = {
+        "metric": "staging of a batch's KV blocks to an image and back: bytes read + written, GB/s",
+        "value": value, "unit": "GB/s", "pct_of_peak_hbm": 100.0 * value / PEAK_HBM_GBS,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"bf16": "bf16", "fp8_e4m3": "u8", "f32": "f32"}[g.kv_dtype], "data": "synthetic",
+        "config": {"workload": args.workload, "path": "stage", "image": args.stage_image, "blocks": nblk,
+                   "image_bytes": image_bytes, "moved_bytes": moved,
+                   "note": "pinned host image: both copies cross PCIe, the HBM roofline does not apply" if host else
+                           "device image: an HBM-to-HBM copy each way"},
+        "roofline": roofline,
+    }
+    if args.cpu_seconds > 0:                                    # the oracle's stage_out + stage_in, cycled
+        opool = ol.BlockPool(w.num_blocks, w.free_order)
+        olay = ol.build_layout(opool, g.block_size, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
+        shape = (w.num_blocks, g.num_kv_heads, 2, g.block_size, g.head_dim)
+        okv = np.zeros(shape, wl.generate.STORAGE[g.kv_dtype])
+        osc = np.ones((w.num_blocks, g.num_kv_heads, 2), np.float32) if g.kv_dtype == "fp8_e4m3" else None
+        wall0, cpu0, reps = time.perf_counter(), time.process_time(), 0
+        while time.perf_counter() - wall0 < args.cpu_seconds:
+            img, img_sc = ost.stage_out(okv, osc, olay)
+            ost.stage_in(okv, osc, olay, img, img_sc)
+            reps += 1
+        wall = time.perf_counter() - wall0
+        line["cpu_baseline"] = {"value": reps * moved / wall / 1e9, "unit": "GB/s",
+                                "cores": max(1, int(round((time.process_time() - cpu0) / wall))), "kind": "oracle",
+                                "sample": f"numpy oracle, {reps} round trips of the whole batch, {wall:.1f} s wall"}
+    print(json.dumps(line))
+
+
 def cpu_prefill_baseline(w, visible, data, seconds):
     """Time the oracle on query rows of the chunk workload, one by one, until about `seconds` have passed."""
     from oracle import attention as oa
@@ -379,6 +472,8 @@ def main():
         return main_ingest(args)
     if args.path == "prefill":
         return main_prefill(args)
+    if args.path == "stage":
+        return main_stage(args)
     import torch
     import workloads as wl
     from paper_2602_12029_amd import binding as B

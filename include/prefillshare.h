@@ -253,6 +253,42 @@ int32_t ps_kv_ingest(const ps_layout* layout, const void* dev_tables, int32_t wh
                      const void* src_v, int64_t src_stride_tok, int64_t src_stride_head, void* kv_pool,
                      float* kv_scales, void* stream);
 
+/* ---- staging of cold KV and admission (Appendix B.2, "KV transfer and staging at high concurrency") -------------
+ * When the resident KV of the decode side exceeds the GPU's capacity, the caches of sessions that are not scheduled
+ * are staged in CPU memory and reloaded when their sessions run again; admission control and reservation of KV blocks
+ * are the alternatives the paper names.  The unit here is a batch layout: it is *parked* (its blocks copied to a
+ * staging image, its references dropped, the blocks back in the pool) and later *resumed* (blocks taken again by the
+ * ordinary policy -- in general other physical blocks -- and the image copied back).
+ *
+ * ps_blocks_needed (host): blocks a batch would take, sum over roots, prompts and requests of ceil(len / block_size)
+ * (Eq. 9); a batch can be admitted if this does not exceed ps_pool_num_free.  root_len may be NULL with num_roots = 0.
+ * ps_layout_state (host): the blocks this layout takes (the same count from its current lengths) and whether it is
+ * parked.
+ * ps_stage_layout (host): the staging image of this layout: its blocks in table order (prefix blocks, suffix
+ * blocks, root blocks: the order of the concatenated block array), each block whole and dense,
+ * [kv_head][K|V][slot][head_dim] in the pool's element type (*block_bytes each); e4m3 pools append the blocks'
+ * scales [block][kv_head][K|V] float32 at *scales_offset_bytes; *total_bytes is the size to allocate.
+ * ps_kv_stage_out / ps_kv_stage_in (device, asynchronous on `stream`): copy the layout's blocks to / from `image`
+ * (16-byte aligned; device memory, or pinned host memory that the device can address -- then the copy crosses PCIe
+ * inside the kernel).  dev_tables must be a current upload.  Bits are copied, nothing is converted.
+ * ps_layout_park (host): drops the layout's references as ps_layout_release does (blocks that reach zero join the
+ * free-list tail in ascending id) but keeps the layout; call it after ps_kv_stage_out has completed.  Every device
+ * call and ps_layout_append on a parked layout return PS_ERR_INVALID_ARG; ps_layout_release still works.
+ * ps_layout_resume (host): takes blocks again (roots, prompts, requests, from the head of the free list as it is
+ * now) and re-derives the plan with the options last used; upload the tables again, then ps_kv_stage_in.
+ * PS_ERR_OOM: the batch does not fit; pool and layout unchanged, still parked. */
+int32_t ps_blocks_needed(int32_t block_size, int32_t num_roots, const int32_t* root_len, int32_t num_prompts,
+                         const int32_t* prefix_len, int32_t num_requests, const int32_t* suffix_len, int64_t* out);
+int32_t ps_layout_state(const ps_layout* layout, int64_t* num_blocks, int32_t* parked);
+int32_t ps_stage_layout(const ps_layout* layout, int64_t* block_bytes, int64_t* scales_offset_bytes,
+                        int64_t* total_bytes);
+int32_t ps_kv_stage_out(const ps_layout* layout, const void* dev_tables, const void* kv_pool, const float* kv_scales,
+                        void* image, void* stream);
+int32_t ps_kv_stage_in(const ps_layout* layout, const void* dev_tables, const void* image, void* kv_pool,
+                       float* kv_scales, void* stream);
+int32_t ps_layout_park(ps_pool* pool, ps_layout* layout);
+int32_t ps_layout_resume(ps_pool* pool, ps_layout* layout);
+
 const char* ps_strerror(int32_t status);
 int32_t ps_last_hip_error(void);
 

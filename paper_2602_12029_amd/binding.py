@@ -26,6 +26,8 @@ EXPORTS = [
     "ps_prefix_attention", "ps_suffix_attention", "ps_prefix_suffix_attention", "ps_merge_states", "ps_decode_attention",
     "ps_layout_lengths", "ps_layout_append", "ps_kv_append", "ps_kv_ingest",
     "ps_layout_set_visible", "ps_layout_request_list", "ps_kv_layout_tree", "ps_layout_root_tables",
+    "ps_blocks_needed", "ps_layout_state", "ps_stage_layout", "ps_kv_stage_out", "ps_kv_stage_in", "ps_layout_park",
+    "ps_layout_resume",
     "ps_strerror", "ps_last_hip_error",
 ]
 
@@ -320,6 +322,49 @@ def ps_kv_ingest(layout, dev_tables, which: int, src_k, src_v, src_stride_tok: i
                  kv_scales, stream=0):
     _check(_lib().ps_kv_ingest(layout, _p(dev_tables), C.c_int32(which), _p(src_k), _p(src_v), C.c_int64(src_stride_tok),
                                C.c_int64(src_stride_head), _p(kv_pool), _p(kv_scales), _p(stream)), "ps_kv_ingest")
+
+
+# ---- staging of cold KV and admission ----------------------------------------------------------------
+def ps_blocks_needed(block_size: int, prefix_len, suffix_len, root_len=()) -> int:
+    rl, rlp = _i32(root_len)
+    pl, plp = _i32(prefix_len)
+    sl, slp = _i32(suffix_len)
+    out = C.c_int64()
+    _check(_lib().ps_blocks_needed(C.c_int32(block_size), C.c_int32(rl.size), rlp, C.c_int32(pl.size), plp,
+                                   C.c_int32(sl.size), slp, C.byref(out)), "ps_blocks_needed")
+    return out.value
+
+
+def ps_layout_state(layout):
+    """(blocks the layout takes, parked?)"""
+    n, parked = C.c_int64(), C.c_int32()
+    _check(_lib().ps_layout_state(layout, C.byref(n), C.byref(parked)), "ps_layout_state")
+    return n.value, bool(parked.value)
+
+
+def ps_stage_layout(layout):
+    """(bytes per block, offset of the e4m3 scales, total bytes) of the layout's staging image."""
+    bb, so, tot = C.c_int64(), C.c_int64(), C.c_int64()
+    _check(_lib().ps_stage_layout(layout, C.byref(bb), C.byref(so), C.byref(tot)), "ps_stage_layout")
+    return bb.value, so.value, tot.value
+
+
+def ps_kv_stage_out(layout, dev_tables, kv_pool, kv_scales, image, stream=0):
+    _check(_lib().ps_kv_stage_out(layout, _p(dev_tables), _p(kv_pool), _p(kv_scales), _p(image), _p(stream)),
+           "ps_kv_stage_out")
+
+
+def ps_kv_stage_in(layout, dev_tables, image, kv_pool, kv_scales, stream=0):
+    _check(_lib().ps_kv_stage_in(layout, _p(dev_tables), _p(image), _p(kv_pool), _p(kv_scales), _p(stream)),
+           "ps_kv_stage_in")
+
+
+def ps_layout_park(pool, layout):
+    _check(_lib().ps_layout_park(pool, layout), "ps_layout_park")
+
+
+def ps_layout_resume(pool, layout):
+    _check(_lib().ps_layout_resume(pool, layout), "ps_layout_resume")
 
 
 def ps_strerror(status: int) -> str:

@@ -75,7 +75,7 @@ int32_t launch_set(const ps_layout* lay, const psdev::AttnParams& p, const void*
 
 int32_t check_pass_args(const ps_layout* lay, const void* dev_tables, const void* q, const void* kv,
                         const float* scales, const void* workspace) {
-  if (!lay || !dev_tables || !workspace) return PS_ERR_INVALID_ARG;
+  if (!lay || !dev_tables || !workspace || lay->parked) return PS_ERR_INVALID_ARG;
   if (!lay->items.empty() && (!q || !kv)) return PS_ERR_INVALID_ARG;
   if (lay->geo.kv_dtype == PS_FP8_E4M3 && !scales && !lay->items.empty()) return PS_ERR_INVALID_ARG;
   return PS_OK;
@@ -131,7 +131,7 @@ int32_t ps_prefix_suffix_attention(const ps_layout* lay, const void* dev_tables,
 
 int32_t ps_kv_ingest(const ps_layout* lay, const void* dev_tables, int32_t which, const void* src_k, const void* src_v,
                      int64_t src_stride_tok, int64_t src_stride_head, void* kv_pool, float* kv_scales, void* stream) {
-  if (!lay || !dev_tables || which < 0 || which > 2) return PS_ERR_INVALID_ARG;
+  if (!lay || !dev_tables || which < 0 || which > 2 || lay->parked) return PS_ERR_INVALID_ARG;
   const ps_geometry& g = lay->geo;
   const size_t entries = which == 0 ? lay->prefix_blk.size() : (which == 1 ? lay->suffix_blk.size() : lay->root_blk.size());
   if (entries == 0) return PS_OK;
@@ -148,13 +148,41 @@ int32_t ps_kv_ingest(const ps_layout* lay, const void* dev_tables, int32_t which
 
 int32_t ps_kv_append(const ps_layout* lay, const void* dev_tables, const void* new_k, const void* new_v, void* kv_pool,
                      float* kv_scales, void* stream) {
-  if (!lay || !dev_tables) return PS_ERR_INVALID_ARG;
+  if (!lay || !dev_tables || lay->parked) return PS_ERR_INVALID_ARG;
   if (lay->num_requests == 0) return PS_OK;
   if (!new_k || !new_v || !kv_pool || (lay->geo.kv_dtype == PS_FP8_E4M3 && !kv_scales)) return PS_ERR_INVALID_ARG;
   if (int32_t rc = psdev::launch_kv_append(lay, dev_tables, new_k, new_v, kv_pool, kv_scales,
                                            static_cast<hipStream_t>(stream)))
     return rc;
   return check_hip(hipGetLastError());
+}
+
+namespace {
+
+int32_t stage(const ps_layout* lay, const void* dev_tables, bool to_image, void* kv_pool, float* kv_scales, void* image,
+              void* stream) {
+  if (!lay || !dev_tables || lay->parked) return PS_ERR_INVALID_ARG;
+  int64_t scales_off = 0, total = 0;
+  ps_stage_layout(lay, nullptr, &scales_off, &total);
+  if (lay->prefix_blk.empty() && lay->suffix_blk.empty() && lay->root_blk.empty()) return PS_OK;
+  if (!kv_pool || !image || (lay->geo.kv_dtype == PS_FP8_E4M3 && !kv_scales)) return PS_ERR_INVALID_ARG;
+  if (reinterpret_cast<uintptr_t>(image) % 16) return PS_ERR_SHAPE;
+  if (int32_t rc = psdev::launch_kv_stage(lay, dev_tables, to_image, kv_pool, kv_scales, image, scales_off,
+                                          static_cast<hipStream_t>(stream)))
+    return rc;
+  return check_hip(hipGetLastError());
+}
+
+}  // namespace
+
+int32_t ps_kv_stage_out(const ps_layout* lay, const void* dev_tables, const void* kv_pool, const float* kv_scales,
+                        void* image, void* stream) {
+  return stage(lay, dev_tables, true, const_cast<void*>(kv_pool), const_cast<float*>(kv_scales), image, stream);
+}
+
+int32_t ps_kv_stage_in(const ps_layout* lay, const void* dev_tables, const void* image, void* kv_pool, float* kv_scales,
+                       void* stream) {
+  return stage(lay, dev_tables, false, kv_pool, kv_scales, const_cast<void*>(image), stream);
 }
 
 int32_t ps_decode_attention(const ps_layout* lay, const void* dev_tables, const void* q, const void* kv_pool,

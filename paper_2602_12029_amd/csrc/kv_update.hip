@@ -220,6 +220,56 @@ __global__ __launch_bounds__(256) void append_e4m3_kernel(KvWriteParams p, const
   for (int c = lane; c < p.head_dim; c += 64) dst[c] = uint8_t(f32x2_to_e4m3(bf16_bits_to_f32(src[c]) / scale, 0.f) & 0xffu);
 }
 
+// ---- staging of whole blocks (cold KV parked in host memory and reloaded, Appendix B.2) -------------------
+// One wavefront per (entry, KV head, K|V) tile of B x d elements; the image is dense, [entry][head][K|V][slot][d]
+// in table order, followed by the e4m3 scales [entry][head][K|V].  TO_IMAGE: pool -> image, else image -> pool.
+// Bits are copied, 16 bytes per lane and step, four loads in flight before the first store.
+template <bool TO_IMAGE>
+__global__ __launch_bounds__(256) void stage_copy_kernel(KvWriteParams p, uint8_t* __restrict__ image,
+                                                         float* __restrict__ image_scales, int num_entries,
+                                                         int elem_bytes) {
+  const int lane = threadIdx.x & 63;
+  const int64_t tile = int64_t(blockIdx.x) * 4 + (threadIdx.x >> 6);   // (entry, head, which)
+  if (tile >= int64_t(num_entries) * p.num_kv_heads * 2) return;
+  const int which = int(tile & 1);
+  const int h = int((tile >> 1) % p.num_kv_heads);
+  const int e = int((tile >> 1) / p.num_kv_heads);
+  const int id = p.blk[e];
+  const int row_bytes = p.head_dim * elem_bytes;
+  const int row_chunks = row_bytes >> 4;
+  const int chunks = p.block_size * row_chunks;
+  uint8_t* pool_tile = static_cast<uint8_t*>(p.kv) +
+                       (int64_t(id) * p.s_block + int64_t(h) * p.s_head + int64_t(which) * p.s_kv) * elem_bytes;
+  uint8_t* image_tile = image + tile * int64_t(p.block_size) * row_bytes;
+  const int64_t tok_bytes = p.s_tok * elem_bytes;
+  for (int c0 = 0; c0 < chunks; c0 += 256) {
+    uint4 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int c = c0 + 64 * u + lane;
+      if (c < chunks) {
+        const int slot = c / row_chunks, col = c % row_chunks;
+        const uint8_t* src = TO_IMAGE ? pool_tile + slot * tok_bytes + 16 * col : image_tile + 16 * int64_t(c);
+        v[u] = *reinterpret_cast<const uint4*>(src);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int c = c0 + 64 * u + lane;
+      if (c < chunks) {
+        const int slot = c / row_chunks, col = c % row_chunks;
+        uint8_t* dst = TO_IMAGE ? image_tile + 16 * int64_t(c) : pool_tile + slot * tok_bytes + 16 * col;
+        *reinterpret_cast<uint4*>(dst) = v[u];
+      }
+    }
+  }
+  if (image_scales && lane == 0) {
+    float* pool_scale = p.scales + (int64_t(id) * p.num_kv_heads + h) * 2 + which;
+    if (TO_IMAGE) image_scales[tile] = *pool_scale;
+    else *pool_scale = image_scales[tile];
+  }
+}
+
 KvWriteParams make_write_params(const ps_layout* lay, const void* dev_tables, void* kv, float* scales) {
   const int32_t* t = static_cast<const int32_t*>(dev_tables);
   const ps_geometry& g = lay->geo;
@@ -304,6 +354,26 @@ int32_t launch_kv_append(const ps_layout* lay, const void* dev_tables, const voi
   else
     hipLaunchKernelGGL(append_e4m3_kernel, grid, block, 0, st, p, static_cast<const uint16_t*>(new_k),
                        static_cast<const uint16_t*>(new_v), lay->num_requests);
+  return PS_OK;
+}
+
+int32_t launch_kv_stage(const ps_layout* lay, const void* dev_tables, bool to_image, void* kv, float* scales,
+                        void* image, int64_t scales_offset_bytes, hipStream_t st) {
+  const ps_geometry& g = lay->geo;
+  const int64_t entries = int64_t(lay->prefix_blk.size() + lay->suffix_blk.size() + lay->root_blk.size());
+  if (entries == 0) return PS_OK;
+  const int esz = g.kv_dtype == PS_F32 ? 4 : (g.kv_dtype == PS_BF16 ? 2 : 1);
+  if ((g.head_dim * esz) % 16) return PS_ERR_UNSUPPORTED;
+  const int64_t tiles = entries * g.num_kv_heads * 2;
+  if (tiles > INT32_MAX) return PS_ERR_INVALID_ARG;
+  const dim3 grid{unsigned((tiles + 3) / 4)}, block{256};
+  const KvWriteParams p = make_write_params(lay, dev_tables, kv, scales);
+  uint8_t* img = static_cast<uint8_t*>(image);
+  float* img_scales = g.kv_dtype == PS_FP8_E4M3 ? reinterpret_cast<float*>(img + scales_offset_bytes) : nullptr;
+  if (to_image)
+    hipLaunchKernelGGL(stage_copy_kernel<true>, grid, block, 0, st, p, img, img_scales, int(entries), esz);
+  else
+    hipLaunchKernelGGL(stage_copy_kernel<false>, grid, block, 0, st, p, img, img_scales, int(entries), esz);
   return PS_OK;
 }
 

@@ -21,6 +21,10 @@ int32_t launch_kv_ingest(const ps_layout* lay, const void* dev_tables, int which
                          int64_t src_s_tok, int64_t src_s_head, void* kv, float* scales, hipStream_t st);
 int32_t launch_kv_append(const ps_layout* lay, const void* dev_tables, const void* new_k, const void* new_v, void* kv,
                          float* scales, hipStream_t st);
+// Whole blocks of a layout, in table order, to (to_image) or from a dense staging image; e4m3 scales follow the
+// blocks at scales_offset_bytes.
+int32_t launch_kv_stage(const ps_layout* lay, const void* dev_tables, bool to_image, void* kv, float* scales,
+                        void* image, int64_t scales_offset_bytes, hipStream_t st);
 int32_t launch_merge(const int32_t* slot_base, const float* ws_o, const float* ws_lse, void* out, float* out_lse,
                      int num_requests, const ps_geometry& g, hipStream_t st);
 

@@ -345,6 +345,88 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   return PS_OK;
 }
 
+namespace {
+
+// Drops every reference the layout holds; blocks that reach zero join the free-list tail in ascending id.
+// PS_ERR_REFCOUNT leaves the pool unchanged.
+int32_t drop_references(ps_pool* pool, const ps_layout* lay) {
+  std::vector<int64_t> drop(size_t(pool->num_blocks), 0);
+  for (int32_t t = 0; t < lay->num_roots; ++t) {
+    const int32_t k = lay->root_group_indptr[size_t(t) + 1] - lay->root_group_indptr[size_t(t)];
+    for (int32_t i = lay->root_blk_indptr[size_t(t)]; i < lay->root_blk_indptr[size_t(t) + 1]; ++i) {
+      const int32_t b = lay->root_blk[size_t(i)];
+      if (b < 0 || b >= pool->num_blocks) return PS_ERR_REFCOUNT;
+      drop[size_t(b)] += k;
+    }
+  }
+  for (int32_t p = 0; p < lay->num_prompts; ++p) {
+    const int32_t k = lay->group_indptr[size_t(p) + 1] - lay->group_indptr[size_t(p)];
+    for (int32_t i = lay->prefix_blk_indptr[size_t(p)]; i < lay->prefix_blk_indptr[size_t(p) + 1]; ++i) {
+      const int32_t b = lay->prefix_blk[size_t(i)];
+      if (b < 0 || b >= pool->num_blocks) return PS_ERR_REFCOUNT;
+      drop[size_t(b)] += k;
+    }
+  }
+  for (int32_t b : lay->suffix_blk) {
+    if (b < 0 || b >= pool->num_blocks) return PS_ERR_REFCOUNT;
+    drop[size_t(b)] += 1;
+  }
+  for (int32_t b = 0; b < pool->num_blocks; ++b)
+    if (pool->refcount[size_t(b)] < drop[size_t(b)]) return PS_ERR_REFCOUNT;
+  for (int32_t b = 0; b < pool->num_blocks; ++b) {
+    if (!drop[size_t(b)]) continue;
+    pool->refcount[size_t(b)] -= int32_t(drop[size_t(b)]);
+    if (pool->refcount[size_t(b)] == 0) pool->free_list.push_back(b);
+  }
+  return PS_OK;
+}
+
+// Takes the blocks of every segment by the canonical policy (roots, prompts, requests; head of the free list).  The
+// caller has checked that the free list is long enough.
+void take_blocks(ps_pool* pool, ps_layout* lay) {
+  const int32_t B = lay->geo.block_size;
+  auto take = [&](int32_t refs) {
+    const int32_t blk = pool->free_list.front();
+    pool->free_list.pop_front();
+    pool->refcount[size_t(blk)] += refs;
+    return blk;
+  };
+  lay->root_blk.clear();
+  lay->prefix_blk.clear();
+  lay->suffix_blk.clear();
+  lay->root_blk_indptr.assign(size_t(lay->num_roots) + 1, 0);
+  for (int32_t t = 0; t < lay->num_roots; ++t) {
+    const int32_t k = lay->root_group_indptr[size_t(t) + 1] - lay->root_group_indptr[size_t(t)];
+    const int64_t n = ceil_div(lay->root_len[size_t(t)], B);
+    for (int64_t i = 0; i < n; ++i) lay->root_blk.push_back(take(k));
+    lay->root_blk_indptr[size_t(t) + 1] = int32_t(lay->root_blk.size());
+  }
+  lay->prefix_blk_indptr.assign(size_t(lay->num_prompts) + 1, 0);
+  for (int32_t p = 0; p < lay->num_prompts; ++p) {
+    const int32_t k = lay->group_indptr[size_t(p) + 1] - lay->group_indptr[size_t(p)];
+    const int64_t n = ceil_div(lay->prefix_len[size_t(p)], B);
+    for (int64_t i = 0; i < n; ++i) lay->prefix_blk.push_back(take(k));
+    lay->prefix_blk_indptr[size_t(p) + 1] = int32_t(lay->prefix_blk.size());
+  }
+  lay->suffix_blk_indptr.assign(size_t(lay->num_requests) + 1, 0);
+  for (int32_t r = 0; r < lay->num_requests; ++r) {
+    const int64_t n = ceil_div(lay->suffix_len[size_t(r)], B);
+    for (int64_t i = 0; i < n; ++i) lay->suffix_blk.push_back(take(1));
+    lay->suffix_blk_indptr[size_t(r) + 1] = int32_t(lay->suffix_blk.size());
+  }
+}
+
+int64_t blocks_of(const ps_layout* lay) {
+  const int32_t B = lay->geo.block_size;
+  int64_t n = 0;
+  for (int32_t l : lay->root_len) n += ceil_div(l, B);
+  for (int32_t l : lay->prefix_len) n += ceil_div(l, B);
+  for (int32_t l : lay->suffix_len) n += ceil_div(l, B);
+  return n;
+}
+
+}  // namespace
+
 // ---------------------------------------------------------------------------------------------------
 extern "C" {
 
@@ -470,30 +552,7 @@ int32_t ps_kv_layout_tree(ps_pool* pool, const ps_geometry* geometry, int32_t nu
     }
   }
 
-  auto take = [&](int32_t refs) {
-    const int32_t blk = pool->free_list.front();
-    pool->free_list.pop_front();
-    pool->refcount[size_t(blk)] += refs;
-    return blk;
-  };
-  lay->root_blk_indptr.assign(size_t(num_roots) + 1, 0);
-  for (int32_t t = 0; t < num_roots; ++t) {
-    const int64_t n = ceil_div(root_len[t], B);
-    for (int64_t i = 0; i < n; ++i) lay->root_blk.push_back(take(below_count[size_t(t)]));
-    lay->root_blk_indptr[size_t(t) + 1] = int32_t(lay->root_blk.size());
-  }
-  lay->prefix_blk_indptr.assign(size_t(num_prompts) + 1, 0);
-  for (int32_t p = 0; p < num_prompts; ++p) {
-    const int64_t n = ceil_div(prefix_len[p], B);
-    for (int64_t i = 0; i < n; ++i) lay->prefix_blk.push_back(take(members_count[size_t(p)]));
-    lay->prefix_blk_indptr[size_t(p) + 1] = int32_t(lay->prefix_blk.size());
-  }
-  lay->suffix_blk_indptr.assign(size_t(num_requests) + 1, 0);
-  for (int32_t r = 0; r < num_requests; ++r) {
-    const int64_t n = ceil_div(suffix_len[r], B);
-    for (int64_t i = 0; i < n; ++i) lay->suffix_blk.push_back(take(1));
-    lay->suffix_blk_indptr[size_t(r) + 1] = int32_t(lay->suffix_blk.size());
-  }
+  take_blocks(pool, lay);
 
   if (int32_t st = ps_plan_build(lay, nullptr)) {
     // cannot fail with default options, but never leave references behind
@@ -525,35 +584,65 @@ int32_t ps_layout_root_tables(const ps_layout* lay, int32_t* num_roots, const in
 
 int32_t ps_layout_release(ps_pool* pool, ps_layout* lay) {
   if (!pool || !lay) return PS_ERR_INVALID_ARG;
-  std::vector<int64_t> drop(size_t(pool->num_blocks), 0);
-  for (int32_t t = 0; t < lay->num_roots; ++t) {
-    const int32_t k = lay->root_group_indptr[size_t(t) + 1] - lay->root_group_indptr[size_t(t)];
-    for (int32_t i = lay->root_blk_indptr[size_t(t)]; i < lay->root_blk_indptr[size_t(t) + 1]; ++i) {
-      const int32_t b = lay->root_blk[size_t(i)];
-      if (b < 0 || b >= pool->num_blocks) return PS_ERR_REFCOUNT;
-      drop[size_t(b)] += k;
-    }
-  }
-  for (int32_t p = 0; p < lay->num_prompts; ++p) {
-    const int32_t k = lay->group_indptr[size_t(p) + 1] - lay->group_indptr[size_t(p)];
-    for (int32_t i = lay->prefix_blk_indptr[size_t(p)]; i < lay->prefix_blk_indptr[size_t(p) + 1]; ++i) {
-      const int32_t b = lay->prefix_blk[size_t(i)];
-      if (b < 0 || b >= pool->num_blocks) return PS_ERR_REFCOUNT;
-      drop[size_t(b)] += k;
-    }
-  }
-  for (int32_t b : lay->suffix_blk) {
-    if (b < 0 || b >= pool->num_blocks) return PS_ERR_REFCOUNT;
-    drop[size_t(b)] += 1;
-  }
-  for (int32_t b = 0; b < pool->num_blocks; ++b)
-    if (pool->refcount[size_t(b)] < drop[size_t(b)]) return PS_ERR_REFCOUNT;
-  for (int32_t b = 0; b < pool->num_blocks; ++b) {
-    if (!drop[size_t(b)]) continue;
-    pool->refcount[size_t(b)] -= int32_t(drop[size_t(b)]);
-    if (pool->refcount[size_t(b)] == 0) pool->free_list.push_back(b);
-  }
+  if (!lay->parked)
+    if (int32_t st = drop_references(pool, lay)) return st;
   delete lay;
+  return PS_OK;
+}
+
+int32_t ps_blocks_needed(int32_t block_size, int32_t num_roots, const int32_t* root_len, int32_t num_prompts,
+                         const int32_t* prefix_len, int32_t num_requests, const int32_t* suffix_len, int64_t* out) {
+  if (!out || block_size <= 0 || num_roots < 0 || num_prompts < 0 || num_requests < 0) return PS_ERR_INVALID_ARG;
+  if ((num_roots && !root_len) || (num_prompts && !prefix_len) || (num_requests && !suffix_len)) return PS_ERR_INVALID_ARG;
+  int64_t n = 0;
+  auto add = [&](const int32_t* len, int32_t count) {
+    for (int32_t i = 0; i < count; ++i) {
+      if (len[i] < 0) return false;
+      n += ceil_div(len[i], block_size);
+    }
+    return true;
+  };
+  if (!add(root_len, num_roots) || !add(prefix_len, num_prompts) || !add(suffix_len, num_requests)) return PS_ERR_INVALID_ARG;
+  *out = n;
+  return PS_OK;
+}
+
+int32_t ps_layout_park(ps_pool* pool, ps_layout* lay) {
+  if (!pool || !lay || lay->parked) return PS_ERR_INVALID_ARG;
+  if (int32_t st = drop_references(pool, lay)) return st;
+  lay->parked = true;
+  std::fill(lay->root_blk.begin(), lay->root_blk.end(), -1);
+  std::fill(lay->prefix_blk.begin(), lay->prefix_blk.end(), -1);
+  std::fill(lay->suffix_blk.begin(), lay->suffix_blk.end(), -1);
+  std::fill(lay->append_dest.begin(), lay->append_dest.end(), -1);
+  return PS_OK;
+}
+
+int32_t ps_layout_resume(ps_pool* pool, ps_layout* lay) {
+  if (!pool || !lay || !lay->parked) return PS_ERR_INVALID_ARG;
+  if (blocks_of(lay) > int64_t(pool->free_list.size())) return PS_ERR_OOM;
+  take_blocks(pool, lay);
+  lay->parked = false;
+  return ps_plan_build(lay, &lay->opt);   // options that were accepted before cannot fail
+}
+
+int32_t ps_layout_state(const ps_layout* lay, int64_t* num_blocks, int32_t* parked) {
+  if (!lay) return PS_ERR_INVALID_ARG;
+  if (num_blocks) *num_blocks = blocks_of(lay);
+  if (parked) *parked = lay->parked ? 1 : 0;
+  return PS_OK;
+}
+
+int32_t ps_stage_layout(const ps_layout* lay, int64_t* block_bytes, int64_t* scales_offset_bytes, int64_t* total_bytes) {
+  if (!lay) return PS_ERR_INVALID_ARG;
+  const ps_geometry& g = lay->geo;
+  const int64_t esz = g.kv_dtype == PS_F32 ? 4 : (g.kv_dtype == PS_BF16 ? 2 : 1);
+  const int64_t per_block = int64_t(g.num_kv_heads) * 2 * g.block_size * g.head_dim * esz;
+  const int64_t n = blocks_of(lay);
+  const int64_t scales_off = round_up(n * per_block, 256);
+  if (block_bytes) *block_bytes = per_block;
+  if (scales_offset_bytes) *scales_offset_bytes = scales_off;
+  if (total_bytes) *total_bytes = g.kv_dtype == PS_FP8_E4M3 ? scales_off + n * g.num_kv_heads * 2 * 4 : std::max<int64_t>(n * per_block, 16);
   return PS_OK;
 }
 
@@ -578,7 +667,7 @@ int32_t ps_layout_lengths(const ps_layout* lay, const int32_t** prefix_len, cons
 }
 
 int32_t ps_layout_append(ps_pool* pool, ps_layout* lay, const int32_t* active, const int32_t** dest) {
-  if (!pool || !lay) return PS_ERR_INVALID_ARG;
+  if (!pool || !lay || lay->parked) return PS_ERR_INVALID_ARG;
   const int32_t R = lay->num_requests, B = lay->geo.block_size;
   if (int64_t(pool->num_blocks) * B > INT32_MAX) return PS_ERR_INVALID_ARG;  // slot indices are int32
   auto is_active = [&](int32_t r) { return !active || active[r] != 0; };

@@ -34,6 +34,9 @@ struct ps_layout {
   int32_t num_prompts = 0, num_requests = 0;
   std::vector<int32_t> prefix_len, suffix_len, req_prompt, req_model;
   std::vector<int32_t> prefix_blk_indptr, prefix_blk, group_indptr, group_req, suffix_blk_indptr, suffix_blk;
+  // parked: the blocks were handed back to the pool (their contents staged elsewhere by the caller); the block
+  // arrays keep their shape but name no blocks until ps_layout_resume
+  bool parked = false;
   // optional third level: roots (contexts several prompts begin with); prompt_root[p] = -1: none
   int32_t num_roots = 0;
   std::vector<int32_t> root_len, prompt_root, root_blk_indptr, root_blk, root_group_indptr, root_group_req;

@@ -99,6 +99,23 @@ class DecodeBatch:
                        self._sc(), _stream())
         return dest
 
+    def stage_out(self, image: torch.Tensor):
+        """Copy the batch's blocks (and e4m3 scales) into `image`: uint8, device memory or pinned host memory."""
+        B.ps_kv_stage_out(self.layout, self.tables.data_ptr(), self.kv.data_ptr(), self._sc(), image.data_ptr(), _stream())
+
+    def stage_in(self, image: torch.Tensor):
+        B.ps_kv_stage_in(self.layout, self.tables.data_ptr(), image.data_ptr(), self.kv.data_ptr(), self._sc(), _stream())
+
+    def park(self, pool):
+        """Hand the batch's blocks back to the pool (after stage_out has completed)."""
+        torch.cuda.current_stream().synchronize()
+        B.ps_layout_park(pool, self.layout)
+
+    def resume(self, pool):
+        """Take blocks again and upload the new tables; stage_in then restores the contents."""
+        B.ps_layout_resume(pool, self.layout)
+        self._sync_plan()
+
     def workspace_views(self):
         """(o [slots, Hq, d] fp32, lse [slots, Hq] fp32) views of the partial-state workspace."""
         slots, off = B.ps_workspace_layout(self.layout)

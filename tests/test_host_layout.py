@@ -518,3 +518,74 @@ def test_root_groups_stay_in_the_persistent_launch_unless_the_batch_is_a_prefill
     assert not (sch["items"][:, 7] & 4).any() and len(sch["items"]) == len(items) - len(roots)
     B.ps_layout_release(pool, lay)
     B.ps_pool_destroy(pool)
+
+
+def test_park_and_resume_hand_worked_sequence():
+    """The sequence of tests/test_oracle_staging.py::test_hand_worked_park_and_resume through the C ABI."""
+    geo = B.geometry(4, 2, 64, 4, "f32", "f32")
+    pool = B.ps_pool_create(8, [3, 1, 7, 0, 2, 6, 5, 4])
+    a = B.ps_kv_layout(pool, geo, [6], [0, 0], [0, 1], [1, 5])
+    assert B.ps_layout_state(a) == (5, False)
+    B.ps_layout_park(pool, a)
+    assert B.ps_pool_free_list(pool).tolist() == [6, 5, 4, 0, 1, 2, 3, 7] and not B.ps_pool_refcounts(pool, 8).any()
+    assert B.ps_layout_state(a) == (5, True)
+    t = B.ps_layout_tables(a, 1, 2)
+    assert (t["prefix_blk"] == -1).all() and (t["suffix_blk"] == -1).all()      # a parked layout names no block
+    with pytest.raises(B.PsError) as e:
+        B.ps_layout_park(pool, a)
+    assert e.value.status == B.PS_ERR_INVALID_ARG
+    b = B.ps_kv_layout(pool, geo, [4], [0], [0], [9])
+    assert B.ps_layout_tables(b, 1, 1)["suffix_blk"].tolist() == [5, 4, 0]
+    with pytest.raises(B.PsError) as e:
+        B.ps_layout_resume(pool, a)
+    assert e.value.status == B.PS_ERR_OOM and B.ps_pool_free_list(pool).tolist() == [1, 2, 3, 7]
+    assert B.ps_layout_state(a) == (5, True)
+    B.ps_layout_release(pool, b)
+    B.ps_layout_resume(pool, a)
+    t = B.ps_layout_tables(a, 1, 2)
+    assert t["prefix_blk"].tolist() == [1, 2] and t["suffix_blk"].tolist() == [3, 7, 0]
+    assert B.ps_pool_free_list(pool).tolist() == [4, 5, 6]
+    assert B.ps_pool_refcounts(pool, 8).tolist() == [1, 2, 2, 1, 0, 0, 0, 1]
+    with pytest.raises(B.PsError):
+        B.ps_layout_resume(pool, a)
+    # a parked layout can be released without touching the pool
+    B.ps_layout_park(pool, a)
+    free = B.ps_pool_free_list(pool).tolist()
+    B.ps_layout_release(pool, a)
+    assert B.ps_pool_free_list(pool).tolist() == free and not B.ps_pool_refcounts(pool, 8).any()
+    B.ps_pool_destroy(pool)
+
+
+def test_park_resume_random_batches_against_oracle_and_parked_layouts_refuse_work():
+    from oracle import staging as ost
+    rng = np.random.default_rng(61)
+    for trial in range(10):
+        geo = wl.Geometry(8, 2, 64, int(rng.choice([4, 16])), "f32", "f32")
+        w = wl.make_tree_workload("p", geo, 3, rng.integers(0, 60, 2), [0, 1, -1, 0], rng.integers(0, 120, 4),
+                                  [[0, 1, 2], [1], [0, 2], [2]], rng.integers(0, 50, 7), pool_factor=2.0, seed=trial)
+        pool, lay, opool, olay = _both(w)
+        assert B.ps_blocks_needed(geo.block_size, w.prefix_len, w.suffix_len, w.root_len) == w.blocks_needed() == \
+            ost.blocks_needed(geo.block_size, w.prefix_len, w.suffix_len, w.root_len) == B.ps_layout_state(lay)[0]
+        B.ps_layout_replan(lay, B.plan_options(32, 16))
+        before = B.ps_layout_plan(lay, w.num_requests)
+        B.ps_layout_park(pool, lay)
+        ost.park_layout(opool, olay)
+        assert np.array_equal(B.ps_pool_free_list(pool), np.array(opool.free, np.int32))
+        with pytest.raises(B.PsError) as e:                                # no table growth while parked
+            B.ps_layout_append(pool, lay, w.num_requests)
+        assert e.value.status == B.PS_ERR_INVALID_ARG
+        B.ps_layout_resume(pool, lay)
+        ost.resume_layout(opool, olay)
+        t = dict(B.ps_layout_tables(lay, w.num_prompts, w.num_requests), **B.ps_layout_root_tables(lay))
+        for key in ("prefix_blk", "suffix_blk", "root_blk", "prefix_blk_indptr", "suffix_blk_indptr", "root_blk_indptr"):
+            assert np.array_equal(t[key], getattr(olay, key)), (trial, key)
+        assert np.array_equal(B.ps_pool_refcounts(pool, w.num_blocks), opool.refcount)
+        after = B.ps_layout_plan(lay, w.num_requests)                      # same plan, options kept
+        assert np.array_equal(before["items"], after["items"]) and np.array_equal(before["slot_base"], after["slot_base"])
+        _check_plan(w, lay, after)
+        bb, so, tot = B.ps_stage_layout(lay)
+        assert bb == 2 * 2 * geo.block_size * 64 * 4 and tot == w.blocks_needed() * bb and so % 256 == 0 and so >= tot
+        B.ps_layout_release(pool, lay)
+        B.ps_pool_destroy(pool)
+    with pytest.raises(B.PsError):
+        B.ps_blocks_needed(16, [5], [-1])
