@@ -9,6 +9,7 @@
 #include <cstring>
 #include <new>
 #include <numeric>
+#include <queue>
 #include <set>
 #include <utility>
 
@@ -246,21 +247,30 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
     std::vector<int> order(size_t(count), 0);
     std::iota(order.begin(), order.end(), begin);
     auto cost = [&](int i) { return int64_t(lay->items[size_t(i)].tok_end - lay->items[size_t(i)].tok_begin) + 64; };
-    std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return cost(a) > cost(b); });
-    std::vector<std::vector<int>> lists{size_t(num_wg)};
-    std::set<std::pair<int64_t, int>> load;  // (assigned cost, workgroup)
-    for (int w = 0; w < num_wg; ++w) load.insert({0, w});
-    for (int i : order) {
-      auto least = *load.begin();
-      load.erase(load.begin());
-      lists[size_t(least.second)].push_back(i);
-      load.insert({least.first + cost(i), least.second});
+    auto heavier = [&](int a, int b) { return cost(a) > cost(b); };
+    // the shared items and the suffix items are each in descending cost already; a range that spans both is the
+    // stable merge of two sorted runs
+    const int split = std::min(std::max(lay->num_prefix_items, begin), end) - begin;
+    if (!std::is_sorted(order.begin(), order.begin() + split, heavier)) std::stable_sort(order.begin(), order.begin() + split, heavier);
+    if (!std::is_sorted(order.begin() + split, order.end(), heavier)) std::stable_sort(order.begin() + split, order.end(), heavier);
+    std::inplace_merge(order.begin(), order.begin() + split, order.end(), heavier);
+    // least-loaded workgroup first, lowest index on ties: a min-heap of (assigned cost, workgroup)
+    typedef std::pair<int64_t, int> slot;
+    std::priority_queue<slot, std::vector<slot>, std::greater<slot>> load;
+    for (int w = 0; w < num_wg; ++w) load.push({0, w});
+    std::vector<int> wg_of(size_t(count), 0), fill(size_t(num_wg) + 1, 0);
+    for (int n = 0; n < count; ++n) {
+      const slot least = load.top();
+      load.pop();
+      wg_of[size_t(n)] = least.second;
+      ++fill[size_t(least.second) + 1];
+      load.push({least.first + cost(order[size_t(n)]), least.second});
     }
-    out.indptr.push_back(0);
-    for (const auto& l : lists) {
-      for (int i : l) out.items.push_back(lay->items[size_t(i)]);
-      out.indptr.push_back(int32_t(out.items.size()));
-    }
+    for (int w = 0; w < num_wg; ++w) fill[size_t(w) + 1] += fill[size_t(w)];
+    out.indptr.assign(fill.begin(), fill.end());
+    out.items.resize(size_t(count));
+    for (int n = 0; n < count; ++n)      // a workgroup's items keep the order in which they were assigned
+      out.items[size_t(fill[size_t(wg_of[size_t(n)])]++)] = lay->items[size_t(order[size_t(n)])];
     if (count == 0) out.indptr.assign(1, 0);
     return out;
   };

@@ -28,21 +28,19 @@
 
 #include "device_common.h"
 #include "launch.h"
+#include "mfma_common.h"
 
 namespace psdev {
 
 namespace {
 
-constexpr int kD = 128;
+constexpr int kD = kHeadDim;
 constexpr int kWaves = 4;
-constexpr int kTile = 32;         // tokens per tile buffer
+constexpr int kTile = kTileTokens;
 constexpr int kLdsRow = kD + 4;   // padded row of the merge buffer (floats)
 constexpr int kQRow = kD + 8;     // padded query row (bf16), 16 bytes of padding against bank conflicts
 constexpr int kHdrRing = 128;     // item headers staged in LDS (circular, refilled in halves)
-constexpr float kLazy = 8.f;      // log2 units the row maximum may run ahead of the softmax reference before a rescale
-
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+constexpr float kLazy = kLazyRescale;
 
 template <int KVT>
 struct TileRegs;                  // raw K/V of one 32-token tile as loaded
@@ -56,33 +54,6 @@ struct TileRegs<PS_FP8_E4M3> {
   u32x4 k[2][2];                  // [block][half]: 16 codes of token (lane%16), d 64*half + 16*(lane/16)..+15
   u32x2 v[8];                     // 8 codes: token i, d columns 8*(lane%16)..+7
 };
-
-__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
-
-// two e4m3 codes (bytes 2*half, 2*half+1 of w) -> two bf16 in one register (exact): one
-// v_cvt_scalef32_pk_bf16_fp8 with scale 1 (the instruction applies only the scale's exponent, so the real
-// per-block scales are applied to the scores and probabilities instead)
-__device__ __forceinline__ uint32_t e4m3x2_to_bf16x2(uint32_t w, bool hi) {
-  const bf16x2 b = hi ? __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true)
-                      : __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false);
-  return __builtin_bit_cast(uint32_t, b);
-}
-
-__device__ __forceinline__ u32x4 e4m3x8_to_bf16x8(uint32_t lo, uint32_t hi) {
-  u32x4 r;
-  r.x = e4m3x2_to_bf16x2(lo, false);
-  r.y = e4m3x2_to_bf16x2(lo, true);
-  r.z = e4m3x2_to_bf16x2(hi, false);
-  r.w = e4m3x2_to_bf16x2(hi, true);
-  return r;
-}
-
-// element offset of the 8 query values that meet K's k-step `step` in lane group kg
-template <int KVT>
-__device__ __forceinline__ int q_chunk_elem(int step, int kg) {
-  if constexpr (KVT == PS_BF16) return 32 * step + 8 * kg;
-  return 64 * (step >> 1) + 16 * kg + 8 * (step & 1);
-}
 
 // Wave-uniform view of one work item for one wave.
 struct ItemCtx {

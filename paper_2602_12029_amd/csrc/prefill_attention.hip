@@ -21,39 +21,16 @@
 
 #include "device_common.h"
 #include "launch.h"
+#include "mfma_common.h"
 
 namespace psdev {
 
 namespace {
 
-constexpr int kD = 128;
+constexpr int kD = kHeadDim;
 constexpr int kNT = 4;            // 16-row tiles per wave
-constexpr int kTile = 32;         // tokens per tile
-constexpr float kLazy = 8.f;      // log2 units the row maximum may run ahead of the softmax reference before a rescale
-
-typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
-typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
-
-__device__ __forceinline__ bf16x8 bits_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
-
-// two e4m3 codes (a byte pair of w) -> two bf16, exactly (one v_cvt_scalef32_pk_bf16_fp8, scale 1)
-__device__ __forceinline__ uint32_t codes_to_bf16x2(uint32_t w, bool hi) {
-  const bf16x2 b = hi ? __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true)
-                      : __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false);
-  return __builtin_bit_cast(uint32_t, b);
-}
-__device__ __forceinline__ u32x4 codes_to_bf16x8(uint32_t lo, uint32_t hi) {
-  return u32x4{codes_to_bf16x2(lo, false), codes_to_bf16x2(lo, true), codes_to_bf16x2(hi, false),
-               codes_to_bf16x2(hi, true)};
-}
-
-// element offset of the 8 query values that meet K's k-step `step` in lane group kg (the contraction index is
-// permuted the same way in K as loaded and in Q)
-template <int KVT>
-__device__ __forceinline__ int q_piece(int step, int kg) {
-  if constexpr (KVT == PS_BF16) return 32 * step + 8 * kg;
-  return 64 * (step >> 1) + 16 * kg + 8 * (step & 1);
-}
+constexpr int kTile = kTileTokens;
+constexpr float kLazy = kLazyRescale;
 
 __device__ __forceinline__ int wave_max(int x) {
 #pragma unroll
@@ -104,7 +81,7 @@ __global__ __launch_bounds__(256, 1) void prefill_attention_kernel(AttnParams p,
       lim[t] = limited ? min(tok_end, p.visible[req]) : tok_end;
       const uint16_t* qrow = static_cast<const uint16_t*>(p.q) + (int64_t(req) * p.num_q_heads + kv_head * G + row % G) * kD;
 #pragma unroll
-      for (int st = 0; st < 4; ++st) piece[st] = *reinterpret_cast<const u32x4*>(qrow + q_piece<KVT>(st, kg));
+      for (int st = 0; st < 4; ++st) piece[st] = *reinterpret_cast<const u32x4*>(qrow + q_chunk_elem<KVT>(st, kg));
       lim_hi = max(lim_hi, lim[t]);
       lim_lo = min(lim_lo, lim[t]);
     }
@@ -200,12 +177,12 @@ __global__ __launch_bounds__(256, 1) void prefill_attention_kernel(AttnParams p,
     for (int b = 0; b < 2; ++b) {
       if constexpr (KVT == PS_BF16) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) ka.a[b][s] = bits_bf16x8(kt.k[b][s]);
+        for (int s = 0; s < 4; ++s) ka.a[b][s] = as_bf16x8(kt.k[b][s]);
       } else {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-          ka.a[b][2 * h] = bits_bf16x8(codes_to_bf16x8(kt.k[b][h].x, kt.k[b][h].y));
-          ka.a[b][2 * h + 1] = bits_bf16x8(codes_to_bf16x8(kt.k[b][h].z, kt.k[b][h].w));
+          ka.a[b][2 * h] = as_bf16x8(e4m3x8_to_bf16x8(kt.k[b][h].x, kt.k[b][h].y));
+          ka.a[b][2 * h + 1] = as_bf16x8(e4m3x8_to_bf16x8(kt.k[b][h].z, kt.k[b][h].w));
         }
       }
     }
@@ -220,7 +197,7 @@ __global__ __launch_bounds__(256, 1) void prefill_attention_kernel(AttnParams p,
     asm volatile("" : "+v"(q_lane));
     QOperands q;
 #pragma unroll
-    for (int st = 0; st < 4; ++st) q.b[st] = bits_bf16x8(sm_qb[wave][4 * t + st][q_lane]);
+    for (int st = 0; st < 4; ++st) q.b[st] = as_bf16x8(sm_qb[wave][4 * t + st][q_lane]);
     return q;
   };
   // Raw scores S^T = K Q^T of one tile for row tile t: two accumulation chains (one per 16-token block), issued
@@ -330,7 +307,7 @@ __global__ __launch_bounds__(256, 1) void prefill_attention_kernel(AttnParams p,
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       if constexpr (KVT == PS_BF16) vr[i] = vtile.v[i];
-      else vr[i] = codes_to_bf16x8(vtile.v[i].x, vtile.v[i].y);
+      else vr[i] = e4m3x8_to_bf16x8(vtile.v[i].x, vtile.v[i].y);
     }
     if constexpr (kLimited) {      // slots past the item's range may hold anything: zero them
 #pragma unroll
@@ -347,7 +324,7 @@ __global__ __launch_bounds__(256, 1) void prefill_attention_kernel(AttnParams p,
         const uint32_t a = vr[2 * i2][cc >> 1], b = vr[2 * i2 + 1][cc >> 1];
         w[i2] = __builtin_amdgcn_perm(b, a, (cc & 1) ? 0x07060302u : 0x05040100u);
       }
-      const bf16x8 vt = bits_bf16x8(u32x4{w[0], w[1], w[2], w[3]});
+      const bf16x8 vt = as_bf16x8(u32x4{w[0], w[1], w[2], w[3]});
 #pragma unroll
       for (int t = 0; t < kNT; ++t) acc[t][cc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, pb[t], acc[t][cc], 0, 0, 0);
     }
