@@ -73,7 +73,14 @@ class Layout:
     root_group_req: np.ndarray = None
 
 
-def build_layout(pool: BlockPool, block_size: int, prefix_len, req_prompt, req_model, suffix_len) -> Layout:
+def build_layout(pool: BlockPool, block_size: int, prefix_len, req_prompt, req_model, suffix_len, adopt=None) -> Layout:
+    """adopt (optional): per prompt, the physical ids of blocks another layout already holds that contain the
+    beginning of this prompt's prefix -- the cached context a later step continues from (System Design: prefix-aware
+    routing keeps a context's cache where it is, "enabling incremental cache extension instead of recomputing the
+    prefix from scratch"; execution pipeline: X(i) = [X(i-1); Y(i)]).  Only full blocks are adopted: the n adopted
+    blocks of prompt p are the prompt's tokens [0, n * B), n * B <= Lp; each gains one reference per request on the
+    prompt, exactly like a block taken from the free list, so it stays alive until the last layout that references
+    it is released.  The remaining ceil(Lp/B) - n blocks come from the free list as usual."""
     prefix_len = np.asarray(prefix_len, dtype=np.int64)
     suffix_len = np.asarray(suffix_len, dtype=np.int64)
     req_prompt = np.asarray(req_prompt, dtype=np.int64)
@@ -95,15 +102,26 @@ def build_layout(pool: BlockPool, block_size: int, prefix_len, req_prompt, req_m
 
     nb_prefix = (prefix_len + block_size - 1) // block_size
     nb_suffix = (suffix_len + block_size - 1) // block_size
-    needed = int(nb_prefix.sum() + nb_suffix.sum())
+    adopted = [[] for _ in range(num_p)] if adopt is None else [[int(b) for b in a] for a in adopt]
+    if len(adopted) != num_p:
+        raise LayoutError("one list of adopted blocks per prompt")
+    seen = set()
+    for p in range(num_p):
+        if len(adopted[p]) * block_size > prefix_len[p]:
+            raise LayoutError("adopted blocks must be full blocks of the prompt's prefix")
+        for blk in adopted[p]:
+            if not 0 <= blk < pool.num_blocks or pool.refcount[blk] <= 0 or blk in seen:
+                raise LayoutError("an adopted block must be alive and named once")
+            seen.add(blk)
+    needed = int(nb_prefix.sum() + nb_suffix.sum()) - sum(len(a) for a in adopted)
     if needed > len(pool.free):
         raise OutOfBlocks(f"need {needed} blocks, {len(pool.free)} free")
 
     prefix_indptr = np.zeros(num_p + 1, np.int32)
     prefix_blk = []
     for p in range(num_p):
-        for _ in range(int(nb_prefix[p])):
-            blk = pool.free.popleft()
+        for i in range(int(nb_prefix[p])):
+            blk = adopted[p][i] if i < len(adopted[p]) else pool.free.popleft()
             pool.refcount[blk] += len(members[p])
             prefix_blk.append(blk)
         prefix_indptr[p + 1] = len(prefix_blk)
