@@ -109,6 +109,23 @@ int32_t ps_kv_layout_tree(ps_pool* pool, const ps_geometry* geometry, int32_t nu
                           int32_t num_prompts, const int32_t* prompt_root, const int32_t* prefix_len,
                           int32_t num_requests, const int32_t* req_prompt, const int32_t* req_model,
                           const int32_t* suffix_len, ps_layout** out);
+/* ps_kv_layout_adopt: ps_kv_layout for a batch that continues cached contexts.  Prefix-aware routing keeps a context's
+ * cache where it is, "enabling incremental cache extension instead of recomputing the prefix from scratch" (System
+ * Design), and the context grows as X(i) = [X(i-1); Y(i)] (execution pipeline): the layout of the next step -- the
+ * partial prefill of Y(i), or the next decode batch over X(i) -- adopts the blocks that already hold the beginning of
+ * its prompts.  adopt_indptr[P+1], adopt_blk[..]: for prompt p the physical ids of its first
+ * n = adopt_indptr[p+1] - adopt_indptr[p] prefix blocks, taken over from a layout that still holds them.  Only full
+ * blocks are adopted (n * block_size <= prefix_len[p]); each gains one reference per request on the prompt, like a
+ * block from the free list, and stays alive until the last layout referencing it is released; the other
+ * ceil(Lp/B) - n blocks come from the free list as usual.  ps_kv_ingest(which = 0) on such a layout leaves the adopted
+ * blocks alone: its source holds, per prompt, only the tokens from n * block_size on.  A parked layout gives up its
+ * adoptions: its image holds the adopted blocks' contents and a resume takes fresh blocks for all of them.
+ * Additional errors: PS_ERR_INVALID_ARG for an adopted id that is out of range, not referenced by any layout, or
+ * named twice, and for more adopted blocks than the prefix has full blocks. */
+int32_t ps_kv_layout_adopt(ps_pool* pool, const ps_geometry* geometry, int32_t num_prompts, const int32_t* prefix_len,
+                           const int32_t* adopt_indptr, const int32_t* adopt_blk, int32_t num_requests,
+                           const int32_t* req_prompt, const int32_t* req_model, const int32_t* suffix_len,
+                           ps_layout** out);
 /* Host views of the root level (valid until release; any output pointer may be NULL): root_blk_indptr[T+1],
  * root_blk[..], root_group_indptr[T+1], root_group_req[..] (the requests below a root, ascending). */
 int32_t ps_layout_root_tables(const ps_layout* layout, int32_t* num_roots, const int32_t** root_blk_indptr,

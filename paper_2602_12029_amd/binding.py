@@ -26,7 +26,7 @@ EXPORTS = [
     "ps_prefix_attention", "ps_suffix_attention", "ps_prefix_suffix_attention", "ps_merge_states", "ps_decode_attention",
     "ps_layout_lengths", "ps_layout_append", "ps_kv_append", "ps_kv_ingest",
     "ps_layout_set_visible", "ps_layout_request_list", "ps_kv_layout_tree", "ps_layout_root_tables",
-    "ps_blocks_needed", "ps_layout_state", "ps_stage_layout", "ps_kv_stage_out", "ps_kv_stage_in", "ps_layout_park",
+    "ps_kv_layout_adopt", "ps_blocks_needed", "ps_layout_state", "ps_stage_layout", "ps_kv_stage_out", "ps_kv_stage_in", "ps_layout_park",
     "ps_layout_resume",
     "ps_strerror", "ps_last_hip_error",
 ]
@@ -174,6 +174,26 @@ def ps_kv_layout_tree(pool, geo: ps_geometry, root_len, prompt_root, prefix_len,
     st = _lib().ps_kv_layout_tree(pool, C.byref(geo), C.c_int32(rl.size), rlp, C.c_int32(pl.size), prp, plp,
                                   C.c_int32(rp.size), rpp, rmp, slp, C.byref(out))
     _check(st, "ps_kv_layout_tree")
+    return out
+
+
+def ps_kv_layout_adopt(pool, geo: ps_geometry, prefix_len, adopt, req_prompt, req_model, suffix_len):
+    """adopt: per prompt, the list of block ids (full blocks of the beginning of its prefix) taken over from a
+    layout that still holds them."""
+    pl, plp = _i32(prefix_len)
+    rp, rpp = _i32(req_prompt)
+    rm, rmp = _i32(req_model)
+    sl, slp = _i32(suffix_len)
+    if len(adopt) != pl.size or not (rp.shape == rm.shape == sl.shape):
+        raise ValueError("array lengths do not match")
+    indptr = np.zeros(pl.size + 1, np.int32)
+    indptr[1:] = np.cumsum([len(a) for a in adopt])
+    ai, aip = _i32(indptr)
+    ab, abp = _i32(np.concatenate([np.asarray(a, np.int32) for a in adopt]) if pl.size else np.zeros(0, np.int32))
+    out = C.c_void_p()
+    st = _lib().ps_kv_layout_adopt(pool, C.byref(geo), C.c_int32(pl.size), plp, aip, abp, C.c_int32(rp.size), rpp, rmp,
+                                   slp, C.byref(out))
+    _check(st, "ps_kv_layout_adopt")
     return out
 
 

@@ -63,6 +63,7 @@ __global__ __launch_bounds__(256) void ingest_copy_kernel(KvWriteParams p, const
   const int h = int((tile >> 1) % p.num_kv_heads);
   const int e = entry0 + int((tile >> 1) / p.num_kv_heads);
   const int n_valid = p.ent_valid[e];
+  if (n_valid <= 0) return;   // a block adopted from another layout: its contents are already there
   const T* src = (which ? src_v : src_k) + int64_t(p.ent_tok0[e]) * src_s_tok + int64_t(h) * src_s_head;
   T* dst = static_cast<T*>(p.kv) + int64_t(p.blk[e]) * p.s_block + int64_t(h) * p.s_head + int64_t(which) * p.s_kv;
   const int cpt = p.head_dim / kVec;   // 16-byte chunks per token
@@ -87,6 +88,7 @@ __global__ __launch_bounds__(256) void ingest_e4m3_kernel(KvWriteParams p, const
   const int h = int((tile >> 1) % uint32_t(p.num_kv_heads));
   const int e = entry0 + int((tile >> 1) / uint32_t(p.num_kv_heads));
   const int n_valid = p.ent_valid[e];
+  if (n_valid <= 0) return;   // a block adopted from another layout: contents and scale are already there
   const uint16_t* src = (which ? src_v : src_k) + int64_t(p.ent_tok0[e]) * src_s_tok + int64_t(h) * src_s_head;
   const int id = p.blk[e];
   uint8_t* dst = static_cast<uint8_t*>(p.kv) + int64_t(id) * p.s_block + int64_t(h) * p.s_head + int64_t(which) * p.s_kv;

@@ -317,22 +317,27 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   int32_t* b = lay->blob.data();
   {
     const int32_t B = g.block_size;
-    auto fill_entries = [&](const std::vector<int32_t>& indptr, const std::vector<int32_t>& len, int32_t entry0) {
+    // skip: per segment, leading blocks that are not to be written (adopted from another layout); the ragged source
+    // then holds only the tokens after them
+    auto fill_entries = [&](const std::vector<int32_t>& indptr, const std::vector<int32_t>& len, int32_t entry0,
+                            const std::vector<int32_t>* skip) {
       int64_t tok = 0;
       for (size_t s = 0; s + 1 < indptr.size(); ++s) {
+        const int64_t skipped = skip ? int64_t((*skip)[s + 1] - (*skip)[s]) * B : 0;
         for (int32_t i = indptr[s]; i < indptr[s + 1]; ++i) {
           const int64_t first = int64_t(i - indptr[s]) * B;
           if (tok + first > INT32_MAX) return false;
-          b[lay->off_ent_tok0 + entry0 + i] = int32_t(tok + first);
-          b[lay->off_ent_valid + entry0 + i] = int32_t(std::min<int64_t>(B, len[s] - first));
+          const bool kept = first < skipped;
+          b[lay->off_ent_tok0 + entry0 + i] = kept ? 0 : int32_t(tok + first - skipped);
+          b[lay->off_ent_valid + entry0 + i] = kept ? 0 : int32_t(std::min<int64_t>(B, len[s] - first));
         }
-        tok += len[s];
+        tok += len[s] - skipped;
       }
       return true;
     };
-    if (!fill_entries(lay->prefix_blk_indptr, lay->prefix_len, 0) ||
-        !fill_entries(lay->suffix_blk_indptr, lay->suffix_len, total_prefix_blocks) ||
-        (lay->num_roots && !fill_entries(lay->root_blk_indptr, lay->root_len, root_blk0)))
+    if (!fill_entries(lay->prefix_blk_indptr, lay->prefix_len, 0, lay->adopt_indptr.empty() ? nullptr : &lay->adopt_indptr) ||
+        !fill_entries(lay->suffix_blk_indptr, lay->suffix_len, total_prefix_blocks, nullptr) ||
+        (lay->num_roots && !fill_entries(lay->root_blk_indptr, lay->root_len, root_blk0, nullptr)))
       return PS_ERR_INVALID_ARG;
     lay->append_dest.resize(size_t(R), -1);
     std::copy(lay->append_dest.begin(), lay->append_dest.end(), b + lay->off_dest);
@@ -412,10 +417,20 @@ void take_blocks(ps_pool* pool, ps_layout* lay) {
     lay->root_blk_indptr[size_t(t) + 1] = int32_t(lay->root_blk.size());
   }
   lay->prefix_blk_indptr.assign(size_t(lay->num_prompts) + 1, 0);
+  const bool adopting = !lay->adopt_indptr.empty();
   for (int32_t p = 0; p < lay->num_prompts; ++p) {
     const int32_t k = lay->group_indptr[size_t(p) + 1] - lay->group_indptr[size_t(p)];
     const int64_t n = ceil_div(lay->prefix_len[size_t(p)], B);
-    for (int64_t i = 0; i < n; ++i) lay->prefix_blk.push_back(take(k));
+    const int32_t a0 = adopting ? lay->adopt_indptr[size_t(p)] : 0, a1 = adopting ? lay->adopt_indptr[size_t(p) + 1] : 0;
+    for (int64_t i = 0; i < n; ++i) {
+      if (i < a1 - a0) {   // a cached block another layout holds: one more reference per request, like a fresh one
+        const int32_t blk = lay->adopt_blk[size_t(a0 + i)];
+        pool->refcount[size_t(blk)] += k;
+        lay->prefix_blk.push_back(blk);
+      } else {
+        lay->prefix_blk.push_back(take(k));
+      }
+    }
     lay->prefix_blk_indptr[size_t(p) + 1] = int32_t(lay->prefix_blk.size());
   }
   lay->suffix_blk_indptr.assign(size_t(lay->num_requests) + 1, 0);
@@ -426,7 +441,7 @@ void take_blocks(ps_pool* pool, ps_layout* lay) {
   }
 }
 
-int64_t blocks_of(const ps_layout* lay) {
+int64_t blocks_of(const ps_layout* lay) {   // blocks the layout references, adopted ones included
   const int32_t B = lay->geo.block_size;
   int64_t n = 0;
   for (int32_t l : lay->root_len) n += ceil_div(l, B);
@@ -486,10 +501,14 @@ int32_t ps_pool_refcounts(const ps_pool* pool, const int32_t** refcount) {
   return PS_OK;
 }
 
-int32_t ps_kv_layout_tree(ps_pool* pool, const ps_geometry* geometry, int32_t num_roots, const int32_t* root_len,
-                          int32_t num_prompts, const int32_t* prompt_root, const int32_t* prefix_len,
-                          int32_t num_requests, const int32_t* req_prompt, const int32_t* req_model,
-                          const int32_t* suffix_len, ps_layout** out) {
+}  // extern "C"
+
+namespace {
+
+int32_t build_layout(ps_pool* pool, const ps_geometry* geometry, int32_t num_roots, const int32_t* root_len,
+                     int32_t num_prompts, const int32_t* prompt_root, const int32_t* prefix_len,
+                     const int32_t* adopt_indptr, const int32_t* adopt_blk, int32_t num_requests,
+                     const int32_t* req_prompt, const int32_t* req_model, const int32_t* suffix_len, ps_layout** out) {
   if (!pool || !geometry || !out || num_roots < 0 || num_prompts < 0 || num_requests < 0) return PS_ERR_INVALID_ARG;
   if ((num_prompts && !prefix_len) || (num_requests && (!req_prompt || !req_model || !suffix_len)))
     return PS_ERR_INVALID_ARG;
@@ -525,6 +544,21 @@ int32_t ps_kv_layout_tree(ps_pool* pool, const ps_geometry* geometry, int32_t nu
     needed += ceil_div(prefix_len[p], B);
   }
   for (int32_t r = 0; r < num_requests; ++r) needed += ceil_div(suffix_len[r], B);
+  if (adopt_indptr) {
+    // adopted blocks: full blocks of the prompt's prefix, alive (referenced by some layout) and named once
+    if (adopt_indptr[0] != 0 || (adopt_indptr[num_prompts] > 0 && !adopt_blk)) return PS_ERR_INVALID_ARG;
+    std::set<int32_t> named;
+    for (int32_t p = 0; p < num_prompts; ++p) {
+      const int32_t n = adopt_indptr[p + 1] - adopt_indptr[p];
+      if (n < 0 || int64_t(n) * B > prefix_len[p]) return PS_ERR_INVALID_ARG;
+      for (int32_t i = adopt_indptr[p]; i < adopt_indptr[p + 1]; ++i) {
+        const int32_t blk = adopt_blk[i];
+        if (blk < 0 || blk >= pool->num_blocks || pool->refcount[size_t(blk)] <= 0 || !named.insert(blk).second)
+          return PS_ERR_INVALID_ARG;
+      }
+      needed -= n;
+    }
+  }
   if (needed > int64_t(pool->free_list.size())) return PS_ERR_OOM;
 
   ps_layout* lay = new (std::nothrow) ps_layout();
@@ -536,6 +570,10 @@ int32_t ps_kv_layout_tree(ps_pool* pool, const ps_geometry* geometry, int32_t nu
   lay->suffix_len.assign(suffix_len, suffix_len + num_requests);
   lay->req_prompt.assign(req_prompt, req_prompt + num_requests);
   lay->req_model.assign(req_model, req_model + num_requests);
+  if (adopt_indptr && adopt_indptr[num_prompts] > 0) {
+    lay->adopt_indptr.assign(adopt_indptr, adopt_indptr + num_prompts + 1);
+    lay->adopt_blk.assign(adopt_blk, adopt_blk + adopt_indptr[num_prompts]);
+  }
   lay->num_roots = num_roots;
   if (num_roots) {
     lay->root_len.assign(root_len, root_len + num_roots);
@@ -573,11 +611,32 @@ int32_t ps_kv_layout_tree(ps_pool* pool, const ps_geometry* geometry, int32_t nu
   return PS_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+int32_t ps_kv_layout_tree(ps_pool* pool, const ps_geometry* geometry, int32_t num_roots, const int32_t* root_len,
+                          int32_t num_prompts, const int32_t* prompt_root, const int32_t* prefix_len,
+                          int32_t num_requests, const int32_t* req_prompt, const int32_t* req_model,
+                          const int32_t* suffix_len, ps_layout** out) {
+  return build_layout(pool, geometry, num_roots, root_len, num_prompts, prompt_root, prefix_len, nullptr, nullptr,
+                      num_requests, req_prompt, req_model, suffix_len, out);
+}
+
 int32_t ps_kv_layout(ps_pool* pool, const ps_geometry* geometry, int32_t num_prompts, const int32_t* prefix_len,
                      int32_t num_requests, const int32_t* req_prompt, const int32_t* req_model,
                      const int32_t* suffix_len, ps_layout** out) {
-  return ps_kv_layout_tree(pool, geometry, 0, nullptr, num_prompts, nullptr, prefix_len, num_requests, req_prompt,
-                           req_model, suffix_len, out);
+  return build_layout(pool, geometry, 0, nullptr, num_prompts, nullptr, prefix_len, nullptr, nullptr, num_requests,
+                      req_prompt, req_model, suffix_len, out);
+}
+
+int32_t ps_kv_layout_adopt(ps_pool* pool, const ps_geometry* geometry, int32_t num_prompts, const int32_t* prefix_len,
+                           const int32_t* adopt_indptr, const int32_t* adopt_blk, int32_t num_requests,
+                           const int32_t* req_prompt, const int32_t* req_model, const int32_t* suffix_len,
+                           ps_layout** out) {
+  if (num_prompts > 0 && !adopt_indptr) return PS_ERR_INVALID_ARG;
+  return build_layout(pool, geometry, 0, nullptr, num_prompts, nullptr, prefix_len, adopt_indptr, adopt_blk,
+                      num_requests, req_prompt, req_model, suffix_len, out);
 }
 
 int32_t ps_layout_root_tables(const ps_layout* lay, int32_t* num_roots, const int32_t** root_blk_indptr,
@@ -621,6 +680,8 @@ int32_t ps_layout_park(ps_pool* pool, ps_layout* lay) {
   if (!pool || !lay || lay->parked) return PS_ERR_INVALID_ARG;
   if (int32_t st = drop_references(pool, lay)) return st;
   lay->parked = true;
+  lay->adopt_indptr.clear();   // a resumed layout holds fresh blocks only: its image carries the adopted contents
+  lay->adopt_blk.clear();
   std::fill(lay->root_blk.begin(), lay->root_blk.end(), -1);
   std::fill(lay->prefix_blk.begin(), lay->prefix_blk.end(), -1);
   std::fill(lay->suffix_blk.begin(), lay->suffix_blk.end(), -1);

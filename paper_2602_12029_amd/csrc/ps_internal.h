@@ -34,6 +34,9 @@ struct ps_layout {
   int32_t num_prompts = 0, num_requests = 0;
   std::vector<int32_t> prefix_len, suffix_len, req_prompt, req_model;
   std::vector<int32_t> prefix_blk_indptr, prefix_blk, group_indptr, group_req, suffix_blk_indptr, suffix_blk;
+  // blocks adopted from another layout (the cached beginning of a prompt's prefix): adopt_indptr[P+1], ids; empty
+  // when nothing is adopted.  They are the first blocks of the prompt's prefix list and are not written by ingest.
+  std::vector<int32_t> adopt_indptr, adopt_blk;
   // parked: the blocks were handed back to the pool (their contents staged elsewhere by the caller); the block
   // arrays keep their shape but name no blocks until ps_layout_resume
   bool parked = false;

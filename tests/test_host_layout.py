@@ -589,3 +589,78 @@ def test_park_resume_random_batches_against_oracle_and_parked_layouts_refuse_wor
         B.ps_pool_destroy(pool)
     with pytest.raises(B.PsError):
         B.ps_blocks_needed(16, [5], [-1])
+
+
+def test_adopted_blocks_hand_worked_and_rules():
+    """tests/test_oracle_layout.py::test_adopted_blocks_hand_worked and ::test_adoption_rules through the C ABI."""
+    geo = B.geometry(4, 2, 64, 4, "f32", "f32")
+    pool = B.ps_pool_create(10)
+    a = B.ps_kv_layout(pool, geo, [10], [0, 0], [0, 1], [2, 5])
+    c = B.ps_kv_layout_adopt(pool, geo, [14], [[0, 1]], [0, 0, 0], [0, 1, 2], [0, 3, 0])
+    t = B.ps_layout_tables(c, 1, 3)
+    assert t["prefix_blk"].tolist() == [0, 1, 6, 7] and t["suffix_blk"].tolist() == [8]
+    assert B.ps_pool_refcounts(pool, 10).tolist() == [5, 5, 2, 1, 1, 1, 3, 3, 1, 0] and B.ps_pool_free_list(pool).tolist() == [9]
+    assert B.ps_layout_state(c) == (5, False)
+    B.ps_layout_release(pool, a)
+    assert B.ps_pool_refcounts(pool, 10).tolist() == [3, 3, 0, 0, 0, 0, 3, 3, 1, 0]
+    assert B.ps_pool_free_list(pool).tolist() == [9, 2, 3, 4, 5]
+    B.ps_layout_release(pool, c)
+    assert not B.ps_pool_refcounts(pool, 10).any() and B.ps_pool_free_list(pool).tolist() == [9, 2, 3, 4, 5, 0, 1, 6, 7, 8]
+    B.ps_pool_destroy(pool)
+    pool = B.ps_pool_create(6)
+    a = B.ps_kv_layout(pool, geo, [9], [0], [0], [0])
+    bad = [([11], [[0, 1, 2]], [0], B.PS_ERR_INVALID_ARG),      # only full blocks: 3 * 4 > 11
+           ([12], [[0, 5]], [0], B.PS_ERR_INVALID_ARG),         # block 5 is not alive
+           ([12, 12], [[0], [0]], [0, 1], B.PS_ERR_INVALID_ARG),  # named twice
+           ([24], [[0, 1]], [0], B.PS_ERR_OOM)]                 # needs 4 more, 3 free
+    for prefix, adopt, rp, status in bad:
+        with pytest.raises(B.PsError) as e:
+            B.ps_kv_layout_adopt(pool, geo, prefix, adopt, rp, [0] * len(rp), [0] * len(rp))
+        assert e.value.status == status
+        assert B.ps_pool_refcounts(pool, 6).tolist() == [1, 1, 1, 0, 0, 0] and B.ps_pool_free_list(pool).tolist() == [3, 4, 5]
+    b = B.ps_kv_layout_adopt(pool, geo, [4], [[]], [0], [0], [0])                   # adopting nothing
+    assert B.ps_layout_tables(b, 1, 1)["prefix_blk"].tolist() == [3]
+    B.ps_layout_release(pool, a)
+    B.ps_layout_release(pool, b)
+    assert not B.ps_pool_refcounts(pool, 6).any()
+    B.ps_pool_destroy(pool)
+
+
+def test_adoption_random_chains_against_oracle():
+    """Contexts continued over several steps: each step's layout adopts the full prefix blocks of the one before, which
+    is then released; tables, refcounts and free lists stay equal to the oracle's throughout."""
+    rng = np.random.default_rng(71)
+    for trial in range(8):
+        bsz = int(rng.choice([4, 16]))
+        geo = B.geometry(8, 2, 64, bsz, "f32", "f32")
+        num_p = int(rng.integers(1, 4))
+        pool, opool = B.ps_pool_create(400), ol.BlockPool(400)
+        ctx = rng.integers(1, 60, num_p)
+        prev = prev_o = None
+        for step in range(4):
+            membership = [sorted(rng.choice(4, size=int(rng.integers(1, 4)), replace=False).tolist()) for _ in range(num_p)]
+            rp = [p for p, m in enumerate(membership) for _ in m]
+            rm = [x for m in membership for x in m]
+            sl = rng.integers(0, 40, len(rp))
+            if prev is None:
+                adopt = [[] for _ in range(num_p)]
+            else:
+                pt = B.ps_layout_tables(prev, num_p, prev_nreq)
+                adopt = [pt["prefix_blk"][pt["prefix_blk_indptr"][p]:pt["prefix_blk_indptr"][p] + int(prev_ctx[p]) // bsz].tolist()
+                         for p in range(num_p)]
+            lay = B.ps_kv_layout_adopt(pool, geo, ctx, adopt, rp, rm, sl)
+            olay = ol.build_layout(opool, bsz, ctx, rp, rm, sl, adopt=adopt)
+            t = B.ps_layout_tables(lay, num_p, len(rp))
+            for key in t:
+                assert np.array_equal(t[key], getattr(olay, key)), (trial, step, key)
+            if prev is not None:
+                B.ps_layout_release(pool, prev)
+                ol.release_layout(opool, prev_o)
+            assert np.array_equal(B.ps_pool_refcounts(pool, 400), opool.refcount)
+            assert np.array_equal(B.ps_pool_free_list(pool), np.array(opool.free, np.int32))
+            prev, prev_o, prev_ctx, prev_nreq = lay, olay, ctx.copy(), len(rp)
+            ctx = ctx + rng.integers(0, 50, num_p)                      # the contexts grow
+        B.ps_layout_release(pool, prev)
+        ol.release_layout(opool, prev_o)
+        assert not B.ps_pool_refcounts(pool, 400).any()
+        B.ps_pool_destroy(pool)
