@@ -14,7 +14,9 @@ error bounds, order-of-arrival identities between append and ingest, scalar
 brute force and a hand-worked table.  The third sharing level (layout.build_layout_tree, a
 context several prompts begin with; tests/test_oracle_tree.py) is pinned by a hand-worked table, the
 block-count and refcount invariants, brute-force dense attention and bitwise identity with the
-two-level oracle on the flattened batch.  Staging of cold blocks (staging.py; tests/test_oracle_staging.py)
+two-level oracle on the flattened batch.  Adoption of a cached context's blocks by a later layout (layout.build_layout(adopt=...);
+tests/test_oracle_layout.py) is pinned by a hand-worked instance, its rules, and attention over the
+continued context against the unpaged definition.  Staging of cold blocks (staging.py; tests/test_oracle_staging.py)
 is pinned by a hand-worked park / resume sequence, the block-count identity, and the requirement that
 a parked, overwritten and resumed batch reads back bit for bit.  No function here is unpinned.
 """

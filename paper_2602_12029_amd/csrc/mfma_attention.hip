@@ -313,8 +313,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
         // units; the scales are positive, so a block's maximum scales like its scores); only when it fires somewhere in
         // the wave is the maximum of each row put together across the row's four lanes, which must agree on m_run.
         // A row that has seen nothing yet has m_run = -inf and stays there until a score arrives.
-        float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])) * sc_k[0],
-                         fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])) * sc_k[1]);
+        float mx = fmaxf(max_of4(s[0]) * sc_k[0], max_of4(s[1]) * sc_k[1]);
         if (__builtin_amdgcn_ballot_w64(mx > m_run[t] + kLazy) != 0) {
           mx = fmaxf(mx, lane_xor(mx, 16));
           mx = fmaxf(mx, lane_xor(mx, 32));

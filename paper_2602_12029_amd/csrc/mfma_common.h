@@ -35,6 +35,13 @@ __device__ __forceinline__ u32x4 e4m3x8_to_bf16x8(uint32_t lo, uint32_t hi) {
   return r;
 }
 
+// Largest of the four scores of a block.  The fold starts from the constant -inf, which lets the compiler emit two
+// three-input maxima and nothing else (a two-input float maximum first quiets its inputs, one instruction each).
+__device__ __forceinline__ float max_of4(f32x4 s) {
+  const float seed = -__builtin_inff();
+  return fmaxf(fmaxf(fmaxf(fmaxf(seed, s[0]), s[1]), s[2]), s[3]);
+}
+
 // element offset of the 8 query values that meet K's k-step `step` in lane group kg: K rows are fetched 16 bytes per
 // lane (8 bf16, or 16 e4m3 codes = two k-steps), so the contraction index is permuted, identically in K and Q
 template <int KVT>
