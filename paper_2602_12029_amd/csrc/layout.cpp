@@ -7,6 +7,8 @@
 #include <algorithm>
 #include <cstdlib>
 #include <cstring>
+#include <map>
+#include <tuple>
 #include <new>
 #include <numeric>
 #include <queue>
@@ -222,6 +224,34 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   std::stable_sort(suffix_items.begin(), suffix_items.end(), by_cost);
   lay->num_rowsplit_items = 0;
   for (const ps_item& it : prefix_items) lay->num_rowsplit_items += (it.kind & kPsItemRowSplit) ? 1 : 0;
+  if (lay->num_rowsplit_items > 8) {
+    // XCD-aware launch order of the prefill kernel.  Workgroup i of a launch runs on XCD i mod 8, and each XCD has
+    // its own L2.  The row groups that read the same K/V range (same segment, token begin and KV head: a family)
+    // are therefore placed eight apart, on one XCD, and next to each other in that XCD's sequence, so that they run
+    // at the same time and the range comes out of HBM once instead of once per row group.  Families go, heaviest
+    // first, to the XCD with the fewest items so far.
+    const int n_rs = lay->num_rowsplit_items;
+    typedef std::tuple<int32_t, int32_t, int32_t> range_key;             // (segment, token begin, KV head)
+    std::map<range_key, size_t> family_of;
+    std::vector<std::vector<ps_item>> family;                             // in order of first (= heaviest) member
+    for (int i = 0; i < n_rs; ++i) {
+      const ps_item& it = prefix_items[size_t(i)];
+      const auto at = family_of.emplace(range_key{it.blk_off, it.tok_begin, it.kv_head}, family.size());
+      if (at.second) family.emplace_back();
+      family[at.first->second].push_back(it);
+    }
+    std::vector<std::vector<ps_item>> column(8);
+    for (const auto& members : family) {
+      size_t target = 0;
+      for (size_t c = 1; c < 8; ++c)
+        if (column[c].size() < column[target].size()) target = c;
+      column[target].insert(column[target].end(), members.begin(), members.end());
+    }
+    int out = 0;
+    for (size_t row = 0; out < n_rs; ++row)
+      for (size_t c = 0; c < 8; ++c)
+        if (row < column[c].size()) prefix_items[size_t(out++)] = column[c][row];
+  }
   lay->num_prefix_items = int32_t(prefix_items.size());
   lay->items = std::move(prefix_items);
   lay->items.insert(lay->items.end(), suffix_items.begin(), suffix_items.end());
