@@ -103,6 +103,8 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   const bool limited = !lay->visible.empty();
   auto visible_of = [&](int32_t r) { return limited ? lay->visible[size_t(r)] : lay->prefix_len[size_t(lay->req_prompt[size_t(r)])]; };
   std::vector<int32_t> nsplit_root(R, 0), nsplit_prefix(R), nsplit_suffix(R);
+  lay->suffix_chunk_size.assign(size_t(R), 0);
+  lay->suffix_chunks.assign(size_t(R), 0);
   std::vector<ps_item> prefix_items, suffix_items;
   const int32_t max_req = std::max(1, 64 / group);
   const int32_t total_prefix_blocks = int32_t(lay->prefix_blk.size());
@@ -118,6 +120,7 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   // a separate launch for a handful of root items would leave most of the chip idle while it runs).  In a
   // partial-prefill batch (visible lengths set) large groups go to the prefill kernel, roots included.
   const int32_t root_blk0 = int32_t(lay->prefix_blk.size() + lay->suffix_blk.size());   // roots close the block array
+  lay->planned_root_blk0 = root_blk0;
   for (int32_t t = 0; t < lay->num_roots; ++t) {
     int32_t n = 0;
     const int64_t size = chunking(lay->root_len[size_t(t)], prefix_chunk, &n);
@@ -195,6 +198,8 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
     int32_t n = 0;
     const int64_t size = chunking(lay->suffix_len[r], suffix_chunk, &n);
     nsplit_suffix[r] = n;
+    lay->suffix_chunk_size[size_t(r)] = int32_t(size);
+    lay->suffix_chunks[size_t(r)] = n;
     for (int32_t c = 0; c < n; ++c)
       for (int32_t h = 0; h < g.num_kv_heads; ++h) {
         ps_item it{};
@@ -267,7 +272,7 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
 
   // Schedules for the persistent MFMA kernel: longest-processing-time-first packing of a set of items
   // onto the resident workgroups (cost = tokens + a fixed per-item charge), each list longest first.
-  struct packed { std::vector<ps_item> items; std::vector<int32_t> indptr; int32_t max_rows = 0, occ = 1; };
+  typedef ps_layout::packed_set packed;
   auto pack = [&](int begin, int end) {
     packed out;
     const int count = end - begin;
@@ -306,12 +311,23 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   };
   const int n_items = int(lay->items.size());
   const bool pre_mfma = lay->prefix_variant == PS_VARIANT_MFMA, suf_mfma = lay->suffix_variant == PS_VARIANT_MFMA;
-  packed pk_prefix, pk_suffix, pk_all;
   const int first_packed = lay->num_rowsplit_items;   // row-split items run in the prefill kernel, one workgroup each
-  if (pre_mfma) pk_prefix = pack(first_packed, lay->num_prefix_items);
-  if (suf_mfma) pk_suffix = pack(lay->num_prefix_items, n_items);
-  if (pre_mfma && suf_mfma) pk_all = pack(first_packed, n_items);
+  lay->pk_prefix = pre_mfma ? pack(first_packed, lay->num_prefix_items) : packed{};
+  lay->pk_suffix = suf_mfma ? pack(lay->num_prefix_items, n_items) : packed{};
+  lay->pk_all = (pre_mfma && suf_mfma) ? pack(first_packed, n_items) : packed{};
+  return ps_blob_build(lay);
+}
 
+// Lays the tables out for the device: everything the kernels read, as one int32 blob.
+int32_t ps_blob_build(ps_layout* lay) {
+  typedef ps_layout::packed_set packed;
+  const ps_geometry& g = lay->geo;
+  const int32_t R = lay->num_requests;
+  const int32_t total_prefix_blocks = int32_t(lay->prefix_blk.size());
+  const int32_t root_blk0 = int32_t(lay->prefix_blk.size() + lay->suffix_blk.size());
+  const packed &pk_prefix = lay->pk_prefix, &pk_suffix = lay->pk_suffix, &pk_all = lay->pk_all;
+  const bool limited = !lay->visible.empty();
+  auto visible_of = [&](int32_t r) { return limited ? lay->visible[size_t(r)] : lay->prefix_len[size_t(lay->req_prompt[size_t(r)])]; };
   // device blob: [block ids: prefix ++ suffix ++ root][request list: group_req ++ identity ++ root groups ++ per-chunk
   // subsets][items]
   // [slot_base][visible][schedules]
@@ -803,7 +819,46 @@ int32_t ps_layout_append(ps_pool* pool, ps_layout* lay, const int32_t* active, c
   }
   lay->suffix_blk.swap(blk);
   lay->suffix_blk_indptr.swap(indptr);
-  if (int32_t st = ps_plan_build(lay, &lay->opt)) return st;
+  // A step that leaves the chunk structure of every private segment as it is (same number of chunks, same chunk
+  // size where there are several) only moves token ends and block offsets: the plan -- items, their order, the
+  // packing onto workgroups -- is kept and patched, and only the tables are laid out again.  Anything else (a first
+  // token, a segment outgrowing its chunks) plans afresh.
+  bool same_structure = lay->suffix_chunks.size() == size_t(R) && lay->suffix_chunk > 0;
+  const int64_t granule = std::lcm<int64_t>(B, 32);
+  for (int32_t r = 0; r < R && same_structure; ++r) {
+    if (!is_active(r)) continue;
+    const int64_t len = lay->suffix_len[size_t(r)];
+    const int64_t count = ceil_div(len, lay->suffix_chunk);
+    const int64_t size = round_up(ceil_div(len, count), granule);
+    const int64_t n = ceil_div(len, size);
+    if (len <= 1 || n != lay->suffix_chunks[size_t(r)] || (n > 1 && size != lay->suffix_chunk_size[size_t(r)]))
+      same_structure = false;
+    else
+      lay->suffix_chunk_size[size_t(r)] = int32_t(size);
+  }
+  if (same_structure) {
+    const int32_t prefix_blocks = int32_t(lay->prefix_blk.size());
+    const int32_t root_shift = int32_t(lay->prefix_blk.size() + lay->suffix_blk.size()) - lay->planned_root_blk0;
+    auto patch = [&](std::vector<ps_item>& items) {
+      for (ps_item& it : items) {
+        if (it.kind & kPsItemSuffix) {
+          const int32_t r = it.req_off - R;   // private-suffix items index the identity part of the request list
+          it.blk_off = prefix_blocks + lay->suffix_blk_indptr[size_t(r)];
+          it.tok_end = std::min(lay->suffix_len[size_t(r)], it.tok_begin + lay->suffix_chunk_size[size_t(r)]);
+        } else if (it.kind & kPsItemRoot) {
+          it.blk_off += root_shift;
+        }
+      }
+    };
+    patch(lay->items);
+    patch(lay->pk_prefix.items);
+    patch(lay->pk_suffix.items);
+    patch(lay->pk_all.items);
+    lay->planned_root_blk0 += root_shift;
+    if (int32_t st = ps_blob_build(lay)) return st;
+  } else {
+    if (int32_t st = ps_plan_build(lay, &lay->opt)) return st;
+  }
   if (dest) *dest = lay->append_dest.data();
   return PS_OK;
 }

@@ -68,6 +68,18 @@ struct ps_layout {
     int32_t num_wg = 0, max_rows = 0, occ = 1;  // occ: workgroups per compute unit the grid was sized for
   };
   schedule sched_prefix, sched_suffix, sched_all;
+  // the schedules' contents as packed by the planner (copied into the blob; kept so that a decode step that changes
+  // no chunk structure can patch token counts and block offsets instead of planning again)
+  struct packed_set {
+    std::vector<ps_item> items;
+    std::vector<int32_t> indptr;
+    int32_t max_rows = 0, occ = 1;
+  };
+  packed_set pk_prefix, pk_suffix, pk_all;
+  // per request: tokens per suffix chunk and number of suffix chunks in the current plan; where the root blocks
+  // started in the concatenated block array when the plan was made
+  std::vector<int32_t> suffix_chunk_size, suffix_chunks;
+  int32_t planned_root_blk0 = 0;
 
   // where the token of the most recent ps_layout_append went: block * B + slot per request, -1 = none
   std::vector<int32_t> append_dest;
@@ -94,4 +106,5 @@ constexpr int kPsMfmaMaxChunk = 4096;  // tokens per MFMA work item (32 tiles pe
 
 // layout.cpp
 int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* opt);
+int32_t ps_blob_build(ps_layout* lay);
 bool ps_mfma_supported(const ps_geometry& g);

@@ -664,3 +664,38 @@ def test_adoption_random_chains_against_oracle():
         ol.release_layout(opool, prev_o)
         assert not B.ps_pool_refcounts(pool, 400).any()
         B.ps_pool_destroy(pool)
+
+
+@pytest.mark.parametrize("tree", [False, True])
+def test_plan_stays_valid_over_many_decode_steps(tree):
+    """Appends mostly patch the plan instead of rebuilding it: after every step the plan must still tile every segment
+    at its current length, and the schedules must hold exactly the plan's items (chunk sizes of 32 / 64 tokens make
+    segments outgrow their chunks all the time, which plans afresh)."""
+    import copy
+    geo = wl.Geometry(32, 8, 128, 16, "bf16", "bf16")
+    rng = np.random.default_rng(79)
+    if tree:
+        w = wl.make_tree_workload("steps", geo, 3, [100], [0, -1, 0], [300, 31, 0], [[0, 1, 2], [1], [0, 2]],
+                                  [5, 0, 129, 64, 17, 33], pool_factor=3.0, seed=1)
+    else:
+        w = wl.make_workload("steps", geo, 3, [333, 48], [[0, 1, 2], [1]], [40, 0, 97, 16], pool_factor=3.0, seed=1)
+    pool, lay, opool, olay = _both(w)
+    cur = copy.copy(w)
+    cur.suffix_len = w.suffix_len.copy()
+    for pc, sc in ((0, 0), (64, 32), (256, 64)):
+        B.ps_layout_replan(lay, B.plan_options(pc, sc))
+        for step in range(40):
+            active = (rng.random(w.num_requests) < 0.7).astype(np.int32)
+            dest = B.ps_layout_append(pool, lay, w.num_requests, active)
+            odest = ol.append_step(opool, olay, active)
+            assert np.array_equal(dest, odest)
+            cur.suffix_len = cur.suffix_len + active
+            t = B.ps_layout_tables(lay, w.num_prompts, w.num_requests)
+            assert np.array_equal(t["suffix_blk"], olay.suffix_blk) and np.array_equal(t["suffix_blk_indptr"], olay.suffix_blk_indptr)
+            plan = B.ps_layout_plan(lay, w.num_requests)
+            _check_plan(cur, lay, plan)
+            sch = B.ps_layout_schedule(lay, 2)
+            key = lambda a: sorted(map(tuple, a.tolist()))
+            assert key(sch["items"]) == key(plan["items"])
+    B.ps_layout_release(pool, lay)
+    B.ps_pool_destroy(pool)
