@@ -128,9 +128,12 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
     for (int32_t i = 0; i < count; ++i) nsplit_root[size_t(lay->root_group_req[size_t(g0 + i)])] = n;
     const bool row_split = limited && prefix_mfma && int64_t(count) * group > 64;
     const int32_t per_item = row_split ? std::max(1, 256 / group) : max_req;
+    // Row groups outside, KV heads inside: items of equal cost reach the workgroups in this order (LPT, lowest
+    // index on ties) and workgroup i runs on XCD i mod 8, so with a multiple of eight KV heads the row groups that
+    // read one (range, head) start together on one XCD and share its L2.
     for (int32_t c = 0; c < n; ++c)
-      for (int32_t h = 0; h < g.num_kv_heads; ++h)
-        for (int32_t m0 = 0; m0 < count; m0 += per_item) {
+      for (int32_t m0 = 0; m0 < count; m0 += per_item)
+        for (int32_t h = 0; h < g.num_kv_heads; ++h) {
           ps_item it{};
           it.blk_off = root_blk0 + lay->root_blk_indptr[size_t(t)];
           it.tok_begin = int32_t(c * size);
@@ -171,8 +174,8 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
       // by rows, so that a K/V tile is fetched once per 256 rows instead of once per 64.
       const bool row_split = limited && prefix_mfma && int64_t(count) * group > 64;
       const int32_t per_item = row_split ? std::max(1, 256 / group) : max_req;
-      for (int32_t h = 0; h < g.num_kv_heads; ++h)
-        for (int32_t m0 = 0; m0 < count; m0 += per_item) {
+      for (int32_t m0 = 0; m0 < count; m0 += per_item)      // row groups outside, heads inside (see the roots)
+        for (int32_t h = 0; h < g.num_kv_heads; ++h) {
           ps_item it{};
           it.blk_off = lay->prefix_blk_indptr[p];
           it.tok_begin = int32_t(c * size);
