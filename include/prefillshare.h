@@ -164,7 +164,9 @@ int32_t ps_layout_plan(const ps_layout* layout, int32_t* num_items, const int32_
  * sees fewer tokens than the item's token end, bit 2 = an item of up to 256 rows (the new tokens of a
  * context in a partial prefill, the requests below a root), which a workgroup of the prefill kernel splits
  * over its waves by rows (such items lead the item array and are not part of the schedules below), bit 3 =
- * a root segment. */
+ * a root segment, bit 4 = further items (other row groups of the same sharing group) read the same K/V
+ * range.  A launch streams its K/V past the caches (non-temporal loads) unless a quarter or more of its
+ * tokens lie in bit-4 items. */
 int32_t ps_layout_request_list(const ps_layout* layout, int32_t* count, const int32_t** list);
 
 /* Schedule of the persistent matrix-core kernel for one launchable set of items (which: 0 = prefix items,

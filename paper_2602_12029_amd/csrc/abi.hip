@@ -63,7 +63,7 @@ int32_t launch_set(const ps_layout* lay, const psdev::AttnParams& p, const void*
     if (set != WorkSet::kSuffix && lay->num_rowsplit_items > 0)
       rc = psdev::launch_prefill_attention(p, lay->geo, p.items, lay->num_rowsplit_items, st);
     if (rc == PS_OK)
-      rc = psdev::launch_mfma_attention(p, lay->geo, s.max_rows, s.occ, set != WorkSet::kSuffix && lay->any_masked,
+      rc = psdev::launch_mfma_attention(p, lay->geo, s.max_rows, s.occ, set != WorkSet::kSuffix && lay->any_masked, s.stream,
                                         reinterpret_cast<const ps_item*>(t + s.off_items), t + s.off_indptr, s.num_wg,
                                         st);
   } else {

@@ -10,7 +10,8 @@ bool wave_supported(const ps_geometry& g);
 int32_t launch_wave_attention(const AttnParams& p, const ps_geometry& g, int item_begin, int n_items, hipStream_t st);
 // Persistent launch: workgroup w walks wg_items[wg_indptr[w] .. wg_indptr[w+1]).
 // `masked`: the set holds items whose rows see different token counts (per-request visible prefix lengths).
-int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max_rows, int occ, bool masked,
+// `stream`: K/V tile loads are non-temporal (the set's K/V is read by one item each, or nearly so).
+int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max_rows, int occ, bool masked, bool stream,
                               const ps_item* wg_items, const int32_t* wg_indptr, int num_wg, hipStream_t st);
 // Partial prefill: one workgroup per row-split item (up to 256 query rows, split over the waves by rows).
 int32_t launch_prefill_attention(const AttnParams& p, const ps_geometry& g, const ps_item* items, int num_items,

@@ -83,7 +83,7 @@ struct RowLimit { int lim[NT]; };  // per row tile: first token that row (lane %
 // NT: 16-row tiles carried; NB: tile buffers in the register ring; OCC: waves per SIMD the register
 // budget is sized for; MASKED: rows may see only a leading part of an item's token range (per-request visible
 // prefix length), which costs a compare per score and guards against rows that have seen nothing yet.
-template <int NT, int KVT, int NB, int OCC, bool MASKED>
+template <int NT, int KVT, int NB, int OCC, bool MASKED, bool STREAM>
 __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, const ps_item* __restrict__ wg_items,
                                                                   const int32_t* __restrict__ wg_indptr) {
   __shared__ float sm_o[kWaves][16][kLdsRow];
@@ -205,6 +205,10 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
 
   // ---- tile loads: buffer loads, block base in SGPRs, two loop-invariant VGPR offsets ---------------------
   // `live` false (or a 16-token block past the segment end) gives a zero-sized descriptor: zeros, no traffic.
+  // STREAM: the K/V of this launch is (almost all) read by one item only, so the loads are non-temporal -- the
+  // lines do not displace what the caches hold and are not kept for a reader that never comes.  The policy is an
+  // immediate of the load and a branch around loads would spoil the wait counts, hence one choice per launch.
+  constexpr int kPolicy = STREAM ? kNonTemporal : 0;
   auto load_item_tile = [&](TileRegs<KVT>& tr, const ItemCtx& c, const ItemMeta& m, int k, bool live) {
     const int sub_a = c.sub0 + 2 * (wave + kWaves * k);
     const int idx = (2 * k) & 63;
@@ -219,16 +223,16 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
           __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(addr), 0, valid ? 0x7fffffff : 0, 0x00020000);
       if constexpr (KVT == PS_BF16) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) tr.k[b][s] = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off + 64 * s, 0, 0);
+        for (int s = 0; s < 4; ++s) tr.k[b][s] = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off + 64 * s, 0, kPolicy);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-          tr.v[4 * b + i] = __builtin_amdgcn_raw_buffer_load_b128(rs, v_lane_off, kv_bytes + i * tok_bytes, 0);
+          tr.v[4 * b + i] = __builtin_amdgcn_raw_buffer_load_b128(rs, v_lane_off, kv_bytes + i * tok_bytes, kPolicy);
       } else {
 #pragma unroll
-        for (int s = 0; s < 2; ++s) tr.k[b][s] = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off + 64 * s, 0, 0);
+        for (int s = 0; s < 2; ++s) tr.k[b][s] = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off + 64 * s, 0, kPolicy);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-          tr.v[4 * b + i] = __builtin_amdgcn_raw_buffer_load_b64(rs, v_lane_off, kv_bytes + i * tok_bytes, 0);
+          tr.v[4 * b + i] = __builtin_amdgcn_raw_buffer_load_b64(rs, v_lane_off, kv_bytes + i * tok_bytes, kPolicy);
       }
     }
   };
@@ -520,7 +524,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
   }
 }
 
-int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max_rows, int occ, bool masked,
+int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max_rows, int occ, bool masked, bool stream,
                               const ps_item* wg_items, const int32_t* wg_indptr, int num_wg, hipStream_t st) {
   if (num_wg <= 0) return PS_OK;
   const int spb = g.block_size / 16;
@@ -529,12 +533,17 @@ int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max
   if (g.kv_dtype != PS_BF16 && g.kv_dtype != PS_FP8_E4M3) return PS_ERR_UNSUPPORTED;
   const dim3 grid(num_wg), block(256);
   const int nt = max_rows <= 16 ? 1 : (max_rows <= 32 ? 2 : 4);
-#define PS_LAUNCH(NT, KVT, NB, OCC)                                                                                  \
-  do {                                                                                                               \
-    if (masked)                                                                                                      \
-      hipLaunchKernelGGL((mfma_attention_kernel<NT, KVT, NB, OCC, true>), grid, block, 0, st, p, wg_items, wg_indptr); \
-    else                                                                                                             \
-      hipLaunchKernelGGL((mfma_attention_kernel<NT, KVT, NB, OCC, false>), grid, block, 0, st, p, wg_items, wg_indptr); \
+#define PS_LAUNCH_AS(NT, KVT, NB, OCC, MASKED, STREAM) \
+  hipLaunchKernelGGL((mfma_attention_kernel<NT, KVT, NB, OCC, MASKED, STREAM>), grid, block, 0, st, p, wg_items, wg_indptr)
+#define PS_LAUNCH(NT, KVT, NB, OCC)                                \
+  do {                                                             \
+    if (masked) {                                                  \
+      if (stream) PS_LAUNCH_AS(NT, KVT, NB, OCC, true, true);      \
+      else PS_LAUNCH_AS(NT, KVT, NB, OCC, true, false);            \
+    } else {                                                       \
+      if (stream) PS_LAUNCH_AS(NT, KVT, NB, OCC, false, true);     \
+      else PS_LAUNCH_AS(NT, KVT, NB, OCC, false, false);           \
+    }                                                              \
   } while (0)
   // two tile buffers per wave everywhere (deeper rings measured no faster); `occ` is the residency the
   // plan sized the grid for (ps_mfma_occupancy)
@@ -548,6 +557,7 @@ int32_t launch_mfma_attention(const AttnParams& p, const ps_geometry& g, int max
     else PS_LAUNCH(4, PS_FP8_E4M3, 2, 1);
   }
 #undef PS_LAUNCH
+#undef PS_LAUNCH_AS
   return PS_OK;
 }
 

@@ -11,6 +11,8 @@ constexpr int kTileTokens = 32;   // tokens per tile: two 16-token blocks
 // log2 units a score may run ahead of a row's softmax reference before the reference moves and the accumulators
 // are rescaled (probabilities then stay below 2^kLazyRescale instead of below 1)
 constexpr float kLazyRescale = 8.f;
+// cache-policy operand of a buffer load: bit 1 = nt, the line is not expected to be read again
+constexpr int kNonTemporal = 2;
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;

@@ -26,7 +26,8 @@ struct ps_item {
 };
 // bit 2: up to 256 rows, split over the four waves of a workgroup by rows instead of by tokens (partial prefill)
 // bit 3: a root segment (a context several prompts begin with), read by every request below the root
-constexpr int32_t kPsItemSuffix = 1, kPsItemMasked = 2, kPsItemRowSplit = 4, kPsItemRoot = 8;
+// bit 4: other items (further row groups of the same sharing group) read the same K/V range: keep it cacheable
+constexpr int32_t kPsItemSuffix = 1, kPsItemMasked = 2, kPsItemRowSplit = 4, kPsItemRoot = 8, kPsItemReread = 16;
 static_assert(sizeof(ps_item) == 32, "ps_item is 8 int32");
 
 struct ps_layout {
@@ -66,6 +67,7 @@ struct ps_layout {
   struct schedule {
     int64_t off_items = 0, off_indptr = 0;  // blob offsets in words
     int32_t num_wg = 0, max_rows = 0, occ = 1;  // occ: workgroups per compute unit the grid was sized for
+    bool stream = true;   // K/V loads of the launch are non-temporal (little of the set's K/V is read by several items)
   };
   schedule sched_prefix, sched_suffix, sched_all;
   // the schedules' contents as packed by the planner (copied into the blob; kept so that a decode step that changes
@@ -74,6 +76,7 @@ struct ps_layout {
     std::vector<ps_item> items;
     std::vector<int32_t> indptr;
     int32_t max_rows = 0, occ = 1;
+    bool stream = true;
   };
   packed_set pk_prefix, pk_suffix, pk_all;
   // per request: tokens per suffix chunk and number of suffix chunks in the current plan; where the root blocks

@@ -109,8 +109,12 @@ def _check_plan(w, lay, plan, visible=None):
     root_of = [int(w.prompt_root[w.req_prompt[r]]) if w.num_roots else -1 for r in range(R)]
     seen = np.asarray(w.prefix_len)[np.asarray(w.req_prompt)] if visible is None else np.asarray(visible)
     cover = {}                                             # (request, kv head) -> list of (kind, begin, end, slot)
+    readers = {}                                           # (segment, token begin, kv head) -> items reading that range
     for blk_off, t0, t1, req_off, n_req, head, split, kind in items.tolist():
-        assert t1 > t0 >= 0 and n_req >= 1 and 0 <= head < g.num_kv_heads and 0 <= kind <= 15
+        readers[(blk_off, t0, head)] = readers.get((blk_off, t0, head), 0) + 1
+    for blk_off, t0, t1, req_off, n_req, head, split, kind in items.tolist():
+        assert t1 > t0 >= 0 and n_req >= 1 and 0 <= head < g.num_kv_heads and 0 <= kind <= 31
+        assert bool(kind & 16) == (readers[(blk_off, t0, head)] > 1)       # bit 4: several row groups read the range
         assert n_req * g.group <= (256 if kind & 4 else 64) or n_req == 1     # rows one item may carry
         assert t0 % g.block_size == 0
         reqs = req_list[req_off:req_off + n_req].tolist()
@@ -301,7 +305,8 @@ def test_many_models_split_into_row_chunks():
     pool, lay, _, _ = _both(w)
     plan = B.ps_layout_plan(lay, w.num_requests)
     _check_plan(w, lay, plan)
-    prefix = plan["items"][plan["items"][:, 7] == 0]
+    prefix = plan["items"][plan["items"][:, 7] & 1 == 0]
+    assert (prefix[:, 7] == 16).all()                         # three row groups read every range
     assert sorted(prefix[prefix[:, 5] == 0][:, 4].tolist()) == [2, 4, 4]
     B.ps_layout_release(pool, lay)
     B.ps_pool_destroy(pool)
@@ -503,7 +508,7 @@ def test_root_groups_stay_in_the_persistent_launch_unless_the_batch_is_a_prefill
     _check_plan(w, lay, plan)
     items = plan["items"]
     roots = items[items[:, 7] & 8 != 0]
-    assert len(roots) and (roots[:, 7] == 8).all() and roots[:, 4].max() == 16      # 128 requests x 4 heads: 8 x 64 rows
+    assert len(roots) and (roots[:, 7] == 8 | 16).all() and roots[:, 4].max() == 16   # 128 requests x 4 heads: 8 x 64 rows
     sch = B.ps_layout_schedule(lay, 2)
     assert len(sch["items"]) == len(items)                                          # one launch holds everything
     # with visible lengths set (a partial-prefill batch) groups of more than 64 rows go to the prefill kernel
@@ -513,7 +518,7 @@ def test_root_groups_stay_in_the_persistent_launch_unless_the_batch_is_a_prefill
     _check_plan(w, lay, plan, visible)
     items = plan["items"]
     roots = items[items[:, 7] & 8 != 0]
-    assert (roots[:, 7] == 12).all() and roots[:, 4].max() == 64 and (items[:len(roots), 7] & 4).all()
+    assert (roots[:, 7] == 12 | 16).all() and roots[:, 4].max() == 64 and (items[:len(roots), 7] & 4).all()
     sch = B.ps_layout_schedule(lay, 2)
     assert not (sch["items"][:, 7] & 4).any() and len(sch["items"]) == len(items) - len(roots)
     B.ps_layout_release(pool, lay)
