@@ -20,6 +20,13 @@ namespace {
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
+// Bulk K/V passes through these kernels once and is far larger than the caches: loads and stores are non-temporal,
+// so the lines neither displace what the caches hold nor wait there for a reader that never comes.
+template <typename V>
+__device__ __forceinline__ V stream_load(const V* p) { return __builtin_nontemporal_load(p); }
+template <typename V>
+__device__ __forceinline__ void stream_store(V* p, V v) { __builtin_nontemporal_store(v, p); }
+
 // e4m3fn code -> float32 (exact)
 __device__ __forceinline__ float e4m3_to_f32(uint32_t code) {
   const uint32_t e = (code >> 3) & 0xf, m = code & 7;
@@ -69,8 +76,8 @@ __global__ __launch_bounds__(256) void ingest_copy_kernel(KvWriteParams p, const
   const int cpt = p.head_dim / kVec;   // 16-byte chunks per token
   for (int c = lane; c < n_valid * cpt; c += 64) {
     const int t = c / cpt, col = (c % cpt) * kVec;
-    *reinterpret_cast<u32x4*>(dst + int64_t(t) * p.s_tok + col) =
-        *reinterpret_cast<const u32x4*>(src + int64_t(t) * src_s_tok + col);
+    stream_store(reinterpret_cast<u32x4*>(dst + int64_t(t) * p.s_tok + col),
+                 stream_load(reinterpret_cast<const u32x4*>(src + int64_t(t) * src_s_tok + col)));
   }
 }
 
@@ -101,7 +108,7 @@ __global__ __launch_bounds__(256) void ingest_e4m3_kernel(KvWriteParams p, const
 #pragma unroll
   for (int i = 0; i < CH; ++i) {
     const int c = min(lane + 64 * i, total - 1);
-    raw[i] = *reinterpret_cast<const u32x4*>(src + int64_t(token_of(c)) * src_s_tok + column_of(c));
+    raw[i] = stream_load(reinterpret_cast<const u32x4*>(src + int64_t(token_of(c)) * src_s_tok + column_of(c)));
   }
   float amax = 0.f;
 #pragma unroll
@@ -162,7 +169,7 @@ __global__ __launch_bounds__(256) void ingest_e4m3_kernel(KvWriteParams p, const
       u32x2 out;
       out[0] = uint32_t(__builtin_amdgcn_cvt_pk_fp8_f32(q[2], q[3], __builtin_amdgcn_cvt_pk_fp8_f32(q[0], q[1], 0, false), true));
       out[1] = uint32_t(__builtin_amdgcn_cvt_pk_fp8_f32(q[6], q[7], __builtin_amdgcn_cvt_pk_fp8_f32(q[4], q[5], 0, false), true));
-      *reinterpret_cast<u32x2*>(dst + int64_t(token_of(c)) * p.s_tok + column_of(c)) = out;
+      stream_store(reinterpret_cast<u32x2*>(dst + int64_t(token_of(c)) * p.s_tok + column_of(c)), out);
     }
   }
 }
@@ -245,14 +252,14 @@ __global__ __launch_bounds__(256) void stage_copy_kernel(KvWriteParams p, uint8_
   uint8_t* image_tile = image + tile * int64_t(p.block_size) * row_bytes;
   const int64_t tok_bytes = p.s_tok * elem_bytes;
   for (int c0 = 0; c0 < chunks; c0 += 256) {
-    uint4 v[4];
+    u32x4 v[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int c = c0 + 64 * u + lane;
       if (c < chunks) {
         const int slot = c / row_chunks, col = c % row_chunks;
         const uint8_t* src = TO_IMAGE ? pool_tile + slot * tok_bytes + 16 * col : image_tile + 16 * int64_t(c);
-        v[u] = *reinterpret_cast<const uint4*>(src);
+        v[u] = stream_load(reinterpret_cast<const u32x4*>(src));
       }
     }
 #pragma unroll
@@ -261,7 +268,7 @@ __global__ __launch_bounds__(256) void stage_copy_kernel(KvWriteParams p, uint8_
       if (c < chunks) {
         const int slot = c / row_chunks, col = c % row_chunks;
         uint8_t* dst = TO_IMAGE ? image_tile + 16 * int64_t(c) : pool_tile + slot * tok_bytes + 16 * col;
-        *reinterpret_cast<uint4*>(dst) = v[u];
+        stream_store(reinterpret_cast<u32x4*>(dst), v[u]);
       }
     }
   }
