@@ -315,6 +315,11 @@ def main_stage(args):
         k_ms = float(np.mean([ev.elapsed_ms(i) for i in range(0, args.steps, every)]))
         roofline.update(achieved=2 * image_bytes / (k_ms * 1e-3) / 1e9, kernel_ms=k_ms, algorithmic_bytes=2 * image_bytes)
         roofline["frac"] = roofline["achieved"] / PEAK_HBM_GBS
+    summary = os.path.join(ROOT, "profiles", f"stage_kernel_{args.workload}.md")
+    if not host and os.path.exists(summary):
+        for text in open(summary):
+            if text.startswith("traffic_bytes_per_launch:"):
+                roofline["traffic"] = float(text.split(":")[1])
     value = moved / (ms_per_step * 1e-3) / 1e9
     line = {
         "metric": "staging of a batch's KV blocks to an image and back: bytes read + written, GB/s",
