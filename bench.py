@@ -81,6 +81,20 @@ class HipEvents:
 
 
 def cpu_baseline(w, lay_tables, data, seconds):
+    """The oracle on the host: with the threads its BLAS takes by itself, and (a shorter sample) on one thread."""
+    line = _cpu_baseline_leg(w, data, seconds)
+    try:
+        from threadpoolctl import threadpool_limits
+        with threadpool_limits(limits=1):
+            one = _cpu_baseline_leg(w, data, seconds / 3)
+        line["single_thread"] = {"value": one["value"], "unit": "GB/s", "queries_per_s": one["queries_per_s"],
+                                 "sample": one["sample"]}
+    except ImportError:
+        pass
+    return line
+
+
+def _cpu_baseline_leg(w, data, seconds):
     """Time the oracle on whole prompts (all their requests) until about `seconds` have passed."""
     from oracle import attention as oa
     from oracle import layout as ol
