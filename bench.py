@@ -47,6 +47,8 @@ def parse():
     ap.add_argument("--suffix-chunk", type=int, default=0)
     ap.add_argument("--prefix-variant", default="auto")
     ap.add_argument("--suffix-variant", default="auto")
+    ap.add_argument("--kv-policy", default="auto", choices=["auto", "stream", "cacheable"],
+                    help="K/V loads of the matrix-core decode kernel: non-temporal, ordinary, or chosen per launch")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target wall time of the oracle sample; 0 = skip")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events in the timed loop")
     ap.add_argument("--event-every", type=int, default=4,
@@ -417,8 +419,9 @@ def main_prefill(args):
     scales = None if data.scales is None else torch.from_numpy(data.scales).to(dev)
     batch = DecodeBatch(layout, geo, w.num_requests, q, kv0, scales)
     t_lay0 = time.perf_counter()
+    policy = {"auto": B.PS_KV_POLICY_AUTO, "stream": B.PS_KV_POLICY_STREAM, "cacheable": B.PS_KV_POLICY_CACHEABLE}
     B.ps_layout_replan(layout, B.plan_options(args.prefix_chunk, args.suffix_chunk, variant[args.prefix_variant],
-                                              variant[args.suffix_variant]))
+                                              variant[args.suffix_variant], 0, policy[args.kv_policy]))
     batch.set_visible(visible)
     t_plan_ms = (time.perf_counter() - t_lay0) * 1e3
     plan = B.ps_layout_plan(layout, w.num_requests)
@@ -513,8 +516,9 @@ def main():
                                      w.suffix_len)
     else:
         layout = B.ps_kv_layout(pool, geo, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
+    policy = {"auto": B.PS_KV_POLICY_AUTO, "stream": B.PS_KV_POLICY_STREAM, "cacheable": B.PS_KV_POLICY_CACHEABLE}
     B.ps_layout_replan(layout, B.plan_options(args.prefix_chunk, args.suffix_chunk, variant[args.prefix_variant],
-                                              variant[args.suffix_variant]))
+                                              variant[args.suffix_variant], 0, policy[args.kv_policy]))
     t_layout_ms = (time.perf_counter() - t_lay0) * 1e3
     tables = B.ps_layout_tables(layout, w.num_prompts, w.num_requests)
     roots = B.ps_layout_root_tables(layout)

@@ -68,7 +68,14 @@ typedef struct ps_plan_options {
   int32_t prefix_variant;      /* PS_VARIANT_*                                                    */
   int32_t suffix_variant;      /* PS_VARIANT_*                                                    */
   int32_t num_cus;             /* compute units to plan for; 0 = 256                              */
+  int32_t kv_cache_policy;     /* PS_KV_POLICY_*: how the matrix-core decode kernel loads K/V     */
 } ps_plan_options;
+
+/* K/V loads of the matrix-core decode kernel.  STREAM: non-temporal (the bytes are wanted once: they
+ * do not displace what the caches hold); CACHEABLE: ordinary loads (several row groups of a sharing
+ * group read the same range and should meet in L2); AUTO: per launch, STREAM unless a quarter or more
+ * of the launch's tokens lie in ranges that several items read.  The results are the same bits. */
+enum { PS_KV_POLICY_AUTO = 0, PS_KV_POLICY_STREAM = 1, PS_KV_POLICY_CACHEABLE = 2 };
 
 /* ---- block pool (pool of cached KV blocks, Background "Prefix Caching") -------------------------
  * ps_pool_create: num_blocks >= 0; free_order = host permutation of [0, num_blocks) giving the
@@ -165,8 +172,7 @@ int32_t ps_layout_plan(const ps_layout* layout, int32_t* num_items, const int32_
  * context in a partial prefill, the requests below a root), which a workgroup of the prefill kernel splits
  * over its waves by rows (such items lead the item array and are not part of the schedules below), bit 3 =
  * a root segment, bit 4 = further items (other row groups of the same sharing group) read the same K/V
- * range.  A launch streams its K/V past the caches (non-temporal loads) unless a quarter or more of its
- * tokens lie in bit-4 items. */
+ * range (see PS_KV_POLICY_AUTO). */
 int32_t ps_layout_request_list(const ps_layout* layout, int32_t* count, const int32_t** list);
 
 /* Schedule of the persistent matrix-core kernel for one launchable set of items (which: 0 = prefix items,

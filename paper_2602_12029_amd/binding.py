@@ -15,6 +15,7 @@ import numpy as np
 PS_OK, PS_ERR_INVALID_ARG, PS_ERR_SHAPE, PS_ERR_OOM, PS_ERR_REFCOUNT, PS_ERR_UNSUPPORTED, PS_ERR_DEVICE = range(7)
 PS_F32, PS_BF16, PS_FP8_E4M3 = 0, 1, 2
 PS_VARIANT_AUTO, PS_VARIANT_WAVE, PS_VARIANT_MFMA = 0, 1, 2
+PS_KV_POLICY_AUTO, PS_KV_POLICY_STREAM, PS_KV_POLICY_CACHEABLE = 0, 1, 2
 DTYPE_CODE = {"f32": PS_F32, "bf16": PS_BF16, "fp8_e4m3": PS_FP8_E4M3}
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libprefillshare.so")
@@ -50,7 +51,8 @@ class ps_geometry(C.Structure):
 
 class ps_plan_options(C.Structure):
     _fields_ = [("prefix_chunk_tokens", C.c_int32), ("suffix_chunk_tokens", C.c_int32),
-                ("prefix_variant", C.c_int32), ("suffix_variant", C.c_int32), ("num_cus", C.c_int32)]
+                ("prefix_variant", C.c_int32), ("suffix_variant", C.c_int32), ("num_cus", C.c_int32),
+                ("kv_cache_policy", C.c_int32)]
 
 
 _LIB = None
@@ -104,8 +106,10 @@ def geometry(num_q_heads, num_kv_heads, head_dim, block_size, q_dtype, kv_dtype,
                        DTYPE_CODE.get(q_dtype, q_dtype), DTYPE_CODE.get(kv_dtype, kv_dtype), *strides)
 
 
-def plan_options(prefix_chunk_tokens=0, suffix_chunk_tokens=0, prefix_variant=0, suffix_variant=0, num_cus=0):
-    return ps_plan_options(prefix_chunk_tokens, suffix_chunk_tokens, prefix_variant, suffix_variant, num_cus)
+def plan_options(prefix_chunk_tokens=0, suffix_chunk_tokens=0, prefix_variant=0, suffix_variant=0, num_cus=0,
+                 kv_cache_policy=0):
+    return ps_plan_options(prefix_chunk_tokens, suffix_chunk_tokens, prefix_variant, suffix_variant, num_cus,
+                           kv_cache_policy)
 
 
 # ---- pool ------------------------------------------------------------------------------------------

@@ -52,6 +52,7 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   if (opt.prefix_chunk_tokens < 0 || opt.suffix_chunk_tokens < 0 || opt.num_cus < 0) return PS_ERR_INVALID_ARG;
   auto bad_variant = [](int32_t v) { return v != PS_VARIANT_AUTO && v != PS_VARIANT_WAVE && v != PS_VARIANT_MFMA; };
   if (bad_variant(opt.prefix_variant) || bad_variant(opt.suffix_variant)) return PS_ERR_INVALID_ARG;
+  if (opt.kv_cache_policy < PS_KV_POLICY_AUTO || opt.kv_cache_policy > PS_KV_POLICY_CACHEABLE) return PS_ERR_INVALID_ARG;
   const ps_geometry& g = lay->geo;
   const bool mfma_ok = ps_mfma_supported(g);
   if ((opt.prefix_variant == PS_VARIANT_MFMA || opt.suffix_variant == PS_VARIANT_MFMA) && !mfma_ok)
@@ -293,7 +294,8 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
       tokens_all += it.tok_end - it.tok_begin;
       if (it.kind & kPsItemReread) tokens_reread += it.tok_end - it.tok_begin;
     }
-    out.stream = 4 * tokens_reread < tokens_all;
+    out.stream = opt.kv_cache_policy == PS_KV_POLICY_AUTO ? 4 * tokens_reread < tokens_all
+                                                           : opt.kv_cache_policy == PS_KV_POLICY_STREAM;
     const int num_wg = std::max(1, std::min(count, num_cus * out.occ));
     std::vector<int> order(size_t(count), 0);
     std::iota(order.begin(), order.end(), begin);

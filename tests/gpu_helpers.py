@@ -68,9 +68,10 @@ class GpuCase:
         scales = None if self.data.scales is None else torch.from_numpy(self.data.scales).to(device)
         self.batch = DecodeBatch(self.layout, self.geo, w.num_requests, q, kv, scales)
 
-    def replan(self, prefix_chunk=0, suffix_chunk=0, prefix_variant="auto", suffix_variant="auto", num_cus=0):
+    def replan(self, prefix_chunk=0, suffix_chunk=0, prefix_variant="auto", suffix_variant="auto", num_cus=0,
+               kv_cache_policy=0):
         self.batch.replan(B.plan_options(prefix_chunk, suffix_chunk, VARIANT[prefix_variant], VARIANT[suffix_variant],
-                                         num_cus))
+                                         num_cus, kv_cache_policy))
 
     def set_visible(self, visible=None):
         self.batch.set_visible(visible)

@@ -72,6 +72,28 @@ def test_separate_passes_and_partial_states(gpu):
     case.close()
 
 
+@pytest.mark.parametrize("name", ["ragged_bf16", "many_models", "ragged_fp8"])
+def test_kv_cache_policies_give_the_same_bits(gpu, name):
+    """Streamed (non-temporal) and cacheable K/V loads are the same arithmetic: outputs agree bit for bit, and with
+    the oracle; the automatic choice is one of the two."""
+    from paper_2602_12029_amd import binding as B
+    spec = next(s for s in RAGGED if s[0] == name)
+    _, geo, models, prefix, membership, suffix = spec
+    w = wl.make_workload(name, geo, models, prefix, membership, suffix, pool_factor=1.5, seed=23)
+    case = gpu(w)
+    outs = {}
+    for policy in (B.PS_KV_POLICY_STREAM, B.PS_KV_POLICY_CACHEABLE, B.PS_KV_POLICY_AUTO):
+        case.replan(prefix_variant="mfma", suffix_variant="mfma", kv_cache_policy=policy)
+        case.poison_workspace()
+        case.batch.decode_attention()
+        _check(case, label=f"{name} policy {policy}")
+        outs[policy] = (case.batch.out.clone(), case.batch.lse.clone())
+    for policy in (B.PS_KV_POLICY_CACHEABLE, B.PS_KV_POLICY_AUTO):
+        assert torch.equal(outs[policy][0].view(torch.int16), outs[B.PS_KV_POLICY_STREAM][0].view(torch.int16))
+        assert torch.equal(outs[policy][1].view(torch.int32), outs[B.PS_KV_POLICY_STREAM][1].view(torch.int32))
+    case.close()
+
+
 def test_merge_states_alone_on_caller_built_workspace(gpu):
     w = wl.named_workload("tiny", seed=3)
     case = gpu(w)

@@ -340,6 +340,12 @@ def test_error_paths():
     assert not B.ps_pool_refcounts(other, 3).any()
     # forcing the MFMA variant on fp32 inputs is refused
     assert status(B.ps_layout_replan, lay, B.plan_options(prefix_variant=B.PS_VARIANT_MFMA)) == B.PS_ERR_UNSUPPORTED
+    # an unknown K/V cache policy is refused; the known ones are accepted and change no table
+    assert status(B.ps_layout_replan, lay, B.plan_options(kv_cache_policy=3)) == B.PS_ERR_INVALID_ARG
+    before = B.ps_layout_plan(lay, 1)["items"].copy()
+    for policy in (B.PS_KV_POLICY_STREAM, B.PS_KV_POLICY_CACHEABLE, B.PS_KV_POLICY_AUTO):
+        B.ps_layout_replan(lay, B.plan_options(kv_cache_policy=policy))
+        assert np.array_equal(B.ps_layout_plan(lay, 1)["items"], before)
     B.ps_layout_release(pool, lay)
     assert B.ps_pool_num_free(pool) == 3
     B.ps_pool_destroy(other)
