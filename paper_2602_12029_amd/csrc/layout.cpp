@@ -378,14 +378,18 @@ int32_t ps_blob_build(ps_layout* lay) {
   lay->off_ent_valid = pad4(lay->off_ent_tok0 + num_blk_entries);
   lay->off_dest = pad4(lay->off_ent_valid + num_blk_entries);
   words = pad4(lay->off_dest + R);
-  lay->blob.assign(size_t(std::max<int64_t>(words, 4)), 0);
+  // (the tables grow by a few words per decode step: room to spare keeps the buffer -- and its mapped pages -- in
+  // place instead of taking a fresh allocation every step)
+  const size_t blob_words = size_t(std::max<int64_t>(words, 4));
+  if (lay->blob.capacity() < blob_words) lay->blob.reserve(blob_words + blob_words / 4 + 1024);
+  lay->blob.assign(blob_words, 0);
   int32_t* b = lay->blob.data();
   {
     const int32_t B = g.block_size;
     // skip: per segment, leading blocks that are not to be written (adopted from another layout); the ragged source
     // then holds only the tokens after them
-    auto fill_entries = [&](const std::vector<int32_t>& indptr, const std::vector<int32_t>& len, int32_t entry0,
-                            const std::vector<int32_t>* skip) {
+    auto fill_entries = [&](const std::vector<int32_t>& indptr, const std::vector<int32_t>& len, int32_t* tok0_out,
+                            int32_t* valid_out, const std::vector<int32_t>* skip) {
       int64_t tok = 0;
       for (size_t s = 0; s + 1 < indptr.size(); ++s) {
         const int64_t skipped = skip ? int64_t((*skip)[s + 1] - (*skip)[s]) * B : 0;
@@ -393,16 +397,35 @@ int32_t ps_blob_build(ps_layout* lay) {
           const int64_t first = int64_t(i - indptr[s]) * B;
           if (tok + first > INT32_MAX) return false;
           const bool kept = first < skipped;
-          b[lay->off_ent_tok0 + entry0 + i] = kept ? 0 : int32_t(tok + first - skipped);
-          b[lay->off_ent_valid + entry0 + i] = kept ? 0 : int32_t(std::min<int64_t>(B, len[s] - first));
+          tok0_out[i] = kept ? 0 : int32_t(tok + first - skipped);
+          valid_out[i] = kept ? 0 : int32_t(std::min<int64_t>(B, len[s] - first));
         }
         tok += len[s] - skipped;
       }
       return true;
     };
-    if (!fill_entries(lay->prefix_blk_indptr, lay->prefix_len, 0, lay->adopt_indptr.empty() ? nullptr : &lay->adopt_indptr) ||
-        !fill_entries(lay->suffix_blk_indptr, lay->suffix_len, total_prefix_blocks, nullptr) ||
-        (lay->num_roots && !fill_entries(lay->root_blk_indptr, lay->root_len, root_blk0, nullptr)))
+    // The shared segments (prefixes, roots) never change after the layout is made, so their part of the directory is
+    // worked out once and copied from then on; the private part follows the appends.
+    const size_t n_fixed = lay->prefix_blk.size() + lay->root_blk.size();
+    if (lay->ent_fixed_tok0.size() != n_fixed) {
+      lay->ent_fixed_tok0.assign(n_fixed, 0);
+      lay->ent_fixed_valid.assign(n_fixed, 0);
+      int32_t* root_tok0 = lay->ent_fixed_tok0.data() + lay->prefix_blk.size();
+      int32_t* root_valid = lay->ent_fixed_valid.data() + lay->prefix_blk.size();
+      if (!fill_entries(lay->prefix_blk_indptr, lay->prefix_len, lay->ent_fixed_tok0.data(), lay->ent_fixed_valid.data(),
+                        lay->adopt_indptr.empty() ? nullptr : &lay->adopt_indptr) ||
+          (lay->num_roots && !fill_entries(lay->root_blk_indptr, lay->root_len, root_tok0, root_valid, nullptr))) {
+        lay->ent_fixed_tok0.clear();
+        lay->ent_fixed_valid.clear();
+        return PS_ERR_INVALID_ARG;
+      }
+    }
+    std::copy(lay->ent_fixed_tok0.begin(), lay->ent_fixed_tok0.begin() + total_prefix_blocks, b + lay->off_ent_tok0);
+    std::copy(lay->ent_fixed_valid.begin(), lay->ent_fixed_valid.begin() + total_prefix_blocks, b + lay->off_ent_valid);
+    std::copy(lay->ent_fixed_tok0.begin() + total_prefix_blocks, lay->ent_fixed_tok0.end(), b + lay->off_ent_tok0 + root_blk0);
+    std::copy(lay->ent_fixed_valid.begin() + total_prefix_blocks, lay->ent_fixed_valid.end(), b + lay->off_ent_valid + root_blk0);
+    if (!fill_entries(lay->suffix_blk_indptr, lay->suffix_len, b + lay->off_ent_tok0 + total_prefix_blocks,
+                      b + lay->off_ent_valid + total_prefix_blocks, nullptr))
       return PS_ERR_INVALID_ARG;
     lay->append_dest.resize(size_t(R), -1);
     std::copy(lay->append_dest.begin(), lay->append_dest.end(), b + lay->off_dest);
@@ -746,6 +769,8 @@ int32_t ps_layout_park(ps_pool* pool, ps_layout* lay) {
   if (int32_t st = drop_references(pool, lay)) return st;
   lay->parked = true;
   lay->adopt_indptr.clear();   // a resumed layout holds fresh blocks only: its image carries the adopted contents
+  lay->ent_fixed_tok0.clear();   // ... so the directory of the shared segments is worked out again
+  lay->ent_fixed_valid.clear();
   lay->adopt_blk.clear();
   std::fill(lay->root_blk.begin(), lay->root_blk.end(), -1);
   std::fill(lay->prefix_blk.begin(), lay->prefix_blk.end(), -1);

@@ -83,6 +83,8 @@ struct ps_layout {
   // started in the concatenated block array when the plan was made
   std::vector<int32_t> suffix_chunk_size, suffix_chunks;
   int32_t planned_root_blk0 = 0;
+  // directory entries (first source token, valid tokens) of the shared segments' blocks: prefixes, then roots
+  std::vector<int32_t> ent_fixed_tok0, ent_fixed_valid;
 
   // where the token of the most recent ps_layout_append went: block * B + slot per request, -1 = none
   std::vector<int32_t> append_dest;
