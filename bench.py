@@ -34,12 +34,14 @@ def parse():
     ap.add_argument("--stage-image", default="device", choices=["device", "host"],
                     help="--path stage: where the staging image lives (device memory: the kernels' own rate; pinned "
                          "host memory: the rate across PCIe)")
-    ap.add_argument("--path", default="decode", choices=["decode", "ingest", "prefill", "stage"],
+    ap.add_argument("--path", default="decode", choices=["decode", "ingest", "prefill", "stage", "loop"],
                     help="decode: the attention step (the headline metric); ingest: hand-off of the batch's KV into "
                          "the paged pool (ps_kv_ingest over every prefix and suffix), a step = one whole hand-off; "
                          "prefill: attention of newly appended context tokens against the cached context "
                          "(workloads prefill_b8 | prefill_fp8 | prefill_tiny); stage: a step copies every KV block of "
-                         "the batch to a staging image and back (ps_kv_stage_out + ps_kv_stage_in)")
+                         "the batch to a staging image and back (ps_kv_stage_out + ps_kv_stage_in); loop: a multi-step decode "
+                         "loop, a step = one token appended to every private segment (ps_layout_append, upload, "
+                         "ps_kv_append) + the attention step")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--models", type=int, default=0, help="override the number of decode models M (b8, long, fp8_70b)")
     ap.add_argument("--copies", type=int, default=3, help="distinct KV pool copies rotated between steps")
@@ -485,6 +487,102 @@ def main_prefill(args):
     print(json.dumps(line))
 
 
+def main_loop(args):
+    """A multi-step decode loop: per step one token is appended to every private segment (host tables, upload, the
+    store of the new K/V) and one decode-attention call follows, all on one stream, the host never waiting for the GPU."""
+    import torch
+    import workloads as wl
+    from paper_2602_12029_amd import binding as B
+    from paper_2602_12029_amd.runtime import to_device
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    dev = "cuda:0"
+    w = wl.named_workload(args.workload, args.seed, args.models or None)
+    g = w.geometry
+    R = w.num_requests
+    total_steps = args.warmup + args.steps
+    extra = R * (total_steps // g.block_size + 2)                       # blocks the appends may take
+    geo = B.geometry(g.num_q_heads, g.num_kv_heads, g.head_dim, g.block_size, g.q_dtype, g.kv_dtype)
+    order = np.concatenate([np.asarray(w.free_order, np.int32), np.arange(w.num_blocks, w.num_blocks + extra, dtype=np.int32)])
+    pool = B.ps_pool_create(w.num_blocks + extra, order)
+    layout = B.ps_kv_layout(pool, geo, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
+    tables = B.ps_layout_tables(layout, w.num_prompts, R)
+    data = wl.fill_pool(w, tables["prefix_blk_indptr"], tables["prefix_blk"], tables["suffix_blk_indptr"], tables["suffix_blk"])
+    kv_filled = to_device(data.kv, g.kv_dtype, dev)
+    per_block = kv_filled.numel() // w.num_blocks
+    kv = torch.zeros((w.num_blocks + extra) * per_block, dtype=kv_filled.dtype, device=dev)
+    kv[:kv_filled.numel()] = kv_filled.reshape(-1)
+    scales = None
+    if data.scales is not None:
+        scales = torch.ones((w.num_blocks + extra, g.num_kv_heads, 2), dtype=torch.float32, device=dev)
+        scales[:w.num_blocks] = torch.from_numpy(data.scales).to(dev)
+    q = to_device(w.q_bits(), g.q_dtype, dev)
+    out = torch.empty_like(q)
+    gen = torch.Generator(device=dev).manual_seed(args.seed)
+    new_k = torch.randn((R, g.num_kv_heads, g.head_dim), device=dev, generator=gen).to(torch.bfloat16 if g.kv_dtype != "f32" else torch.float32)
+    new_v = torch.randn((R, g.num_kv_heads, g.head_dim), device=dev, generator=gen).to(new_k.dtype)
+    # device buffers with room for the growth of the tables and of the partial-state workspace; two table buffers,
+    # filled alternately on a copy stream, so that the upload of step i + 1 overlaps with the kernels of step i
+    tab_bytes = int(B.ps_layout_device_bytes(layout) * 1.5) + (1 << 20)
+    tabs = [torch.empty(tab_bytes, dtype=torch.uint8, device=dev) for _ in range(2)]
+    wsp = torch.empty(int(B.ps_workspace_bytes(layout) * 2) + (1 << 20), dtype=torch.uint8, device=dev)
+    compute = torch.cuda.current_stream()
+    copy = torch.cuda.Stream()                                    # default priority
+    uploaded = [torch.cuda.Event() for _ in range(2)]             # tables i are on the device
+    consumed = [torch.cuda.Event() for _ in range(2)]             # the kernels that read tables i are done
+    stream, copy_stream = int(compute.cuda_stream), int(copy.cuda_stream)
+    sc = scales.data_ptr() if scales is not None else 0
+    host_s = 0.0
+    count = 0
+
+    def step():
+        nonlocal host_s, count
+        i = count & 1
+        count += 1
+        h0 = time.perf_counter()
+        B.ps_layout_append(pool, layout, R)
+        if B.ps_layout_device_bytes(layout) > tab_bytes or B.ps_workspace_bytes(layout) > wsp.numel():
+            sys.exit("bench.py: tables or workspace outgrew their buffers")
+        host_s += time.perf_counter() - h0
+        if count > 2:
+            copy.wait_event(consumed[i])
+        B.ps_layout_upload(layout, tabs[i].data_ptr(), copy_stream)
+        uploaded[i].record(copy)
+        compute.wait_event(uploaded[i])
+        tp = tabs[i].data_ptr()
+        B.ps_kv_append(layout, tp, new_k.data_ptr(), new_v.data_ptr(), kv.data_ptr(), sc, stream)
+        B.ps_decode_attention(layout, tp, q.data_ptr(), kv.data_ptr(), sc, wsp.data_ptr(), out.data_ptr(), 0, stream)
+        consumed[i].record(compute)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    host_s = 0.0
+    bytes0 = wl.ideal_bytes(w) + R * args.warmup * g.token_bytes
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    ideal = bytes0 + R * g.token_bytes * (args.steps + 1) / 2            # mean over the timed steps: one more token per request and step
+    value = ideal / (ms_per_step * 1e-3) / 1e9
+    line = {
+        "metric": "decode loop (append + decode attention per step): ideal-byte HBM GB/s + queries/sec",
+        "value": value, "unit": "GB/s", "pct_of_peak_hbm": 100.0 * value / PEAK_HBM_GBS,
+        "queries_per_s": R / (ms_per_step * 1e-3), "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "host_ms_per_step": host_s * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": {"bf16": "bf16", "fp8_e4m3": "u8", "f32": "f32"}[g.kv_dtype], "data": "synthetic",
+        "config": {"workload": args.workload, "path": "loop", "requests": R, "mean_ideal_bytes": ideal,
+                   "note": "host_ms_per_step = ps_layout_append; the tables go up on a copy stream into two device buffers "
+                           "used alternately, so the upload of a step overlaps with the kernels of the step before"},
+        "roofline": {"bound": "hbm", "achieved": value, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": value / PEAK_HBM_GBS,
+                     "traffic": None, "kernel": "whole step (append store + attention + merge), wall clock"},
+    }
+    print(json.dumps(line))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -496,6 +594,8 @@ def main():
         return main_prefill(args)
     if args.path == "stage":
         return main_stage(args)
+    if args.path == "loop":
+        return main_loop(args)
     import torch
     import workloads as wl
     from paper_2602_12029_amd import binding as B

@@ -16,8 +16,8 @@
  *     current device.  The caller owns all device memory (KV pool, scales, Q, O, workspace, the
  *     uploaded table blob); the library owns only the opaque host objects it creates.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Kernels are enqueued
- *     asynchronously and never synchronise; ps_layout_upload copies from pageable host memory and
- *     may block the host until the copy is staged.
+ *     asynchronously and never synchronise; ps_layout_upload stages the tables in pinned host
+ *     memory the layout owns (two buffers, used alternately) and returns once the copy is enqueued.
  *   - q and out are [R][Hq][d] contiguous in q_dtype.  The KV pool is addressed as
  *         elem(block, kv_head, which, slot, c) = block*kv_stride_block + kv_head*kv_stride_head
  *                                               + which*kv_stride_kv + slot*kv_stride_tok + c
@@ -184,7 +184,10 @@ int32_t ps_layout_schedule(const ps_layout* layout, int32_t which, int32_t* num_
                            const int32_t** items, const int32_t** indptr);
 
 /* Size of the int32 table blob, and its copy to device memory (at least that many bytes, 16-byte
- * aligned) on `stream`. */
+ * aligned) on `stream`.  The copy is asynchronous: the layout may be changed (ps_layout_append,
+ * ps_layout_replan) as soon as the call returns; kernels that use dev_tables must follow on the same
+ * stream or be ordered behind it by the caller.  The third upload of a layout waits on the host for the
+ * first one's copy, the fourth for the second's, and so on. */
 int64_t ps_layout_device_bytes(const ps_layout* layout);
 int32_t ps_layout_upload(const ps_layout* layout, void* dev_tables, void* stream);
 /* Partial-state workspace: fp32 o[num_slots][Hq][d] followed, at lse_offset_bytes, by fp32

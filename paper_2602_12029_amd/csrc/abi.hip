@@ -5,6 +5,16 @@
 
 #include "device_common.h"
 #include "launch.h"
+#include <cstring>
+#include <new>
+
+struct ps_layout::upload_staging {
+  void* buffer[2] = {nullptr, nullptr};   // pinned host memory
+  size_t capacity[2] = {0, 0};
+  hipEvent_t done[2] = {nullptr, nullptr};   // recorded behind the copy that reads the buffer
+  bool in_use[2] = {false, false};
+  int next = 0;
+};
 
 namespace {
 
@@ -41,6 +51,15 @@ psdev::AttnParams make_params(const ps_layout* lay, const void* dev_tables, cons
   p.s_tok = g.kv_stride_tok;
   p.scale_log2 = float(1.4426950408889634 / std::sqrt(double(g.head_dim)));
   return p;
+}
+
+void free_upload_staging(ps_layout::upload_staging* s) {
+  for (int i = 0; i < 2; ++i) {
+    if (s->in_use[i]) (void)hipEventSynchronize(s->done[i]);
+    if (s->done[i]) (void)hipEventDestroy(s->done[i]);
+    if (s->buffer[i]) (void)hipHostFree(s->buffer[i]);
+  }
+  delete s;
 }
 
 enum class WorkSet { kPrefix, kSuffix, kAll };
@@ -89,8 +108,38 @@ int32_t ps_last_hip_error(void) { return g_last_hip_error; }
 
 int32_t ps_layout_upload(const ps_layout* lay, void* dev_tables, void* stream) {
   if (!lay || !dev_tables) return PS_ERR_INVALID_ARG;
-  return check_hip(hipMemcpyAsync(dev_tables, lay->blob.data(), lay->blob.size() * sizeof(int32_t),
-                                  hipMemcpyHostToDevice, static_cast<hipStream_t>(stream)));
+  // The tables go through one of two pinned host buffers the layout owns, so the copy is truly asynchronous: the
+  // call returns once it is enqueued, and the next ps_layout_append may rebuild the tables while it is in flight.
+  // A buffer is reused two uploads later, after the copy that last read it has finished (an event per buffer).
+  if (!lay->staging) {
+    lay->staging = new (std::nothrow) ps_layout::upload_staging();
+    if (!lay->staging) return PS_ERR_OOM;
+    lay->staging_free = free_upload_staging;
+  }
+  ps_layout::upload_staging* s = lay->staging;
+  const int i = s->next;
+  s->next ^= 1;
+  const size_t bytes = lay->blob.size() * sizeof(int32_t);
+  if (s->in_use[i]) {
+    if (int32_t st = check_hip(hipEventSynchronize(s->done[i]))) return st;
+    s->in_use[i] = false;
+  }
+  if (s->capacity[i] < bytes) {
+    if (s->buffer[i]) (void)hipHostFree(s->buffer[i]);
+    s->buffer[i] = nullptr;
+    s->capacity[i] = 0;
+    const size_t want = bytes + bytes / 4 + 4096;
+    if (int32_t st = check_hip(hipHostMalloc(&s->buffer[i], want, hipHostMallocDefault))) return st;
+    s->capacity[i] = want;
+  }
+  if (!s->done[i])
+    if (int32_t st = check_hip(hipEventCreateWithFlags(&s->done[i], hipEventDisableTiming))) return st;
+  std::memcpy(s->buffer[i], lay->blob.data(), bytes);
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (int32_t rc = check_hip(hipMemcpyAsync(dev_tables, s->buffer[i], bytes, hipMemcpyHostToDevice, st))) return rc;
+  if (int32_t rc = check_hip(hipEventRecord(s->done[i], st))) return rc;
+  s->in_use[i] = true;
+  return PS_OK;
 }
 
 int32_t ps_prefix_attention(const ps_layout* lay, const void* dev_tables, const void* q, const void* kv_pool,

@@ -83,6 +83,14 @@ struct ps_layout {
   // started in the concatenated block array when the plan was made
   std::vector<int32_t> suffix_chunk_size, suffix_chunks;
   int32_t planned_root_blk0 = 0;
+  // upload staging (abi.hip): two pinned host buffers used alternately, so that ps_layout_upload returns as soon as
+  // its copy is enqueued and the tables may change again right away; released with the layout
+  struct upload_staging;
+  mutable upload_staging* staging = nullptr;
+  mutable void (*staging_free)(upload_staging*) = nullptr;
+  ~ps_layout() {
+    if (staging && staging_free) staging_free(staging);
+  }
   // directory entries (first source token, valid tokens) of the shared segments' blocks: prefixes, then roots
   std::vector<int32_t> ent_fixed_tok0, ent_fixed_valid;
 
