@@ -11,9 +11,10 @@
 //   online softmax per row (a row lives in lanes n, n+16, n+32, n+48; n = lane % 16)
 //   O^T[dcol, row] += V^T[dcol, token] . P^T[token, row]          A = V^T, B = P^T
 // The C layout of S^T (lane (n, kg) holds tokens 4kg..4kg+3 of a block for row n) is exactly the B
-// layout PV needs, so probabilities never leave their lane.  K rows are fetched 16 bytes per lane in
-// the A layout (the contraction index is permuted consistently in K and Q); V is fetched row-wise
-// (one 16-lane group covers a full token row) and transposed inside each lane with 16-bit picks.
+// layout PV needs, so probabilities never leave their lane.  K rows are fetched 16 bytes per lane, eight
+// lanes to a 128-byte line, and reach the A layout with one rotation inside each row of 16 lanes (the
+// contraction index is permuted consistently in K and Q); V is fetched row-wise (one 16-lane group covers
+// a full token row) and transposed inside each lane with 16-bit picks.
 //
 // Streaming: a wave owns a ring of NB tile buffers in VGPRs; the loads of the tile NB - 1 slots ahead
 // are issued before the math of the current one.  Every slot issues the same 16 buffer loads -- a slot
@@ -46,12 +47,12 @@ template <int KVT>
 struct TileRegs;                  // raw K/V of one 32-token tile as loaded
 template <>
 struct TileRegs<PS_BF16> {
-  u32x4 k[2][4];                  // [block][k-step]: 8 bf16 of token (lane%16), d-chunk 4*step + lane/16
+  u32x4 k[2][4];                  // [block][2 T + h]: 16 bytes of token 8 T + lane % 8, see load_item_tile
   u32x4 v[8];                     // token i of this lane's 8 tokens, d columns 8*(lane%16)..+7
 };
 template <>
 struct TileRegs<PS_FP8_E4M3> {
-  u32x4 k[2][2];                  // [block][half]: 16 codes of token (lane%16), d 64*half + 16*(lane/16)..+15
+  u32x4 k[2][2];                  // [block][T]: 16 codes of token 8 T + lane % 8, see load_item_tile
   u32x2 v[8];                     // 8 codes: token i, d columns 8*(lane%16)..+7
 };
 
@@ -70,6 +71,34 @@ struct ItemMeta {
   int ids;
   float ksc, lvs;   // e4m3: K scale and log2 of the V scale of the block (1 and 0 otherwise)
 };
+
+// K rows reach the lanes in whole 128-byte lines: one load instruction covers 8 tokens, 8 lanes each -- lane (n, kg)
+// takes 16 bytes at chunk (n >> 3) + 2 kg of the line, for token 8 T + (n & 7).  (Fetching 16 bytes per lane for token n
+// directly would ask for half a line per token and instruction; a read kernel with that footprint tops out at 6.2 TB/s
+// on this chip against 7.0 TB/s with whole lines.)  Lanes n < 8 then hold their own token in the T = 0 load and lane
+// (n + 8)'s token in the T = 1 load, lanes n >= 8 the other way round; one rotation by 8 inside each row of 16 lanes
+// hands the foreign half over.  Afterwards every lane (n, kg) holds chunks 2 kg (even) and 2 kg + 1 (odd) of token n.
+constexpr int kRowRor8 = 0x128;   // DPP control: rotate by 8 lanes within each row of 16
+__device__ __forceinline__ u32x4 k_even(u32x4 t0, u32x4 t1) {   // lanes n < 8 keep t0, lanes n >= 8 get lane (n - 8)'s t1
+  u32x4 r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) r[i] = __builtin_amdgcn_update_dpp(t0[i], t1[i], kRowRor8, 0xF, 0xC, false);
+  return r;
+}
+__device__ __forceinline__ u32x4 k_odd(u32x4 t0, u32x4 t1) {    // lanes n >= 8 keep t1, lanes n < 8 get lane (n + 8)'s t0
+  u32x4 r;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) r[i] = __builtin_amdgcn_update_dpp(t1[i], t0[i], kRowRor8, 0xF, 0x3, false);
+  return r;
+}
+// element offset of the 8 query values that meet K's k-step `step` in lane group kg (the contraction index is
+// permuted, identically in K and Q): bf16 rows have two lines, steps (2 h, 2 h + 1) = even and odd chunk of line h;
+// an e4m3 row is one line, steps (0, 1) = the two halves of the even chunk, (2, 3) of the odd one
+template <int KVT>
+__device__ __forceinline__ int k_step_elem(int step, int kg) {
+  if constexpr (KVT == PS_BF16) return 64 * (step >> 1) + 16 * kg + 8 * (step & 1);
+  return 32 * kg + 8 * step;
+}
 
 template <int NT>
 struct QIndex { int idx[NT]; };   // global q row (request * Hq + head) this thread fetches per row tile, -1 = padding
@@ -108,7 +137,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
   const int tok_bytes = int(p.s_tok) * kEsz;
   const int kv_bytes = int(p.s_kv) * kEsz;    // K -> V distance inside a (block, head)
   // per-lane byte offsets inside a 16-token sub-block
-  const int k_lane_off = n * tok_bytes + kg * 16;
+  const int k_lane_off = (n & 7) * tok_bytes + ((n >> 3) + 2 * kg) * 16;
   const int v_lane_off = 4 * kg * tok_bytes + n * (8 * kEsz);
 
   const int64_t kv_base = reinterpret_cast<int64_t>(p.kv);
@@ -151,9 +180,11 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
     if (k < c.my_tiles && sub < c.sub_end) {
       m.ids = p.blk[c.blk_off + (sub >> sub_shift)];
       if constexpr (KVT == PS_FP8_E4M3) {
-        const float* sc = p.scales + (int64_t(m.ids) * p.num_kv_heads + c.kv_head) * 2;
-        m.ksc = sc[0];
-        m.lvs = __builtin_amdgcn_logf(sc[1]);   // log2
+        // K and V scale of the (block, head) as one 8-byte load: the addresses differ from lane to lane, so every
+        // load instruction here costs a cache lookup per lane
+        const u32x2 sc = *reinterpret_cast<const u32x2*>(p.scales + (int64_t(m.ids) * p.num_kv_heads + c.kv_head) * 2);
+        m.ksc = __uint_as_float(sc.x);
+        m.lvs = __builtin_amdgcn_logf(__uint_as_float(sc.y));   // log2
       }
     }
     return m;
@@ -223,13 +254,15 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
           __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(addr), 0, valid ? 0x7fffffff : 0, 0x00020000);
       if constexpr (KVT == PS_BF16) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) tr.k[b][s] = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off + 64 * s, 0, kPolicy);
+        for (int s = 0; s < 4; ++s)   // s = 2 T + h: tokens 8 T .. 8 T + 7, line h of their rows
+          tr.k[b][s] = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off + 128 * (s & 1), 8 * (s >> 1) * tok_bytes, kPolicy);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
           tr.v[4 * b + i] = __builtin_amdgcn_raw_buffer_load_b128(rs, v_lane_off, kv_bytes + i * tok_bytes, kPolicy);
       } else {
 #pragma unroll
-        for (int s = 0; s < 2; ++s) tr.k[b][s] = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off + 64 * s, 0, kPolicy);
+        for (int s = 0; s < 2; ++s)   // s = T: tokens 8 T .. 8 T + 7, whole rows
+          tr.k[b][s] = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off, 8 * s * tok_bytes, kPolicy);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
           tr.v[4 * b + i] = __builtin_amdgcn_raw_buffer_load_b64(rs, v_lane_off, kv_bytes + i * tok_bytes, kPolicy);
@@ -277,13 +310,16 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
     for (int b = 0; b < 2; ++b) {
       if constexpr (KVT == PS_BF16) {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) ka[b][s] = as_bf16x8(tr.k[b][s]);
-      } else {
-#pragma unroll
         for (int h = 0; h < 2; ++h) {
-          ka[b][2 * h] = as_bf16x8(e4m3x8_to_bf16x8(tr.k[b][h].x, tr.k[b][h].y));
-          ka[b][2 * h + 1] = as_bf16x8(e4m3x8_to_bf16x8(tr.k[b][h].z, tr.k[b][h].w));
+          ka[b][2 * h] = as_bf16x8(k_even(tr.k[b][h], tr.k[b][2 + h]));
+          ka[b][2 * h + 1] = as_bf16x8(k_odd(tr.k[b][h], tr.k[b][2 + h]));
         }
+      } else {
+        const u32x4 ev = k_even(tr.k[b][0], tr.k[b][1]), od = k_odd(tr.k[b][0], tr.k[b][1]);
+        ka[b][0] = as_bf16x8(e4m3x8_to_bf16x8(ev.x, ev.y));
+        ka[b][1] = as_bf16x8(e4m3x8_to_bf16x8(ev.z, ev.w));
+        ka[b][2] = as_bf16x8(e4m3x8_to_bf16x8(od.x, od.y));
+        ka[b][3] = as_bf16x8(e4m3x8_to_bf16x8(od.z, od.w));
       }
     }
     // scores and probabilities of every row tile first ...
@@ -295,7 +331,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
         bf16x8 qb[4];
 #pragma unroll
         for (int st = 0; st < 4; ++st)
-          qb[st] = as_bf16x8(*reinterpret_cast<const u32x4*>(&sm_q[t][n][q_chunk_elem<KVT>(st, kg)]));
+          qb[st] = as_bf16x8(*reinterpret_cast<const u32x4*>(&sm_q[t][n][k_step_elem<KVT>(st, kg)]));
         f32x4 s[2];
 #pragma unroll
         for (int b = 0; b < 2; ++b) {
