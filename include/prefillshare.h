@@ -22,7 +22,8 @@
  *         elem(block, kv_head, which, slot, c) = block*kv_stride_block + kv_head*kv_stride_head
  *                                               + which*kv_stride_kv + slot*kv_stride_tok + c
  *     (which: 0 = K, 1 = V; strides in elements; the head_dim axis is contiguous; every stride must
- *     be a multiple of 16 bytes).  kv_scales (fp8 only) is [num_blocks][Hkv][2] fp32: K scale, V scale.
+ *     be a multiple of 16 bytes; where kv_stride_kv + block_size*kv_stride_tok reaches 2 GiB the
+ *     matrix-core kernels do not apply and the plan uses the wavefront kernel).  kv_scales (fp8 only) is [num_blocks][Hkv][2] fp32: K scale, V scale.
  *   - q head h reads KV head h / (Hq / Hkv).  Every stored token of both segments is attended to,
  *     unless ps_layout_set_visible limits how much of the shared prefix a request sees.  Scores are
  *     scaled by 1/sqrt(head_dim).

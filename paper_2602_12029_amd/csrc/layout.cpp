@@ -38,9 +38,14 @@ int32_t check_geometry(const ps_geometry& g) {
 }  // namespace
 
 bool ps_mfma_supported(const ps_geometry& g) {
+  // The matrix-core kernels address a (block, head) slice through a buffer descriptor with 32-bit byte offsets
+  // (V plane + token row + column), so the slice must span less than 2 GiB; a pool with K and V planes further
+  // apart than that goes to the wavefront kernel, which computes 64-bit addresses.
+  const int64_t esz = g.kv_dtype == PS_BF16 ? 2 : 1;
+  const int64_t slice_span = (g.kv_stride_kv + int64_t(g.block_size) * g.kv_stride_tok) * esz;
   return g.q_dtype == PS_BF16 && (g.kv_dtype == PS_BF16 || g.kv_dtype == PS_FP8_E4M3) && g.head_dim == 128 &&
          g.block_size % 16 == 0 && ((g.block_size / 16) & (g.block_size / 16 - 1)) == 0 &&  // 16, 32, 64, ...
-         (g.num_q_heads / g.num_kv_heads) <= 64;
+         (g.num_q_heads / g.num_kv_heads) <= 64 && slice_span < (int64_t(1) << 31);
 }
 
 // ---------------------------------------------------------------------------------------------------

@@ -43,13 +43,32 @@ def check_against_oracle(case, requests=None, label="", visible=None):
     return max_abs, rel_rms
 
 
+def pool_strides(g, num_blocks, pool_layout):
+    """(block, head, kv, tok) strides in elements of a physical pool layout, and the axis order that turns the dense
+    [blk][Hkv][2][B][d] array into it.
+
+    dense        [blk][Hkv][K|V][B][d]   a (block, head) tile is one contiguous piece
+    token_major  [blk][K|V][B][Hkv][d]   all heads of a token side by side, as a model's projection writes them
+    planes       [K|V][blk][Hkv][B][d]   one K cache and one V cache, a whole pool apart
+    """
+    h, b, d = g.num_kv_heads, g.block_size, g.head_dim
+    if pool_layout == "dense":
+        return None, (0, 1, 2, 3, 4)
+    if pool_layout == "token_major":
+        return (2 * b * h * d, d, b * h * d, h * d), (0, 2, 3, 1, 4)
+    if pool_layout == "planes":
+        return (h * b * d, b * d, num_blocks * h * b * d, d), (2, 0, 1, 3, 4)
+    raise ValueError(pool_layout)
+
+
 class GpuCase:
     """One workload on the GPU next to its oracle-side layout and pool."""
 
-    def __init__(self, w: wl.Workload, device="cuda:0"):
+    def __init__(self, w: wl.Workload, device="cuda:0", pool_layout="dense"):
         self.w = w
         g = w.geometry
-        self.geo = B.geometry(g.num_q_heads, g.num_kv_heads, g.head_dim, g.block_size, g.q_dtype, g.kv_dtype)
+        strides, axes = pool_strides(g, w.num_blocks, pool_layout)
+        self.geo = B.geometry(g.num_q_heads, g.num_kv_heads, g.head_dim, g.block_size, g.q_dtype, g.kv_dtype, strides)
         self.pool = B.ps_pool_create(w.num_blocks, w.free_order)
         if w.num_roots:
             self.layout = B.ps_kv_layout_tree(self.pool, self.geo, w.root_len, w.prompt_root, w.prefix_len, w.req_prompt,
@@ -64,7 +83,8 @@ class GpuCase:
             assert np.array_equal(t[key], getattr(self.olay, key)), key
         self.q_bits = w.q_bits()
         q = to_device(self.q_bits, g.q_dtype, device)
-        kv = to_device(self.data.kv, g.kv_dtype, device)
+        # the oracle keeps its dense pool; the device gets the same bits in the layout the strides describe
+        kv = to_device(np.ascontiguousarray(self.data.kv.transpose(axes)), g.kv_dtype, device)
         scales = None if self.data.scales is None else torch.from_numpy(self.data.scales).to(device)
         self.batch = DecodeBatch(self.layout, self.geo, w.num_requests, q, kv, scales)
 

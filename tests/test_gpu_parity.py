@@ -149,6 +149,23 @@ def test_ragged_shapes(gpu, spec):
     case.close()
 
 
+@pytest.mark.parametrize("pool_layout", ["token_major", "planes"])
+@pytest.mark.parametrize("spec", [RAGGED[0], RAGGED[1], RAGGED[2], RAGGED[7]], ids=lambda s: s[0])
+def test_pool_layouts_through_the_strides(gpu, spec, pool_layout):
+    """The pool is addressed through the four strides only: the same bits in two other physical layouts (all heads of
+    a token side by side; K and V caches a whole pool apart) give the same attention, on both kernel families."""
+    name, geo, models, prefix, membership, suffix = spec
+    w = wl.make_workload(name, geo, models, prefix, membership, suffix, pool_factor=1.5, seed=23)
+    case = gpu(w, pool_layout=pool_layout)
+    for variant in _variants(w):
+        for pc, sc in ((0, 0), (64, 32)):
+            case.replan(pc, sc, variant, variant)
+            case.poison_workspace()
+            case.batch.decode_attention()
+            _check(case, label=f"{name} {pool_layout} {variant} chunks {pc}/{sc}")
+    case.close()
+
+
 def test_long_item_lists_per_workgroup(gpu):
     """Few workgroups, hundreds of small items each: the persistent kernel's item pipeline, its header ring
     refills and every kind of item boundary (waves without a tile, one-tile items, ragged tails)."""

@@ -299,6 +299,29 @@ def test_kernel_family_selection():
     assert variants(wl.Geometry(8, 2, 128, 48, "bf16", "bf16")) == (B.PS_VARIANT_WAVE, B.PS_VARIANT_WAVE, False)
 
 
+def test_kernel_family_follows_the_span_of_a_block_head_slice():
+    """The matrix-core kernels use 32-bit byte offsets inside a (block, head) slice; a pool whose K and V planes lie
+    2 GiB or more apart is planned onto the wavefront kernel (64-bit addresses), and asking for the matrix-core
+    kernel on it is refused."""
+    def planned(kv_stride):
+        geo = B.geometry(8, 2, 128, 16, "bf16", "bf16", strides=(2 * 16 * 128, 16 * 128, kv_stride, 128))
+        pool = B.ps_pool_create(8)
+        lay = B.ps_kv_layout(pool, geo, [64], [0], [0], [8])
+        plan = B.ps_layout_plan(lay, 1)
+        forced = None
+        try:
+            B.ps_layout_replan(lay, B.plan_options(0, 0, B.PS_VARIANT_MFMA, B.PS_VARIANT_MFMA))
+        except Exception as e:  # noqa: BLE001 - the binding raises on any non-zero status
+            forced = str(e)
+        B.ps_layout_release(pool, lay)
+        B.ps_pool_destroy(pool)
+        return plan["prefix_variant"], plan["suffix_variant"], forced
+    near = planned((1 << 30) - 16 * 128 - 8)      # the slice ends 16 bytes below 2 GiB (bf16: 2 bytes per element)
+    assert near[:2] == (B.PS_VARIANT_MFMA, B.PS_VARIANT_MFMA) and near[2] is None
+    far = planned((1 << 30) - 16 * 128)           # ... and exactly at 2 GiB
+    assert far[:2] == (B.PS_VARIANT_WAVE, B.PS_VARIANT_WAVE) and far[2] is not None
+
+
 def test_many_models_split_into_row_chunks():
     geo = wl.Geometry(32, 2, 64, 16, "f32", "f32")           # group of 16: at most 4 requests per item
     w = wl.make_workload("many", geo, 10, [64], [list(range(10))], [1] * 10, seed=4)
