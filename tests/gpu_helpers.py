@@ -68,6 +68,7 @@ class GpuCase:
         self.w = w
         g = w.geometry
         strides, axes = pool_strides(g, w.num_blocks, pool_layout)
+        self.pool_axes = axes
         self.geo = B.geometry(g.num_q_heads, g.num_kv_heads, g.head_dim, g.block_size, g.q_dtype, g.kv_dtype, strides)
         self.pool = B.ps_pool_create(w.num_blocks, w.free_order)
         if w.num_roots:

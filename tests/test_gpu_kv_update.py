@@ -41,7 +41,7 @@ def _host_bits(a: np.ndarray) -> np.ndarray:
 
 def _same_pool(case, label):
     torch.cuda.synchronize()
-    got = _bits(case.batch.kv).reshape(case.data.kv.shape)
+    got = _bits(case.batch.kv).transpose(np.argsort(case.pool_axes))     # back to the dense axis order
     assert np.array_equal(got, _host_bits(case.data.kv)), f"{label}: pool bits differ"
     if case.data.scales is not None:
         assert np.array_equal(_bits(case.batch.scales), _host_bits(case.data.scales)), f"{label}: scales differ"
@@ -66,7 +66,7 @@ def _poison(case):
     g = case.w.geometry
     case.data.kv[...] = gen.POISON[g.kv_dtype]
     bits = torch.from_numpy(_host_bits(case.data.kv)).to(case.batch.kv.device)
-    case.batch.kv.copy_(bits.view(case.batch.kv.dtype))
+    case.batch.kv.view(-1).copy_(bits.view(case.batch.kv.dtype).view(-1))   # one value everywhere: any axis order
     if case.data.scales is not None:
         case.data.scales[...] = np.float32("nan")
         case.batch.scales.copy_(torch.from_numpy(case.data.scales).to(case.batch.scales.device))
@@ -103,11 +103,11 @@ def _ingest_both_sides(case, pad=False):
             ku.ingest_segment(case.data.kv, case.data.scales, g.kv_dtype, blk[indptr[i]:indptr[i + 1]], src[i][0], src[i][1])
 
 
-@pytest.mark.parametrize("pad", [False, True])
-def test_ingest_bit_exact(gpu, pad):
+@pytest.mark.parametrize("pad,pool_layout", [(False, "dense"), (True, "dense"), (True, "token_major"), (False, "planes")])
+def test_ingest_bit_exact(gpu, pad, pool_layout):
     for w in _workloads():
-        print(f"ingest {w.name} pad={pad}", flush=True)
-        case = gpu(w)
+        print(f"ingest {w.name} pad={pad} pool {pool_layout}", flush=True)
+        case = gpu(w, pool_layout=pool_layout)
         _poison(case)
         _ingest_both_sides(case, pad)
         _same_pool(case, w.name)
@@ -161,10 +161,11 @@ def _append_steps(case, steps, rng, check_each=False):
             _same_pool(case, f"{w.name} step {t}")
 
 
-def test_append_bit_exact(gpu):
+@pytest.mark.parametrize("pool_layout", ["dense", "token_major"])
+def test_append_bit_exact(gpu, pool_layout):
     for w in _workloads():
-        print(f"append {w.name}", flush=True)
-        case = gpu(w)
+        print(f"append {w.name} pool {pool_layout}", flush=True)
+        case = gpu(w, pool_layout=pool_layout)
         rng = np.random.default_rng(11)
         _append_steps(case, 2 * w.geometry.block_size + 3 if w.geometry.block_size <= 16 else 70, rng, check_each=w.geometry.block_size <= 16)
         _same_pool(case, w.name)
