@@ -34,14 +34,16 @@ def parse():
     ap.add_argument("--stage-image", default="device", choices=["device", "host"],
                     help="--path stage: where the staging image lives (device memory: the kernels' own rate; pinned "
                          "host memory: the rate across PCIe)")
-    ap.add_argument("--path", default="decode", choices=["decode", "ingest", "prefill", "stage", "loop"],
+    ap.add_argument("--path", default="decode", choices=["decode", "ingest", "prefill", "stage", "loop", "probe"],
                     help="decode: the attention step (the headline metric); ingest: hand-off of the batch's KV into "
                          "the paged pool (ps_kv_ingest over every prefix and suffix), a step = one whole hand-off; "
                          "prefill: attention of newly appended context tokens against the cached context "
                          "(workloads prefill_b8 | prefill_fp8 | prefill_tiny); stage: a step copies every KV block of "
                          "the batch to a staging image and back (ps_kv_stage_out + ps_kv_stage_in); loop: a multi-step decode "
                          "loop, a step = one token appended to every private segment (ps_layout_append, upload, "
-                         "ps_kv_append) + the attention step")
+                         "ps_kv_append) + the attention step; probe: no part of the method -- a read-only kernel in "
+                         "the attention kernel's launch shape over 2 GiB, one rate per load-instruction footprint "
+                         "(ps_probe_read), the ceilings the attention kernel's rate is read against")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--models", type=int, default=0, help="override the number of decode models M (b8, long, fp8_70b)")
     ap.add_argument("--copies", type=int, default=3, help="distinct KV pool copies rotated between steps")
@@ -587,6 +589,48 @@ def main_loop(args):
     print(json.dumps(line))
 
 
+def main_probe(args):
+    """--path probe: read ceilings of this GPU for the load footprints of the attention kernel (ps_probe_read)."""
+    import torch
+    from paper_2602_12029_amd import binding as B
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    nbytes = 2 << 30                                   # well past the 256 MB last-level cache
+    buf = torch.ones(nbytes, dtype=torch.uint8, device="cuda:0")
+    stream = int(torch.cuda.current_stream().cuda_stream)
+    patterns = {0: "16 B per lane, 1 KiB contiguous per instruction",
+                1: "16 B per lane, 16 rows x 64 B of 128-byte rows (half lines)",
+                2: "16 B per lane, 16 rows x 64 B of 256-byte rows (half lines)",
+                3: "8 B per lane, 512 B contiguous per instruction"}
+    steps = max(1, min(args.steps, 20))
+    ev = HipEvents(steps)
+    rates = {}
+    t0 = time.perf_counter()
+    for pat, what in patterns.items():
+        for _ in range(2):
+            B.ps_probe_read(buf.data_ptr(), nbytes, pat, 512, stream)
+        for i in range(steps):
+            ev.record(i, 0, stream)
+            B.ps_probe_read(buf.data_ptr(), nbytes, pat, 512, stream)
+            ev.record(i, 1, stream)
+        torch.cuda.synchronize()
+        ms = min(ev.elapsed_ms(i) for i in range(steps))
+        rates[what] = {"GB/s": nbytes / (ms * 1e-3) / 1e9, "ms": ms}
+    wall_ms = (time.perf_counter() - t0) * 1e3 / (len(patterns) * steps)
+    best = max(r["GB/s"] for r in rates.values())
+    print(json.dumps({
+        "metric": "read probe: GB/s of a read-only kernel by load-instruction footprint (not the method's metric)",
+        "value": best, "unit": "GB/s", "n_gpus": 1, "steps": steps, "warmup": 2, "ms_per_step": wall_ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "probe", "bytes": nbytes, "workgroups": 512, "in_flight_per_wave": 8192,
+                   "loads": "non-temporal", "timing": "fastest of the timed launches, HIP events"},
+        "patterns": rates,
+        "roofline": {"bound": "hbm", "achieved": best, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": best / PEAK_HBM_GBS,
+                     "traffic": None},
+    }))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -600,6 +644,8 @@ def main():
         return main_stage(args)
     if args.path == "loop":
         return main_loop(args)
+    if args.path == "probe":
+        return main_probe(args)
     import torch
     import workloads as wl
     from paper_2602_12029_amd import binding as B

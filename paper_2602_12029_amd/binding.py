@@ -28,7 +28,7 @@ EXPORTS = [
     "ps_layout_lengths", "ps_layout_append", "ps_kv_append", "ps_kv_ingest",
     "ps_layout_set_visible", "ps_layout_request_list", "ps_kv_layout_tree", "ps_layout_root_tables",
     "ps_kv_layout_adopt", "ps_blocks_needed", "ps_layout_state", "ps_stage_layout", "ps_kv_stage_out", "ps_kv_stage_in", "ps_layout_park",
-    "ps_layout_resume",
+    "ps_layout_resume", "ps_probe_read",
     "ps_strerror", "ps_last_hip_error",
 ]
 
@@ -381,6 +381,11 @@ def ps_kv_stage_out(layout, dev_tables, kv_pool, kv_scales, image, stream=0):
 def ps_kv_stage_in(layout, dev_tables, image, kv_pool, kv_scales, stream=0):
     _check(_lib().ps_kv_stage_in(layout, _p(dev_tables), _p(image), _p(kv_pool), _p(kv_scales), _p(stream)),
            "ps_kv_stage_in")
+
+
+def ps_probe_read(dev_buf, nbytes: int, pattern: int, num_workgroups: int, stream=0):
+    _check(_lib().ps_probe_read(_p(dev_buf), C.c_int64(nbytes), C.c_int32(pattern), C.c_int32(num_workgroups),
+                                _p(stream)), "ps_probe_read")
 
 
 def ps_layout_park(pool, layout):

@@ -5,7 +5,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = ["layout.cpp", "abi.hip", "wave_attention.hip", "mfma_attention.hip", "prefill_attention.hip", "merge.hip", "kv_update.hip"]
+SOURCES = ["layout.cpp", "abi.hip", "wave_attention.hip", "mfma_attention.hip", "prefill_attention.hip", "merge.hip", "kv_update.hip", "probe.hip"]
 LIB = os.path.join(HERE, "libprefillshare.so")
 
 

@@ -26,6 +26,8 @@ int32_t launch_kv_append(const ps_layout* lay, const void* dev_tables, const voi
 // blocks at scales_offset_bytes.
 int32_t launch_kv_stage(const ps_layout* lay, const void* dev_tables, bool to_image, void* kv, float* scales,
                         void* image, int64_t scales_offset_bytes, hipStream_t st);
+// Measurement aid: reads `bytes` (whole 8 KiB units of it) once with the load footprint `pattern` names.
+int32_t launch_probe_read(const void* buf, int64_t bytes, int pattern, int num_workgroups, hipStream_t st);
 int32_t launch_merge(const int32_t* slot_base, const float* ws_o, const float* ws_lse, void* out, float* out_lse,
                      int num_requests, const ps_geometry& g, hipStream_t st);
 

@@ -228,3 +228,21 @@ def test_full_size_sampled_outputs(gpu, name):
     sample = sorted(set(sample) | {int(by_len[0]), int(by_len[-1])})
     _check(case, requests=sample)
     case.close()
+
+
+def test_read_probe_runs_every_pattern_and_refuses_bad_arguments(gpu):
+    """ps_probe_read is a measurement aid: every footprint runs to completion on a buffer with a ragged tail (only
+    whole 8 KiB units are read), and bad arguments are refused before anything is launched."""
+    from paper_2602_12029_amd import binding as B
+    buf = torch.zeros(3 * 8192 + 100, dtype=torch.uint8, device="cuda:0")
+    stream = int(torch.cuda.current_stream().cuda_stream)
+    for pattern in range(4):
+        for wgs in (1, 7):
+            B.ps_probe_read(buf.data_ptr(), buf.numel(), pattern, wgs, stream)
+    B.ps_probe_read(buf.data_ptr(), 100, 0, 4, stream)          # less than one unit: nothing to read
+    torch.cuda.synchronize()
+    for bad in ((0, buf.numel(), 0, 4), (buf.data_ptr(), -1, 0, 4), (buf.data_ptr(), buf.numel(), 4, 4),
+                (buf.data_ptr(), buf.numel(), 0, 0), (buf.data_ptr() + 8, buf.numel() - 8, 0, 4)):
+        with pytest.raises(B.PsError):
+            B.ps_probe_read(*bad, stream)
+    torch.cuda.synchronize()
