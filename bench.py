@@ -589,6 +589,21 @@ def main_loop(args):
     print(json.dumps(line))
 
 
+def read_ceiling_gbs(stream, nbytes=1 << 30):
+    """Rate of the read probe with whole-line loads: the ceiling this GPU gives a kernel shaped like the attention kernel."""
+    import torch
+    from paper_2602_12029_amd import binding as B
+    buf = torch.ones(nbytes, dtype=torch.uint8, device="cuda:0")
+    ev = HipEvents(5)
+    B.ps_probe_read(buf.data_ptr(), nbytes, 0, 512, stream)
+    for i in range(5):
+        ev.record(i, 0, stream)
+        B.ps_probe_read(buf.data_ptr(), nbytes, 0, 512, stream)
+        ev.record(i, 1, stream)
+    torch.cuda.synchronize()
+    return nbytes / (min(ev.elapsed_ms(i) for i in range(5)) * 1e-3) / 1e9
+
+
 def main_probe(args):
     """--path probe: read ceilings of this GPU for the load footprints of the attention kernel (ps_probe_read)."""
     import torch
@@ -720,6 +735,12 @@ def main():
         k_ms = float(np.mean([ev.elapsed_ms(i) for i in range(0, args.steps, every)]))
         roofline.update(achieved=attn_bytes / (k_ms * 1e-3) / 1e9, kernel_ms=k_ms, algorithmic_bytes=attn_bytes)
         roofline["frac"] = roofline["achieved"] / PEAK_HBM_GBS
+
+    # what a read-only kernel of the same launch shape reaches on this GPU right now (whole-line loads, 1 GiB)
+    if ev is not None and roofline["achieved"]:
+        ceiling = read_ceiling_gbs(stream)
+        roofline["read_ceiling"] = {"value": ceiling, "unit": "GB/s", "frac_of_it": roofline["achieved"] / ceiling,
+                                    "how": "ps_probe_read, 16 B per lane and 1 KiB per instruction, fastest of 5 launches"}
 
     # HBM bytes per launch from the committed rocprofv3 counter summary of this workload, if there is one
     summary = os.path.join(ROOT, "profiles", f"attention_kernel_{args.workload}.md")
