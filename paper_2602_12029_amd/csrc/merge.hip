@@ -25,20 +25,38 @@ __global__ __launch_bounds__(256) void merge_states_kernel(const int32_t* __rest
   const int s0 = slot_base[r], s1 = slot_base[r + 1];
   const float neg_inf = -__builtin_inff();
 
-  float mx = neg_inf;
-  for (int s = s0; s < s1; ++s) mx = fmaxf(mx, ws_lse[int64_t(s) * num_q_heads + h]);
-  float total = 0.f;
+  // Batches of up to four partial states: their lse and o loads all go out before anything is used, so a row with
+  // at most four splits (the usual case: one or two prefix chunks and a suffix chunk) costs one memory round trip
+  // after slot_base instead of one for the maxima and one for the values.  Across batches the running state
+  // (mx, total, acc) is rescaled like an online softmax; a single batch is the plain two-pass formula.
+  float mx = neg_inf, total = 0.f;
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  if (mx != neg_inf) {
-    for (int s = s0; s < s1; ++s) {
-      const float lse = ws_lse[int64_t(s) * num_q_heads + h];
-      const float w = (lse == neg_inf) ? 0.f : fast_exp2((lse - mx) * kLog2e);
-      total += w;
-      const f32x4 o = *reinterpret_cast<const f32x4*>(ws_o + (int64_t(s) * num_q_heads + h) * head_dim + 4 * c4);
-      acc += w * o;
+  for (int b0 = s0; b0 < s1; b0 += 4) {
+    float lse[4];
+    f32x4 o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int s = min(b0 + i, s1 - 1);   // slots past the end re-read the last one and get weight zero below
+      lse[i] = ws_lse[int64_t(s) * num_q_heads + h];
+      o[i] = *reinterpret_cast<const f32x4*>(ws_o + (int64_t(s) * num_q_heads + h) * head_dim + 4 * c4);
+      if (b0 + i >= s1) lse[i] = neg_inf;
     }
-    acc *= 1.f / total;
+    const float bm = fmaxf(fmaxf(fmaxf(lse[0], lse[1]), fmaxf(lse[2], lse[3])), mx);
+    if (bm == neg_inf) continue;           // nothing but empty states so far
+    const float keep = (mx == neg_inf) ? 0.f : fast_exp2((mx - bm) * kLog2e);
+    total *= keep;
+    acc *= keep;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (lse[i] != neg_inf) {             // an empty state has weight zero, whatever its o holds
+        const float w = fast_exp2((lse[i] - bm) * kLog2e);
+        total += w;
+        acc += w * o[i];
+      }
+    }
+    mx = bm;
   }
+  if (mx != neg_inf) acc *= 1.f / total;
   if constexpr (QT == PS_F32) {
     *reinterpret_cast<f32x4*>(static_cast<float*>(out) + row * head_dim + 4 * c4) = acc;
   } else {
