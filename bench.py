@@ -28,7 +28,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="b8",
+    ap.add_argument("--workload", default="mixed",
                     help="tiny | b8 | long | mixed | fp8_70b; tree_tiny | tree_b8 (a context common to all sessions, stored "
                          "once as a third sharing level)")
     ap.add_argument("--stage-image", default="device", choices=["device", "host"],
@@ -55,6 +55,11 @@ def parse():
                     help="K/V loads of the matrix-core decode kernel: non-temporal, ordinary, or chosen per launch")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target wall time of the oracle sample; 0 = skip")
     ap.add_argument("--no-events", action="store_true", help="do not record per-kernel events in the timed loop")
+    ap.add_argument("--event-steps", type=int, default=100,
+                    help="decode path: steps of the event-bracketed loop that follows the timed region (attention "
+                         "launches and whole step one by one: mean, median; at least 20)")
+    ap.add_argument("--no-per-config", dest="per_config", action="store_false",
+                    help="decode path: only the headline workload, not the per_config map over b8 / long / mixed / fp8_70b")
     ap.add_argument("--event-every", type=int, default=4,
                     help="bracket the attention kernel with HIP events on every n-th timed step (each bracket costs "
                          "a few microseconds of stream time)")
@@ -646,32 +651,23 @@ def main_probe(args):
     }))
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs the decode attention of ONE GPU (no collectives, no sharding); "
-                 "use --gpus 1")
-    if args.path == "ingest":
-        return main_ingest(args)
-    if args.path == "prefill":
-        return main_prefill(args)
-    if args.path == "stage":
-        return main_stage(args)
-    if args.path == "loop":
-        return main_loop(args)
-    if args.path == "probe":
-        return main_probe(args)
+def _stats(samples):
+    x = np.asarray(samples, np.float64)
+    return {"mean": float(x.mean()), "median": float(np.median(x)), "min": float(x.min()), "n": int(x.size)}
+
+
+def measure_decode(args, name, steps, warmup, cpu_seconds, ceiling):
+    """One workload through ps_decode_attention: wall clock over exactly `steps` steps, then an event-bracketed loop
+    (at least 20 steps, whatever `steps` is) that gives the attention launch(es) and the whole step one by one."""
     import torch
     import workloads as wl
     from paper_2602_12029_amd import binding as B
     from paper_2602_12029_amd.runtime import DecodeBatch, to_device
 
-    if not torch.cuda.is_available():
-        sys.exit("bench.py: no GPU visible")
     dev = "cuda:0"
     variant = {"auto": B.PS_VARIANT_AUTO, "wave": B.PS_VARIANT_WAVE, "mfma": B.PS_VARIANT_MFMA}
-    tree = args.workload.startswith("tree")
-    w = wl.named_tree_workload(args.workload, args.seed) if tree else wl.named_workload(args.workload, args.seed, args.models or None)
+    tree = name.startswith("tree")
+    w = wl.named_tree_workload(name, args.seed) if tree else wl.named_workload(name, args.seed, args.models or None)
     g = w.geometry
     geo = B.geometry(g.num_q_heads, g.num_kv_heads, g.head_dim, g.block_size, g.q_dtype, g.kv_dtype)
     pool = B.ps_pool_create(w.num_blocks, w.free_order)
@@ -699,66 +695,61 @@ def main():
     sc = scales.data_ptr() if scales is not None else 0
     tp, qp, wp, op = batch.tables.data_ptr(), q.data_ptr(), batch.workspace.data_ptr(), batch.out.data_ptr()
 
-    def attention(kv):      # the dominant kernel(s): prefix + suffix work list
-        B.ps_prefix_suffix_attention(layout, tp, qp, kv.data_ptr(), sc, wp, stream)
-
     if args.calibrate_copy:
         calibrate_copy(dev)
 
-    for i in range(args.warmup):
+    for i in range(warmup):
         batch.decode_attention(with_lse=False, kv=copies[i % len(copies)])
     torch.cuda.synchronize()
-
-    ev = None if args.no_events else HipEvents(args.steps)
-    every = max(1, args.event_every)
-    torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for i in range(args.steps):
-        kv = copies[i % len(copies)]
-        if ev is None or i % every:
-            batch.decode_attention(with_lse=False, kv=kv)
-        else:
-            ev.record(i, 0, stream)
-            attention(kv)
-            ev.record(i, 1, stream)
-            B.ps_merge_states(layout, tp, wp, op, 0, stream)
+    for i in range(steps):
+        batch.decode_attention(with_lse=False, kv=copies[i % len(copies)])
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
 
     ideal = wl.ideal_bytes(w)
     esz_q = wl.generate.ELEM_BYTES[g.q_dtype]
     attn_bytes = ideal - w.num_requests * g.num_q_heads * g.head_dim * esz_q        # O is written by the merge
     roofline = {"bound": "hbm", "kernel": "attention (prefix + suffix work list)", "achieved": None,
                 "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": None, "traffic": None}
-    if ev is not None:
-        k_ms = float(np.mean([ev.elapsed_ms(i) for i in range(0, args.steps, every)]))
-        roofline.update(achieved=attn_bytes / (k_ms * 1e-3) / 1e9, kernel_ms=k_ms, algorithmic_bytes=attn_bytes)
+    step_stats = None
+    if not args.no_events:
+        # the same step, one by one: event, attention launch(es), event, merge, event
+        n = max(20, args.event_steps)
+        ev_a, ev_b = HipEvents(n), HipEvents(n)
+        for i in range(n):
+            kv = copies[(steps + i) % len(copies)]
+            ev_a.record(i, 0, stream)
+            B.ps_prefix_suffix_attention(layout, tp, qp, kv.data_ptr(), sc, wp, stream)
+            ev_a.record(i, 1, stream)
+            B.ps_merge_states(layout, tp, wp, op, 0, stream)
+            ev_b.record(i, 1, stream)
+        torch.cuda.synchronize()
+        ev_b.events = [(ev_a.events[i][0], ev_b.events[i][1]) for i in range(n)]
+        k = _stats([ev_a.elapsed_ms(i) for i in range(n)])
+        step_stats = _stats([ev_b.elapsed_ms(i) for i in range(n)])
+        roofline.update(achieved=attn_bytes / (k["mean"] * 1e-3) / 1e9, kernel_ms=k["mean"], kernel_ms_median=k["median"],
+                        kernel_ms_min=k["min"], kernel_samples=k["n"], algorithmic_bytes=attn_bytes)
         roofline["frac"] = roofline["achieved"] / PEAK_HBM_GBS
+        if ceiling:
+            roofline["read_ceiling"] = {"value": ceiling, "unit": "GB/s", "frac_of_it": roofline["achieved"] / ceiling,
+                                        "how": "ps_probe_read, 16 B per lane and 1 KiB per instruction, fastest of 5 launches"}
 
-    # what a read-only kernel of the same launch shape reaches on this GPU right now (whole-line loads, 1 GiB)
-    if ev is not None and roofline["achieved"]:
-        ceiling = read_ceiling_gbs(stream)
-        roofline["read_ceiling"] = {"value": ceiling, "unit": "GB/s", "frac_of_it": roofline["achieved"] / ceiling,
-                                    "how": "ps_probe_read, 16 B per lane and 1 KiB per instruction, fastest of 5 launches"}
-
-    # HBM bytes per launch from the committed rocprofv3 counter summary of this workload, if there is one
-    summary = os.path.join(ROOT, "profiles", f"attention_kernel_{args.workload}.md")
+    # HBM bytes per launch: not measured by this run -- read from the committed rocprofv3 counter summary of this
+    # workload (two --pmc runs of this command, FETCH_SIZE and WRITE_SIZE), if there is one
+    summary = os.path.join(ROOT, "profiles", f"attention_kernel_{name}.md")
     if os.path.exists(summary):
         for text in open(summary):
             if text.startswith("traffic_bytes_per_launch:"):
                 roofline["traffic"] = float(text.split(":")[1])
+                roofline["traffic_source"] = f"profiles/attention_kernel_{name}.md (rocprofv3 --pmc runs of this command, not this run)"
 
     value = ideal / (ms_per_step * 1e-3) / 1e9
-    line = {
-        "metric": "shared-prefix decode attention: ideal-byte HBM GB/s (% peak) + queries/sec",
-        "value": value, "unit": "GB/s", "pct_of_peak_hbm": 100.0 * value / PEAK_HBM_GBS,
-        "queries_per_s": w.num_requests / (ms_per_step * 1e-3),
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+    res = {
+        "value": value, "pct_of_peak_hbm": 100.0 * value / PEAK_HBM_GBS,
+        "queries_per_s": w.num_requests / (ms_per_step * 1e-3), "ms_per_step": ms_per_step,
         "dtype": "bf16" if g.kv_dtype == "bf16" else ("fp8_e4m3 KV / bf16 Q" if g.kv_dtype == "fp8_e4m3" else "f32"),
-        "data": "synthetic",
-        "config": {"workload": args.workload, "roots": w.num_roots, "models": w.num_models, "prompts": w.num_prompts,
+        "config": {"workload": name, "roots": w.num_roots, "models": w.num_models, "prompts": w.num_prompts,
                    "requests": w.num_requests, "q_heads": g.num_q_heads, "kv_heads": g.num_kv_heads,
                    "head_dim": g.head_dim, "block_size": g.block_size, "ideal_bytes": ideal,
                    "pool_copies": len(copies), "plan_items": int(plan["items"].shape[0]),
@@ -766,8 +757,70 @@ def main():
                    "layout_plan_ms": t_layout_ms},
         "roofline": roofline,
     }
-    if args.cpu_seconds > 0:
-        line["cpu_baseline"] = cpu_baseline(w, tables, data, args.cpu_seconds)
+    if step_stats:
+        res["ms_per_step_median"] = step_stats["median"]
+        res["ms_per_step_events_mean"] = step_stats["mean"]
+        res["value_at_median"] = ideal / (step_stats["median"] * 1e-3) / 1e9
+    if cpu_seconds > 0:
+        res["cpu_baseline"] = cpu_baseline(w, tables, data, cpu_seconds)
+    torch.cuda.synchronize()
+    B.ps_layout_release(pool, layout)
+    B.ps_pool_destroy(pool)
+    del batch, copies, kv0, q, scales, data
+    torch.cuda.empty_cache()
+    return res
+
+
+PER_CONFIG = ("b8", "long", "mixed", "fp8_70b")
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs the decode attention of ONE GPU (no collectives, no sharding); "
+                 "use --gpus 1")
+    if args.path == "ingest":
+        return main_ingest(args)
+    if args.path == "prefill":
+        return main_prefill(args)
+    if args.path == "stage":
+        return main_stage(args)
+    if args.path == "loop":
+        return main_loop(args)
+    if args.path == "probe":
+        return main_probe(args)
+    import torch
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    stream = int(torch.cuda.current_stream().cuda_stream)
+    # what a read-only kernel of the attention kernel's launch shape reaches on this GPU right now (1 GiB)
+    ceiling = None if args.no_events else read_ceiling_gbs(stream)
+    head = measure_decode(args, args.workload, args.steps, args.warmup, args.cpu_seconds, ceiling)
+    line = {
+        "metric": "shared-prefix decode attention: ideal-byte HBM GB/s (% peak) + queries/sec",
+        "value": head["value"], "unit": "GB/s", "pct_of_peak_hbm": head["pct_of_peak_hbm"],
+        "queries_per_s": head["queries_per_s"],
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "ms_per_step_median": head.get("ms_per_step_median"), "value_at_median": head.get("value_at_median"),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": head["dtype"], "data": "synthetic",
+        "config": head["config"], "roofline": head["roofline"],
+    }
+    if "cpu_baseline" in head:
+        line["cpu_baseline"] = head["cpu_baseline"]
+    if args.per_config:
+        # the other benchmark configurations, each its own short run of the same step (no oracle leg)
+        per = {}
+        for name in PER_CONFIG:
+            r = head if name == args.workload else measure_decode(args, name, max(args.steps, 50), max(args.warmup, 10), 0.0, ceiling)
+            rf = r["roofline"]
+            per[name] = {"ms_per_step": r["ms_per_step"], "ms_per_step_median": r.get("ms_per_step_median"),
+                         "value": r["value"], "unit": "GB/s", "pct_of_peak_hbm": r["pct_of_peak_hbm"],
+                         "queries_per_s": r["queries_per_s"], "ideal_bytes": r["config"]["ideal_bytes"],
+                         "roofline_frac": rf["frac"], "kernel_ms": rf.get("kernel_ms"),
+                         "kernel_ms_median": rf.get("kernel_ms_median"),
+                         "read_ceiling_frac": (rf.get("read_ceiling") or {}).get("frac_of_it")}
+        line["per_config"] = per
     print(json.dumps(line))
 
 

@@ -68,7 +68,8 @@ typedef struct ps_plan_options {
   int32_t suffix_chunk_tokens; /* same for private suffixes; 0 = choose                           */
   int32_t prefix_variant;      /* PS_VARIANT_*                                                    */
   int32_t suffix_variant;      /* PS_VARIANT_*                                                    */
-  int32_t num_cus;             /* compute units to plan for; 0 = 256                              */
+  int32_t num_cus;             /* compute units to plan for; 0 = those of the current device (256
+                                  on MI355X, which is also assumed where no device is visible)    */
   int32_t kv_cache_policy;     /* PS_KV_POLICY_*: how the matrix-core decode kernel loads K/V     */
 } ps_plan_options;
 
@@ -117,11 +118,11 @@ int32_t ps_kv_layout_tree(ps_pool* pool, const ps_geometry* geometry, int32_t nu
                           int32_t num_prompts, const int32_t* prompt_root, const int32_t* prefix_len,
                           int32_t num_requests, const int32_t* req_prompt, const int32_t* req_model,
                           const int32_t* suffix_len, ps_layout** out);
-/* ps_kv_layout_adopt: ps_kv_layout for a batch that continues cached contexts.  Prefix-aware routing keeps a context's
- * cache where it is, "enabling incremental cache extension instead of recomputing the prefix from scratch" (System
- * Design), and the context grows as X(i) = [X(i-1); Y(i)] (execution pipeline): the layout of the next step -- the
- * partial prefill of Y(i), or the next decode batch over X(i) -- adopts the blocks that already hold the beginning of
- * its prompts.  adopt_indptr[P+1], adopt_blk[..]: for prompt p the physical ids of its first
+/* ps_kv_layout_adopt: ps_kv_layout for a batch that continues cached contexts.  Prefix-aware routing sends a session
+ * back to the worker that holds its cache, so that the cache is extended rather than rebuilt (System Design,
+ * prefix-aware routing), and the context grows as X(i) = [X(i-1); Y(i)] (System Design, execution pipeline): the
+ * layout of the next step -- the partial prefill of Y(i), or the next decode batch over X(i) -- adopts the blocks that
+ * already hold the beginning of its prompts.  adopt_indptr[P+1], adopt_blk[..]: for prompt p the physical ids of its first
  * n = adopt_indptr[p+1] - adopt_indptr[p] prefix blocks, taken over from a layout that still holds them.  Only full
  * blocks are adopted (n * block_size <= prefix_len[p]); each gains one reference per request on the prompt, like a
  * block from the free list, and stays alive until the last layout referencing it is released; the other
@@ -197,11 +198,19 @@ int64_t ps_workspace_bytes(const ps_layout* layout);
 int32_t ps_workspace_layout(const ps_layout* layout, int64_t* num_slots, int64_t* lse_offset_bytes);
 
 /* ---- attention passes (device pointers; asynchronous on `stream`) ---------------------------------
- * ps_prefix_attention: for every prompt, KV head and chunk of the prompt's shared prefix, streams the
- * chunk's K/V blocks once and applies them to the queries of every request on that prompt and every
- * q head of the KV head's group; writes one partial state per (request, q head, prefix split).
- * ps_suffix_attention: the same over each request's private blocks (flash-decoding split over tokens).
- * Both write only their own slots of `workspace`. */
+ * What all of them compute (Background Eq. 2 and Eq. 4: a decode step attends to the whole cache; Method Eq. 6: the
+ * cache of a decode module is C_base followed by the entries the module appended itself): for request r on prompt p
+ * and q head h, softmax attention of the one query row over [shared prefix of p ; private suffix of r].
+ *
+ * ps_prefix_attention (Method Eq. 5-6: C_base is produced once and every decode module starts from it; Efficiency
+ * Analysis Eq. 9: it is stored once): for every prompt, KV head and chunk of the prompt's shared prefix, streams the
+ * chunk's K/V blocks once and applies them to the queries of every request on that prompt and every q head of the
+ * KV head's group; writes one partial state per (request, q head, prefix split).
+ * ps_suffix_attention (Method Eq. 6, the entries a decode module appended; the N * L_unique term of Eq. 9): the same
+ * over each request's private blocks (flash-decoding split over tokens).
+ * Both write only their own slots of `workspace` (device, ps_workspace_bytes, 16-byte aligned, caller-owned).
+ * Errors: PS_ERR_INVALID_ARG (null layout / tables / workspace, null q or kv_pool with work to do, null kv_scales
+ * for an e4m3 pool, a parked layout), PS_ERR_UNSUPPORTED (no kernel for the geometry), PS_ERR_DEVICE. */
 int32_t ps_prefix_attention(const ps_layout* layout, const void* dev_tables, const void* q,
                             const void* kv_pool, const float* kv_scales, void* workspace, void* stream);
 int32_t ps_suffix_attention(const ps_layout* layout, const void* dev_tables, const void* q,
@@ -210,15 +219,16 @@ int32_t ps_suffix_attention(const ps_layout* layout, const void* dev_tables, con
  * out as one launch (this is the attention part of ps_decode_attention). */
 int32_t ps_prefix_suffix_attention(const ps_layout* layout, const void* dev_tables, const void* q,
                                    const void* kv_pool, const float* kv_scales, void* workspace, void* stream);
-/* ps_merge_states: per (request, q head) combines the request's partial states,
- * lse = log sum_i exp(lse_i), o = sum_i exp(lse_i - lse) o_i, and writes out[R][Hq][d] in q_dtype
- * (bf16: round to nearest even) and, if out_lse != NULL, lse as fp32 [R][Hq].  A request with no
- * tokens at all gets o = 0, lse = -inf.  `workspace` may have been filled by the two passes or by the
+/* ps_merge_states (softmax algebra over the concatenated cache of Background Eq. 2: the attention over
+ * [prefix ; suffix] is the weighted combination of the attentions over its parts): per (request, q head) combines
+ * the request's partial states, lse = log sum_i exp(lse_i), o = sum_i exp(lse_i - lse) o_i, and writes
+ * out[R][Hq][d] in q_dtype (bf16: round to nearest even) and, if out_lse != NULL, lse as fp32 [R][Hq].  A request
+ * with no tokens at all gets o = 0, lse = -inf.  `workspace` may have been filled by the two passes or by the
  * caller in the documented format. */
 int32_t ps_merge_states(const ps_layout* layout, const void* dev_tables, const void* workspace,
                         void* out, float* out_lse, void* stream);
-/* ps_decode_attention: the whole step -- ps_prefix_suffix_attention, then ps_merge_states -- on one
- * stream. */
+/* ps_decode_attention (Background Eq. 2 / Eq. 4, Method Eq. 6: one decode step's attention over the whole cache):
+ * the whole step -- ps_prefix_suffix_attention, then ps_merge_states -- on one stream. */
 int32_t ps_decode_attention(const ps_layout* layout, const void* dev_tables, const void* q,
                             const void* kv_pool, const float* kv_scales, void* workspace,
                             void* out, float* out_lse, void* stream);
@@ -317,19 +327,6 @@ int32_t ps_kv_stage_in(const ps_layout* layout, const void* dev_tables, const vo
                        float* kv_scales, void* stream);
 int32_t ps_layout_park(ps_pool* pool, ps_layout* layout);
 int32_t ps_layout_resume(ps_pool* pool, ps_layout* layout);
-
-/* ---- measurement aid ---------------------------------------------------------------------------------
- * ps_probe_read (device, asynchronous on `stream`): no part of the method.  Reads the first
- * floor(bytes / 8192) * 8192 bytes of dev_buf (device memory, 16-byte aligned, caller-owned, not written) once and
- * discards them, with `num_workgroups` workgroups of four wavefronts, 8 KiB in flight per wavefront and
- * non-temporal loads -- the launch shape of the attention kernel -- and the per-instruction footprint `pattern`
- * names: 0 = 16 bytes per lane, 1 KiB contiguous per instruction; 1 = 16 rows x 64 bytes of 128-byte rows (half a
- * cache line per row and instruction); 2 = 16 rows x 64 bytes of 256-byte rows; 3 = 8 bytes per lane, 512 bytes
- * contiguous per instruction.  Timed by the caller (`bench.py --path probe`), it gives the read ceiling each
- * footprint allows, next to which the attention kernel's own rate is to be read.
- * PS_ERR_INVALID_ARG: null or misaligned buffer, negative size, pattern outside 0..3, num_workgroups outside
- * 1..65536. */
-int32_t ps_probe_read(const void* dev_buf, int64_t bytes, int32_t pattern, int32_t num_workgroups, void* stream);
 
 const char* ps_strerror(int32_t status);
 int32_t ps_last_hip_error(void);

@@ -33,6 +33,18 @@ EXPORTS = [
 ]
 
 
+# entry points that enqueue device work or query the HIP runtime (csrc/abi.hip); the rest is host-only (csrc/layout.cpp)
+DEVICE_EXPORTS = {
+    "ps_layout_upload", "ps_prefix_attention", "ps_suffix_attention", "ps_prefix_suffix_attention", "ps_merge_states",
+    "ps_decode_attention", "ps_kv_append", "ps_kv_ingest", "ps_kv_stage_out", "ps_kv_stage_in", "ps_probe_read",
+    "ps_last_hip_error",
+}
+# Test hook: path of a build of the host side alone (block pool, tables, split plan) under AddressSanitizer / UBSan
+# (`python -m paper_2602_12029_amd.build --sanitize`).  The device entry points do not exist in it, so nothing can
+# compute through it; it serves the CPU-only sanitizer run of the host tests.
+HOST_ONLY_LIB_ENV = "PREFILLSHARE_HOST_ONLY_LIB"
+
+
 class PsError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -62,19 +74,23 @@ _I32P = C.POINTER(C.c_int32)
 def _lib():
     global _LIB
     if _LIB is None:
-        if not os.path.exists(LIB_PATH):
-            raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2602_12029_amd.build` "
+        host_only = os.environ.get(HOST_ONLY_LIB_ENV)
+        path = host_only or LIB_PATH
+        if not os.path.exists(path):
+            raise ImportError(f"{path} is missing: run `python -m paper_2602_12029_amd.build` "
                               "(there is no CPU fallback)")
-        # The caller's device memory and streams come from PyTorch, so the library has to bind to the
-        # HIP runtime PyTorch ships: importing torch first makes the loader resolve libamdhip64 to it.
-        import torch  # noqa: F401
-        lib = C.CDLL(LIB_PATH)
+        if not host_only:
+            # The caller's device memory and streams come from PyTorch, so the library has to bind to the
+            # HIP runtime PyTorch ships: importing torch first makes the loader resolve libamdhip64 to it.
+            import torch  # noqa: F401
+        lib = C.CDLL(path)
         lib.ps_strerror.restype = C.c_char_p
         lib.ps_strerror.argtypes = [C.c_int32]
         lib.ps_layout_device_bytes.restype = C.c_int64
         lib.ps_workspace_bytes.restype = C.c_int64
         for name in EXPORTS:
-            getattr(lib, name)                      # fail early if a symbol is missing
+            if not (host_only and name in DEVICE_EXPORTS):
+                getattr(lib, name)                  # fail early if a symbol is missing
         _LIB = lib
     return _LIB
 

@@ -5,6 +5,8 @@
 
 #include "device_common.h"
 #include "launch.h"
+#include "prefillshare_probe.h"
+#include <atomic>
 #include <cstring>
 #include <new>
 
@@ -61,6 +63,23 @@ void free_upload_staging(ps_layout::upload_staging* s) {
   }
   delete s;
 }
+
+// Compute units of the current device (asked once per device), 0 if there is no device to ask: the planner's
+// default for ps_plan_options.num_cus = 0.
+constexpr int kMaxDevices = 64;
+int32_t current_device_num_cus() {
+  static std::atomic<int32_t> cached[kMaxDevices];
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 0;
+  if (const int32_t known = cached[dev].load(std::memory_order_relaxed)) return known;
+  int count = 0;
+  if (hipDeviceGetAttribute(&count, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || count <= 0) return 0;
+  cached[dev].store(count, std::memory_order_relaxed);
+  return count;
+}
+const struct HookInstaller {
+  HookInstaller() { ps_device_num_cus_hook = current_device_num_cus; }
+} g_hook_installer;
 
 enum class WorkSet { kPrefix, kSuffix, kAll };
 

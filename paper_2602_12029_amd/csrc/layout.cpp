@@ -37,6 +37,8 @@ int32_t check_geometry(const ps_geometry& g) {
 
 }  // namespace
 
+int32_t (*ps_device_num_cus_hook)() = nullptr;
+
 bool ps_mfma_supported(const ps_geometry& g) {
   // The matrix-core kernels address a (block, head) slice through a buffer descriptor with 32-bit byte offsets
   // (V plane + token row + column), so the slice must span less than 2 GiB; a pool with K and V planes further
@@ -63,7 +65,10 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   if ((opt.prefix_variant == PS_VARIANT_MFMA || opt.suffix_variant == PS_VARIANT_MFMA) && !mfma_ok)
     return PS_ERR_UNSUPPORTED;
   const int32_t group = g.num_q_heads / g.num_kv_heads;
-  const int32_t num_cus = opt.num_cus ? opt.num_cus : 256;
+  // compute units to spread the work over: the caller's figure, else the current device's, else MI355X's
+  int32_t num_cus = opt.num_cus;
+  if (num_cus == 0 && ps_device_num_cus_hook) num_cus = ps_device_num_cus_hook();
+  if (num_cus <= 0) num_cus = kPsDefaultNumCus;
 
   // chunk boundaries fall on block boundaries and on the 32-token MFMA tile
   const int64_t granule = std::lcm<int64_t>(g.block_size, 32);

@@ -117,6 +117,11 @@ inline int ps_mfma_occupancy(int max_rows, int kv_dtype) {
 }
 constexpr int kPsMfmaMaxChunk = 4096;  // tokens per MFMA work item (32 tiles per wave)
 
+// Compute units of the current device, or 0 if none can be asked.  Null in a build without the device side of the
+// library (the planner then assumes kPsDefaultNumCus); abi.hip installs it when the library is loaded.
+extern int32_t (*ps_device_num_cus_hook)();
+constexpr int32_t kPsDefaultNumCus = 256;   // MI355X
+
 // layout.cpp
 int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* opt);
 int32_t ps_blob_build(ps_layout* lay);

@@ -14,8 +14,14 @@ VARIANT = {"auto": B.PS_VARIANT_AUTO, "wave": B.PS_VARIANT_WAVE, "mfma": B.PS_VA
 TOL = {"f32": (1e-5, 1e-5), "bf16": (1e-2, 5e-3), "fp8_e4m3": (1e-2, 5e-3)}   # (max-abs, relative RMS) by KV dtype
 
 
-def check_against_oracle(case, requests=None, label="", visible=None):
-    """Output and LSE of the last step on the GPU against the fp64 oracle, element by element."""
+def check_against_oracle(case, requests=None, label="", visible=None, scaled_bar=False):
+    """Output and LSE of the last step on the GPU against the fp64 oracle, element by element.
+
+    The bars are the stated ones: max-abs and relative RMS by KV dtype (TOL).  scaled_bar=True is for cases whose rows
+    see only a handful of tokens (or whose softmax is peaked on a few), so that |O| reaches 2-4: an element with
+    |O_ref| > 1 is then held to tol x |O_ref| instead, because half the spacing of bf16 -- the output format -- is
+    already 7.8e-3 on [2, 4); elements with |O_ref| <= 1 keep the literal bar.  The number of elements that used the
+    scaled bar is printed.  Without the flag every element is held to the literal bar."""
     from paper_2602_12029_amd.runtime import from_device
     w = case.w
     g = w.geometry
@@ -28,15 +34,18 @@ def check_against_oracle(case, requests=None, label="", visible=None):
         got_o, got_lse = got_o[list(requests)], got_lse[list(requests)]
     max_abs, rel_rms, worst = errors(got_o, ref_o)
     tol_abs, tol_rms = TOL[g.kv_dtype]
-    print(f"[{label or w.name}] max_abs={max_abs:.3e} rel_rms={rel_rms:.3e} worst_req_rel_rms={worst:.3e}", flush=True)
     assert np.isfinite(got_o).all()
-    # The max-abs bar is stated for outputs of magnitude <= 1 (N(0,1) values averaged over many tokens).  A row that
-    # sees only a few tokens has |O| up to ~4, where the spacing of bf16 -- the output format -- is 2^-6, half of it
-    # 7.8e-3 by itself; there the bar scales with the magnitude of the element.
-    scaled = float((np.abs(got_o - ref_o) / np.maximum(1.0, np.abs(ref_o))).max(initial=0.0))
-    assert scaled <= tol_abs and rel_rms <= tol_rms
-    if g.q_dtype == "f32" or np.abs(ref_o).max(initial=0.0) <= 1.0:
+    err = np.abs(got_o - ref_o)
+    big = np.abs(ref_o) > 1.0
+    n_scaled = int(big.sum()) if (scaled_bar and g.q_dtype != "f32") else 0
+    print(f"[{label or w.name}] max_abs={max_abs:.3e} rel_rms={rel_rms:.3e} worst_req_rel_rms={worst:.3e} "
+          f"scaled_bar_elements={n_scaled}/{err.size}", flush=True)
+    if n_scaled:
+        assert err[~big].max(initial=0.0) <= tol_abs
+        assert (err[big] / np.abs(ref_o[big])).max(initial=0.0) <= tol_abs
+    else:
         assert max_abs <= tol_abs
+    assert rel_rms <= tol_rms
     finite = np.isfinite(ref_lse)
     assert np.array_equal(np.isneginf(got_lse), np.isneginf(ref_lse))
     assert np.abs(got_lse[finite] - ref_lse[finite]).max(initial=0.0) <= (1e-4 if g.kv_dtype == "f32" else 2e-3)

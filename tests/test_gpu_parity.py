@@ -21,9 +21,10 @@ def gpu():
     return GpuCase
 
 
-def _check(case, requests=None, label=""):
+def _check(case, requests=None, label="", short_rows=False):
+    """short_rows: the case has rows that see only a handful of tokens, so some |O| exceed 1 (see the helper)."""
     from gpu_helpers import check_against_oracle
-    return check_against_oracle(case, requests, label)
+    return check_against_oracle(case, requests, label, scaled_bar=short_rows)
 
 
 def _variants(w):
@@ -86,7 +87,7 @@ def test_kv_cache_policies_give_the_same_bits(gpu, name):
         case.replan(prefix_variant="mfma", suffix_variant="mfma", kv_cache_policy=policy)
         case.poison_workspace()
         case.batch.decode_attention()
-        _check(case, label=f"{name} policy {policy}")
+        _check(case, label=f"{name} policy {policy}", short_rows=True)
         outs[policy] = (case.batch.out.clone(), case.batch.lse.clone())
     for policy in (B.PS_KV_POLICY_CACHEABLE, B.PS_KV_POLICY_AUTO):
         assert torch.equal(outs[policy][0].view(torch.int16), outs[B.PS_KV_POLICY_STREAM][0].view(torch.int16))
@@ -145,7 +146,7 @@ def test_ragged_shapes(gpu, spec):
             case.replan(pc, sc, variant, variant)
             case.poison_workspace()
             case.batch.decode_attention()
-            _check(case, label=f"{name} {variant} chunks {pc}/{sc}")
+            _check(case, label=f"{name} {variant} chunks {pc}/{sc}", short_rows=True)
     case.close()
 
 
@@ -162,7 +163,7 @@ def test_pool_layouts_through_the_strides(gpu, spec, pool_layout):
             case.replan(pc, sc, variant, variant)
             case.poison_workspace()
             case.batch.decode_attention()
-            _check(case, label=f"{name} {pool_layout} {variant} chunks {pc}/{sc}")
+            _check(case, label=f"{name} {pool_layout} {variant} chunks {pc}/{sc}", short_rows=True)
     case.close()
 
 
@@ -182,7 +183,7 @@ def test_long_item_lists_per_workgroup(gpu):
             assert np.diff(sch["indptr"]).max() > 128      # more items per workgroup than the header ring holds
         case.poison_workspace()
         case.batch.decode_attention()
-        _check(case, label=f"lists chunks {pc}/{sc} on {cus} CU")
+        _check(case, label=f"lists chunks {pc}/{sc} on {cus} CU", short_rows=True)
     case.close()
 
 
@@ -198,35 +199,20 @@ def test_request_without_tokens_gives_zero_and_neg_inf(gpu):
     case.close()
 
 
-@pytest.mark.parametrize("name", ["b8", "fp8_70b"])
+@pytest.mark.parametrize("name", ["b8", "fp8_70b", "long", "mixed"])
 def test_full_size_all_outputs(gpu, name):
-    """Full benchmark configurations, default plan (the launch configuration bench.py times), every output."""
+    """Full benchmark configurations, default plan (the launch configuration bench.py times), every output of every
+    request against the oracle at the literal bars; bitwise repeatable (no float atomics anywhere)."""
     w = wl.named_workload(name)
     case = gpu(w)
     case.poison_workspace()
     case.batch.decode_attention()
-    _check(case)
+    torch.cuda.synchronize()
     first = case.batch.out.clone()
-    case.batch.decode_attention()                       # no float atomics anywhere: bitwise repeatable
+    case.batch.decode_attention()
     torch.cuda.synchronize()
     assert torch.equal(first.view(torch.int16), case.batch.out.view(torch.int16))
-    case.close()
-
-
-@pytest.mark.parametrize("name", ["long", "mixed"])
-def test_full_size_sampled_outputs(gpu, name):
-    """The two largest configurations: the oracle computes a seeded sample of requests one by one."""
-    w = wl.named_workload(name)
-    case = gpu(w)
-    case.poison_workspace()
-    case.batch.decode_attention()
-    torch.cuda.synchronize()
-    assert torch.isfinite(case.batch.out.float()).all()
-    sample = sorted(np.random.default_rng(7).choice(w.num_requests, size=12, replace=False).tolist())
-    # include the longest and the shortest prefix
-    by_len = np.argsort(w.prefix_len[w.req_prompt])
-    sample = sorted(set(sample) | {int(by_len[0]), int(by_len[-1])})
-    _check(case, requests=sample)
+    _check(case)
     case.close()
 
 

@@ -46,7 +46,7 @@ def test_park_overwrite_resume(gpu, spec, host_image):
     case = gpu(w)
     case.poison_workspace()
     case.batch.decode_attention()
-    check_against_oracle(case, label=f"{name} before parking")
+    check_against_oracle(case, label=f"{name} before parking", scaled_bar=True)
     first = case.batch.out.clone()
 
     # stage out: the image equals the oracle's, bit for bit
@@ -88,7 +88,7 @@ def test_park_overwrite_resume(gpu, spec, host_image):
     assert np.array_equal(pool_bits[ids], case.data.kv.reshape(case.data.kv.shape[0], -1).view(np.uint8)[ids])
     case.poison_workspace()
     case.batch.decode_attention()
-    check_against_oracle(case, label=f"{name} after resume")
+    check_against_oracle(case, label=f"{name} after resume", scaled_bar=True)
     assert torch.equal(first.view(torch.uint8), case.batch.out.view(torch.uint8))        # same bits as before parking
     B.ps_layout_release(case.pool, other)
     case.close()

@@ -18,11 +18,12 @@ def gpu():
     return GpuCase
 
 
-def _run(case, label, visible=None, requests=None):
+def _run(case, label, visible=None, requests=None, short_rows=True):
+    """short_rows: the case has rows that see only a handful of tokens, so some |O| exceed 1 (see the helper)."""
     from gpu_helpers import check_against_oracle
     case.poison_workspace()
     case.batch.decode_attention()
-    return check_against_oracle(case, requests, label, visible)
+    return check_against_oracle(case, requests, label, visible, scaled_bar=short_rows)
 
 
 def _variants(w):
@@ -76,7 +77,7 @@ def test_tree_b8_all_outputs(gpu):
     """Benchmark-sized three-level batch, default plan (the launch configuration bench.py times), every output."""
     w = wl.named_tree_workload("tree_b8")
     case = gpu(w)
-    _run(case, "tree_b8")
+    _run(case, "tree_b8", short_rows=False)
     first = case.batch.out.clone()
     case.batch.decode_attention()
     torch.cuda.synchronize()

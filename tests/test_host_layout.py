@@ -14,7 +14,9 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "prefillshare.h")).read()
+    headers = sorted(f for f in os.listdir(os.path.join(ROOT, "include")) if f.endswith(".h"))
+    assert headers == ["prefillshare.h", "prefillshare_probe.h"]
+    header = "".join(open(os.path.join(ROOT, "include", f)).read() for f in headers)
     declared = set(re.findall(r"\b(ps_[a-z_]+)\s*\(", header))
     assert declared == set(B.EXPORTS)
     lib = B._lib()

@@ -10,6 +10,7 @@ from .generate import (  # noqa: F401
     CONFIG_NAMES,
     Geometry,
     PoolData,
+    ScoreShape,
     Workload,
     bf16_bits_from_f32,
     chunk_prefill_workload,

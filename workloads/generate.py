@@ -95,6 +95,60 @@ class Segment:
     v_scale: Optional[np.ndarray] = None
 
 
+@dataclass(frozen=True)
+class ScoreShape:
+    """Deterministic structure laid over the N(0,1) draws, so that attention scores are not unit-spread.
+
+    Decode attention in practice sees sink tokens, late dominant keys and scores that drift over a context; i.i.d.
+    N(0,1) queries and keys give none of that (their scores spread a few units and the largest one sits anywhere).
+    Everything here acts on the float32 draws before they are rounded / quantised, so the stored bits are still
+    what both sides read.
+
+    q_gain, k_gain   factors on the query / key draws (score spread = q_gain * k_gain)
+    q_bias           added to every component of every query row
+    k_profile        per-token offset c_j added to every component of key j of a segment of L tokens; with
+                     q_bias = b the score of token j moves by about b * c_j * sqrt(d):
+                       'none'            c_j = 0
+                       'ramp_up'         c_j = k_amp * j / max(1, L - 1)        (scores climb through the segment)
+                       'ramp_down'       c_j = k_amp * (1 - j / max(1, L - 1))
+                       'dominant_first'  c_j = k_amp at j = min(3, L - 1), else 0
+                       'dominant_mid'    c_j = k_amp at j = L // 2, else 0
+                       'dominant_last'   c_j = k_amp at j = L - 1, else 0
+                       'equal'           every key of the segment is replaced by one and the same vector (the
+                                         segment's first draw): all its scores are equal
+    segments         which KV segments get the profile: 'all', 'prefix' (shared prefixes and roots) or 'suffix'
+    """
+    q_gain: float = 1.0
+    k_gain: float = 1.0
+    q_bias: float = 0.0
+    k_profile: str = "none"
+    k_amp: float = 0.0
+    segments: str = "all"
+
+    def shape_q(self, q: np.ndarray) -> np.ndarray:
+        return (q * np.float32(self.q_gain) + np.float32(self.q_bias)).astype(np.float32)
+
+    def shape_k(self, k: np.ndarray, shared: bool) -> np.ndarray:
+        """k [L, Hkv, d] float32 draws of one segment -> shaped float32."""
+        k = (k * np.float32(self.k_gain)).astype(np.float32)
+        length = k.shape[0]
+        if length == 0 or self.k_profile == "none" or self.segments == ("suffix" if shared else "prefix"):
+            return k
+        j = np.arange(length, dtype=np.float64)
+        if self.k_profile == "ramp_up":
+            c = self.k_amp * j / max(1, length - 1)
+        elif self.k_profile == "ramp_down":
+            c = self.k_amp * (1.0 - j / max(1, length - 1))
+        elif self.k_profile in ("dominant_first", "dominant_mid", "dominant_last"):
+            at = {"dominant_first": min(3, length - 1), "dominant_mid": length // 2, "dominant_last": length - 1}
+            c = np.where(j == at[self.k_profile], self.k_amp, 0.0)
+        elif self.k_profile == "equal":
+            return np.broadcast_to(k[:1], k.shape).copy()
+        else:
+            raise ValueError(self.k_profile)
+        return (k + c.astype(np.float32)[:, None, None]).astype(np.float32)
+
+
 @dataclass
 class Workload:
     name: str
@@ -111,6 +165,8 @@ class Workload:
     # optional third level: contexts that several prompts begin with (make_tree_workload)
     root_len: np.ndarray = field(default_factory=lambda: np.zeros(0, np.int32))   # int32 [T]
     prompt_root: Optional[np.ndarray] = None                                      # int32 [P], -1 = no root
+    # optional structure on top of the N(0,1) draws (scores that drift, dominate or tie; see ScoreShape)
+    score_shape: Optional[ScoreShape] = None
 
     @property
     def num_roots(self) -> int:
@@ -137,6 +193,8 @@ class Workload:
     def q_bits(self) -> np.ndarray:
         g = self.geometry
         x = self._normal(4, 0, (self.num_requests, g.num_q_heads, g.head_dim))
+        if self.score_shape is not None:
+            x = self.score_shape.shape_q(x)
         return x if g.q_dtype == "f32" else bf16_bits_from_f32(x)
 
     def _segment(self, tag: int, index: int, length: int) -> Segment:
@@ -145,6 +203,8 @@ class Workload:
         rng = _rng(self.seed, tag, index)
         k = rng.standard_normal(shape, dtype=np.float32)
         v = rng.standard_normal(shape, dtype=np.float32)
+        if self.score_shape is not None:
+            k = self.score_shape.shape_k(k, shared=tag != 6)
         if g.kv_dtype == "f32":
             return Segment(k, v)
         if g.kv_dtype == "bf16":
