@@ -46,7 +46,8 @@ enum {
   PS_ERR_OOM = 3,         /* the pool has too few free blocks; nothing was allocated              */
   PS_ERR_REFCOUNT = 4,    /* release would drive a refcount below zero (wrong pool)               */
   PS_ERR_UNSUPPORTED = 5, /* dtype / head_dim / block_size combination without a kernel           */
-  PS_ERR_DEVICE = 6       /* a HIP call failed; ps_last_hip_error() returns its code              */
+  PS_ERR_DEVICE = 6,      /* a HIP call failed; ps_last_hip_error() returns its code              */
+  PS_ERR_TOO_LARGE = 7    /* the batch needs more than a fixed-size buffer of the library holds    */
 };
 
 enum { PS_F32 = 0, PS_BF16 = 1, PS_FP8_E4M3 = 2 /* OCP e4m3fn, KV only */ };
@@ -232,6 +233,19 @@ int32_t ps_merge_states(const ps_layout* layout, const void* dev_tables, const v
 int32_t ps_decode_attention(const ps_layout* layout, const void* dev_tables, const void* q,
                             const void* kv_pool, const float* kv_scales, void* workspace,
                             void* out, float* out_lse, void* stream);
+/* ps_decode_attention_static: ps_decode_attention for callers that cannot allocate device memory -- code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The partial states go to a buffer of
+ * PS_STATIC_WORKSPACE_BYTES that lives in the library's device image (one per GPU, held until the process ends)
+ * instead of a caller-provided workspace; everything else is as in ps_decode_attention (the caller still passes the
+ * uploaded tables, q, the pool, out).  The call allocates nothing, on the host or on the device.
+ * PS_ERR_TOO_LARGE: ps_workspace_bytes(layout) exceeds PS_STATIC_WORKSPACE_BYTES; nothing is launched.
+ * Every call on a GPU uses that GPU's one buffer: calls that overlap on one GPU (two streams, two threads) race, and
+ * the caller must order them.  Nothing in the buffer needs clearing between calls (the attention passes write every
+ * partial state of the batch before the merge reads it); it keeps the last call's contents. */
+#define PS_STATIC_WORKSPACE_BYTES (64ll << 20)
+int32_t ps_decode_attention_static(const ps_layout* layout, const void* dev_tables, const void* q,
+                                   const void* kv_pool, const float* kv_scales, void* out, float* out_lse,
+                                   void* stream);
 
 /* ---- partial prefill: per-request visible prefix length ------------------------------------------------
  * When a context grows by a segment, the prefill worker extends the shared cache only for the newly

@@ -12,7 +12,8 @@ import os
 
 import numpy as np
 
-PS_OK, PS_ERR_INVALID_ARG, PS_ERR_SHAPE, PS_ERR_OOM, PS_ERR_REFCOUNT, PS_ERR_UNSUPPORTED, PS_ERR_DEVICE = range(7)
+PS_OK, PS_ERR_INVALID_ARG, PS_ERR_SHAPE, PS_ERR_OOM, PS_ERR_REFCOUNT, PS_ERR_UNSUPPORTED, PS_ERR_DEVICE, PS_ERR_TOO_LARGE = range(8)
+PS_STATIC_WORKSPACE_BYTES = 64 << 20
 PS_F32, PS_BF16, PS_FP8_E4M3 = 0, 1, 2
 PS_VARIANT_AUTO, PS_VARIANT_WAVE, PS_VARIANT_MFMA = 0, 1, 2
 PS_KV_POLICY_AUTO, PS_KV_POLICY_STREAM, PS_KV_POLICY_CACHEABLE = 0, 1, 2
@@ -28,7 +29,7 @@ EXPORTS = [
     "ps_layout_lengths", "ps_layout_append", "ps_kv_append", "ps_kv_ingest",
     "ps_layout_set_visible", "ps_layout_request_list", "ps_kv_layout_tree", "ps_layout_root_tables",
     "ps_kv_layout_adopt", "ps_blocks_needed", "ps_layout_state", "ps_stage_layout", "ps_kv_stage_out", "ps_kv_stage_in", "ps_layout_park",
-    "ps_layout_resume", "ps_probe_read",
+    "ps_layout_resume", "ps_probe_read", "ps_decode_attention_static",
     "ps_strerror", "ps_last_hip_error",
 ]
 
@@ -36,7 +37,8 @@ EXPORTS = [
 # entry points that enqueue device work or query the HIP runtime (csrc/abi.hip); the rest is host-only (csrc/layout.cpp)
 DEVICE_EXPORTS = {
     "ps_layout_upload", "ps_prefix_attention", "ps_suffix_attention", "ps_prefix_suffix_attention", "ps_merge_states",
-    "ps_decode_attention", "ps_kv_append", "ps_kv_ingest", "ps_kv_stage_out", "ps_kv_stage_in", "ps_probe_read",
+    "ps_decode_attention", "ps_decode_attention_static", "ps_kv_append", "ps_kv_ingest", "ps_kv_stage_out", "ps_kv_stage_in",
+    "ps_probe_read",
     "ps_last_hip_error",
 }
 # Test hook: path of a build of the host side alone (block pool, tables, split plan) under AddressSanitizer / UBSan
@@ -351,6 +353,11 @@ def ps_merge_states(layout, dev_tables, workspace, out, out_lse=0, stream=0):
 def ps_decode_attention(layout, dev_tables, q, kv_pool, kv_scales, workspace, out, out_lse=0, stream=0):
     _check(_lib().ps_decode_attention(layout, _p(dev_tables), _p(q), _p(kv_pool), _p(kv_scales), _p(workspace),
                                       _p(out), _p(out_lse), _p(stream)), "ps_decode_attention")
+
+
+def ps_decode_attention_static(layout, dev_tables, q, kv_pool, kv_scales, out, out_lse=0, stream=0):
+    _check(_lib().ps_decode_attention_static(layout, _p(dev_tables), _p(q), _p(kv_pool), _p(kv_scales), _p(out),
+                                             _p(out_lse), _p(stream)), "ps_decode_attention_static")
 
 
 def ps_kv_append(layout, dev_tables, new_k, new_v, kv_pool, kv_scales, stream=0):

@@ -10,6 +10,11 @@
 #include <cstring>
 #include <new>
 
+// Partial-state workspace for callers that cannot allocate (ps_decode_attention_static): part of the library's device
+// image, so every GPU the library runs on holds one copy at its own address until the process ends.  In host code
+// this name only stands for the symbol; its device address comes from hipGetSymbolAddress (static_workspace below).
+static __device__ __align__(256) unsigned char scratch[PS_STATIC_WORKSPACE_BYTES];
+
 struct ps_layout::upload_staging {
   void* buffer[2] = {nullptr, nullptr};   // pinned host memory
   size_t capacity[2] = {0, 0};
@@ -80,6 +85,22 @@ int32_t current_device_num_cus() {
 const struct HookInstaller {
   HookInstaller() { ps_device_num_cus_hook = current_device_num_cus; }
 } g_hook_installer;
+
+// Device address of `scratch` on the current device, resolved once per device with that device current.
+int32_t static_workspace(void** out) {
+  static std::atomic<void*> resolved[kMaxDevices];
+  int dev = -1;
+  if (int32_t st = check_hip(hipGetDevice(&dev))) return st;
+  if (dev < 0 || dev >= kMaxDevices) return PS_ERR_UNSUPPORTED;
+  void* ptr = resolved[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    if (int32_t st = check_hip(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)))) return st;
+    if (!ptr) return PS_ERR_DEVICE;
+    resolved[dev].store(ptr, std::memory_order_release);
+  }
+  *out = ptr;
+  return PS_OK;
+}
 
 enum class WorkSet { kPrefix, kSuffix, kAll };
 
@@ -267,6 +288,17 @@ int32_t ps_decode_attention(const ps_layout* lay, const void* dev_tables, const 
   if (lay && lay->num_requests && !out) return PS_ERR_INVALID_ARG;
   if (int32_t rc = ps_prefix_suffix_attention(lay, dev_tables, q, kv_pool, kv_scales, workspace, stream)) return rc;
   return ps_merge_states(lay, dev_tables, workspace, out, out_lse, stream);
+}
+
+int32_t ps_decode_attention_static(const ps_layout* lay, const void* dev_tables, const void* q, const void* kv_pool,
+                                   const float* kv_scales, void* out, float* out_lse, void* stream) {
+  if (!lay) return PS_ERR_INVALID_ARG;
+  if (ps_workspace_bytes(lay) > PS_STATIC_WORKSPACE_BYTES) return PS_ERR_TOO_LARGE;
+  void* workspace = nullptr;
+  if (int32_t st = static_workspace(&workspace)) return st;
+  // the same launches as ps_decode_attention, with the library's own buffer as the workspace (a kernel argument like
+  // any other device pointer); nothing here or below allocates
+  return ps_decode_attention(lay, dev_tables, q, kv_pool, kv_scales, workspace, out, out_lse, stream);
 }
 
 }  // extern "C"

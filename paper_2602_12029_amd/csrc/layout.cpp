@@ -991,6 +991,7 @@ const char* ps_strerror(int32_t status) {
     case PS_ERR_REFCOUNT: return "refcount underflow or double release";
     case PS_ERR_UNSUPPORTED: return "no kernel for this dtype / head_dim / block_size combination";
     case PS_ERR_DEVICE: return "HIP call failed (see ps_last_hip_error)";
+    case PS_ERR_TOO_LARGE: return "the batch's partial states exceed the library's static workspace (PS_STATIC_WORKSPACE_BYTES)";
     default: return "unknown status";
   }
 }
