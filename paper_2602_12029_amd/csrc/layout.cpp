@@ -82,7 +82,7 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   const int64_t ideal = std::max<int64_t>(1, ceil_div(total, int64_t(num_cus)));
   auto pick = [&](int32_t asked) -> int64_t {
     if (asked > 0) return round_up(asked, granule);
-    return std::min<int64_t>(std::max<int64_t>(round_up(ideal, granule), round_up(256, granule)), round_up(4096, granule));
+    return std::min<int64_t>(std::max<int64_t>(round_up(ideal, granule), round_up(256, granule)), round_up(kPsMfmaMaxChunk, granule));
   };
   auto resolve = [&](int32_t v) { return v == PS_VARIANT_AUTO ? (mfma_ok ? PS_VARIANT_MFMA : PS_VARIANT_WAVE) : v; };
   const int64_t mfma_cap = std::max<int64_t>(granule, kPsMfmaMaxChunk / granule * granule);

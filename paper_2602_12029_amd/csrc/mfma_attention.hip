@@ -66,11 +66,23 @@ struct ItemCtx {
   int64_t head_base;   // address of the item's KV head slice in block 0
 };
 
-// Per-lane metadata of an item: block ids (and e4m3 scales) of this wave's tiles.
+// Per-lane metadata of an item: block ids (and e4m3 scales) of this wave's tiles.  Lane 2 k + h of word r describes
+// 16-token block h of the wave's tile 32 r + k, so an item holds up to 64 tiles per wave (kPsMfmaMaxChunk tokens).
 struct ItemMeta {
-  int ids;
-  float ksc, lvs;   // e4m3: K scale and log2 of the V scale of the block (1 and 0 otherwise)
+  int ids[2];
+  float ksc[2], lvs[2];   // e4m3: K scale and log2 of the V scale of the block (1 and 0 otherwise)
 };
+constexpr ItemMeta kNoMeta = {{0, 0}, {1.f, 1.f}, {0.f, 0.f}};
+// entry (k, b) of a metadata word pair: the wave's tile k, block b (k is wave-uniform)
+__device__ __forceinline__ int meta_pick(const int (&word)[2], int k, int b) {
+  const int lo = __builtin_amdgcn_readlane(word[0], ((2 * k) & 63) + b), hi = __builtin_amdgcn_readlane(word[1], ((2 * k) & 63) + b);
+  return (k & 32) ? hi : lo;
+}
+__device__ __forceinline__ float meta_pick(const float (&word)[2], int k, int b) {
+  const int lo = __builtin_amdgcn_readlane(__float_as_int(word[0]), ((2 * k) & 63) + b);
+  const int hi = __builtin_amdgcn_readlane(__float_as_int(word[1]), ((2 * k) & 63) + b);
+  return __int_as_float((k & 32) ? hi : lo);
+}
 
 // K rows reach the lanes in whole 128-byte lines: one load instruction covers 8 tokens, 8 lanes each -- lane (n, kg)
 // takes 16 bytes at chunk (n >> 3) + 2 kg of the line, for token 8 T + (n & 7).  (Fetching 16 bytes per lane for token n
@@ -172,19 +184,22 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
     return c;
   };
 
-  // block ids (and scales) of this wave's tiles of an item: lane 2k+h <- 16-token block h of tile k
+  // block ids (and scales) of this wave's tiles of an item: lane 2k+h of word r <- 16-token block h of tile 32 r + k
   auto fetch_meta = [&](const ItemCtx& c) {
-    ItemMeta m{0, 1.f, 0.f};
-    const int k = lane >> 1;
-    const int sub = c.sub0 + 2 * (wave + kWaves * k) + (lane & 1);
-    if (k < c.my_tiles && sub < c.sub_end) {
-      m.ids = p.blk[c.blk_off + (sub >> sub_shift)];
-      if constexpr (KVT == PS_FP8_E4M3) {
-        // K and V scale of the (block, head) as one 8-byte load: the addresses differ from lane to lane, so every
-        // load instruction here costs a cache lookup per lane
-        const u32x2 sc = *reinterpret_cast<const u32x2*>(p.scales + (int64_t(m.ids) * p.num_kv_heads + c.kv_head) * 2);
-        m.ksc = __uint_as_float(sc.x);
-        m.lvs = __builtin_amdgcn_logf(__uint_as_float(sc.y));   // log2
+    ItemMeta m = kNoMeta;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      const int k = 32 * r + (lane >> 1);
+      const int sub = c.sub0 + 2 * (wave + kWaves * k) + (lane & 1);
+      if (k < c.my_tiles && sub < c.sub_end) {
+        m.ids[r] = p.blk[c.blk_off + (sub >> sub_shift)];
+        if constexpr (KVT == PS_FP8_E4M3) {
+          // K and V scale of the (block, head) as one 8-byte load: the addresses differ from lane to lane, so every
+          // load instruction here costs a cache lookup per lane
+          const u32x2 sc = *reinterpret_cast<const u32x2*>(p.scales + (int64_t(m.ids[r]) * p.num_kv_heads + c.kv_head) * 2);
+          m.ksc[r] = __uint_as_float(sc.x);
+          m.lvs[r] = __builtin_amdgcn_logf(__uint_as_float(sc.y));   // log2
+        }
       }
     }
     return m;
@@ -242,12 +257,11 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
   constexpr int kPolicy = STREAM ? kNonTemporal : 0;
   auto load_item_tile = [&](TileRegs<KVT>& tr, const ItemCtx& c, const ItemMeta& m, int k, bool live) {
     const int sub_a = c.sub0 + 2 * (wave + kWaves * k);
-    const int idx = (2 * k) & 63;
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
       const int sub = sub_a + b;
       const bool valid = live && k < c.my_tiles && sub < c.sub_end;
-      const int id = __builtin_amdgcn_readlane(m.ids, idx + b);
+      const int id = meta_pick(m.ids, k & 63, b);
       const int64_t addr = c.head_base + int64_t(id) * blk_bytes + (sub & sub_mask) * sub_bytes;
       // a descriptor of size zero fetches nothing and returns zeros, whatever its base
       const __amdgpu_buffer_rsrc_t rs =
@@ -298,8 +312,8 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
     if constexpr (KVT == PS_FP8_E4M3) {
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
-        sc_k[b] *= __int_as_float(__builtin_amdgcn_readlane(__float_as_int(meta.ksc), 2 * k + b));
-        lvs[b] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(meta.lvs), 2 * k + b));
+        sc_k[b] *= meta_pick(meta.ksc, k, b);
+        lvs[b] = meta_pick(meta.lvs, k, b);
         inv_v[b] = fast_exp2(-lvs[b]);
       }
     }
@@ -379,36 +393,55 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
         }
       }
     }
-    // V rows of this lane's 8 tokens as bf16, invalid tokens zeroed (their slots may hold anything)
-    u32x4 vr[8];
+    // V rows of this lane's 8 tokens, invalid tokens zeroed (their slots may hold anything)
+    std::remove_reference_t<decltype(tr.v[0])> vraw[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      if constexpr (KVT == PS_BF16) vr[i] = tr.v[i];
-      else vr[i] = e4m3x8_to_bf16x8(tr.v[i].x, tr.v[i].y);
-    }
+    for (int i = 0; i < 8; ++i) vraw[i] = tr.v[i];
     if (!full) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
         const int tok = tok0 + 16 * (i >> 2) + 4 * kg + (i & 3);
-        if (tok >= c.tok_end) vr[i] = u32x4{0, 0, 0, 0};
+        if (tok >= c.tok_end) vraw[i] = std::remove_reference_t<decltype(tr.v[0])>{};
       }
     }
     // ... then O^T += V^T P^T, one 16-column group of V at a time, transposed inside the lane:
     // vt = column cc of this lane's 8 token rows
-#pragma unroll
-    for (int cc = 0; cc < 8; ++cc) {
-      uint32_t w[4];
-#pragma unroll
-      for (int i2 = 0; i2 < 4; ++i2) {
-        // low (even cc) or high (odd cc) halves of a pair of token rows: one byte permute
-        const uint32_t a = vr[2 * i2][cc >> 1], b = vr[2 * i2 + 1][cc >> 1];
-        w[i2] = __builtin_amdgcn_perm(b, a, (cc & 1) ? 0x07060302u : 0x05040100u);
-      }
+    // (every row tile, used or not: the probabilities of an unused one are zero.  A uniform branch around single
+    // matrix instructions here splits the products into many small basic blocks, and one such build returned wrong
+    // sums for items that use fewer row tiles than the kernel carries -- the straight-line form is the one tested)
+    auto accumulate = [&](int cc, const uint32_t (&w)[4]) {
       const bf16x8 vt = as_bf16x8(u32x4{w[0], w[1], w[2], w[3]});
 #pragma unroll
-      for (int t = 0; t < NT; ++t)
-        if (kAllRows || t < c.nt_used)
-          acc[t][cc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, pb[t], acc[t][cc], 0, 0, 0);
+      for (int t = 0; t < NT; ++t) acc[t][cc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, pb[t], acc[t][cc], 0, 0, 0);
+    };
+    if constexpr (KVT == PS_BF16) {
+#pragma unroll
+      for (int cc = 0; cc < 8; ++cc) {
+        uint32_t w[4];
+#pragma unroll
+        for (int i2 = 0; i2 < 4; ++i2) {
+          // low (even cc) or high (odd cc) halves of a pair of token rows: one byte permute
+          const uint32_t a = vraw[2 * i2][cc >> 1], b = vraw[2 * i2 + 1][cc >> 1];
+          w[i2] = __builtin_amdgcn_perm(b, a, (cc & 1) ? 0x07060302u : 0x05040100u);
+        }
+        accumulate(cc, w);
+      }
+    } else {
+      // e4m3: the transposition is done on the codes, before the conversion -- one byte permute gathers columns
+      // (cc, cc + 1) of a pair of token rows, and each half of it converts into one operand register
+#pragma unroll
+      for (int cp = 0; cp < 4; ++cp) {
+        uint32_t w0[4], w1[4];
+#pragma unroll
+        for (int i2 = 0; i2 < 4; ++i2) {
+          const uint32_t a = vraw[2 * i2][cp >> 1], b = vraw[2 * i2 + 1][cp >> 1];
+          const uint32_t pair = __builtin_amdgcn_perm(b, a, (cp & 1) ? 0x07030602u : 0x05010400u);
+          w0[i2] = e4m3x2_to_bf16x2(pair, false);
+          w1[i2] = e4m3x2_to_bf16x2(pair, true);
+        }
+        accumulate(2 * cp, w0);
+        accumulate(2 * cp + 1, w1);
+      }
     }
   };
 
@@ -487,7 +520,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
   store_q(load_q(q_row_index(cur)));
   bool has_next = j_first + 1 < j_last;
   ItemCtx nxt = cur;
-  ItemMeta meta_nxt{0, 1.f, 0.f};
+  ItemMeta meta_nxt = kNoMeta;
   QIndex<NT> q_idx_nxt{};
   RowLimit<NT> lim_nxt{};
   if (has_next) {
@@ -504,7 +537,7 @@ __global__ __launch_bounds__(256, OCC) void mfma_attention_kernel(AttnParams p, 
     if (has_next) q_nxt = load_q(q_idx_nxt);
     const bool has_nn = j + 2 < j_last;
     ItemCtx nn = nxt;
-    ItemMeta meta_nn{0, 1.f, 0.f};
+    ItemMeta meta_nn = kNoMeta;
     QIndex<NT> q_idx_nn{};
     RowLimit<NT> lim_nn{};
     if (has_nn) {

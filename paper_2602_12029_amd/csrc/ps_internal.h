@@ -115,7 +115,7 @@ inline int ps_mfma_occupancy(int max_rows, int kv_dtype) {
   if (max_rows <= 32 && kv_dtype == PS_FP8_E4M3) return 2;
   return 1;
 }
-constexpr int kPsMfmaMaxChunk = 4096;  // tokens per MFMA work item (32 tiles per wave)
+constexpr int kPsMfmaMaxChunk = 8192;  // tokens per MFMA work item (64 tiles per wave: their block ids fill two registers)
 
 // Compute units of the current device, or 0 if none can be asked.  Null in a build without the device side of the
 // library (the planner then assumes kPsDefaultNumCus); abi.hip installs it when the library is loaded.
