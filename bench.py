@@ -3,10 +3,13 @@
 
 A step is one ps_decode_attention call (prefix pass, suffix pass, merge) over one synthetic batch
 with all inputs resident in HBM.  Steps rotate over several copies of the KV pool so that no step
-finds its KV in the last-level cache.  Prints one JSON line:
-  value     ideal-byte GB/s of the whole step (shared KV counted once + private KV + Q + O)
-  roofline  the attention kernel alone, timed with HIP events on its stream inside the timed loop
+finds its KV in the last-level cache.  The default workload is `mixed`, the largest of the benchmark
+configurations.  Prints one JSON line:
+  value     ideal-byte GB/s of the whole step (shared KV counted once + private KV + Q + O), wall clock over
+            exactly --steps steps; ms_per_step_median / value_at_median come from an event-bracketed loop after it
+  roofline  the attention launch alone, timed with HIP events on its stream (at least 20 brackets)
   cpu_baseline  the fp64 numpy oracle on a bounded sample of the same workload, on this host
+  per_config    the same step on b8, long, mixed and fp8_70b (short runs, no oracle leg)
 """
 import argparse
 import ctypes
