@@ -497,9 +497,12 @@ def main_prefill(args):
     print(json.dumps(line))
 
 
-def main_loop(args):
+def measure_loop(args, name, steps, warmup, random_kv=False):
     """A multi-step decode loop: per step one token is appended to every private segment (host tables, upload, the
-    store of the new K/V) and one decode-attention call follows, all on one stream, the host never waiting for the GPU."""
+    store of the new K/V) and one decode-attention call follows, all on one stream, the host never waiting for the GPU.
+    random_kv: fill the pool on the device with random bits instead of the workload's generated K/V (the step's time
+    does not depend on the values; used for the per_config map, where generating `mixed` a second time would cost a
+    minute of host time)."""
     import torch
     import workloads as wl
     from paper_2602_12029_amd import binding as B
@@ -508,25 +511,33 @@ def main_loop(args):
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     dev = "cuda:0"
-    w = wl.named_workload(args.workload, args.seed, args.models or None)
+    w = wl.named_workload(name, args.seed, args.models or None)
     g = w.geometry
     R = w.num_requests
-    total_steps = args.warmup + args.steps
+    total_steps = warmup + steps
     extra = R * (total_steps // g.block_size + 2)                       # blocks the appends may take
     geo = B.geometry(g.num_q_heads, g.num_kv_heads, g.head_dim, g.block_size, g.q_dtype, g.kv_dtype)
     order = np.concatenate([np.asarray(w.free_order, np.int32), np.arange(w.num_blocks, w.num_blocks + extra, dtype=np.int32)])
     pool = B.ps_pool_create(w.num_blocks + extra, order)
     layout = B.ps_kv_layout(pool, geo, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
     tables = B.ps_layout_tables(layout, w.num_prompts, R)
-    data = wl.fill_pool(w, tables["prefix_blk_indptr"], tables["prefix_blk"], tables["suffix_blk_indptr"], tables["suffix_blk"])
-    kv_filled = to_device(data.kv, g.kv_dtype, dev)
-    per_block = kv_filled.numel() // w.num_blocks
-    kv = torch.zeros((w.num_blocks + extra) * per_block, dtype=kv_filled.dtype, device=dev)
-    kv[:kv_filled.numel()] = kv_filled.reshape(-1)
+    per_block = g.num_kv_heads * 2 * g.block_size * g.head_dim
     scales = None
-    if data.scales is not None:
-        scales = torch.ones((w.num_blocks + extra, g.num_kv_heads, 2), dtype=torch.float32, device=dev)
-        scales[:w.num_blocks] = torch.from_numpy(data.scales).to(dev)
+    if random_kv:
+        n_el = (w.num_blocks + extra) * per_block
+        if g.kv_dtype == "fp8_e4m3":
+            kv = torch.randint(0, 120, (n_el,), dtype=torch.uint8, device=dev)          # finite e4m3 codes
+            scales = torch.ones((w.num_blocks + extra, g.num_kv_heads, 2), dtype=torch.float32, device=dev)
+        else:
+            kv = torch.randn(n_el, device=dev).to(torch.bfloat16 if g.kv_dtype == "bf16" else torch.float32)
+    else:
+        data = wl.fill_pool(w, tables["prefix_blk_indptr"], tables["prefix_blk"], tables["suffix_blk_indptr"], tables["suffix_blk"])
+        kv_filled = to_device(data.kv, g.kv_dtype, dev)
+        kv = torch.zeros((w.num_blocks + extra) * per_block, dtype=kv_filled.dtype, device=dev)
+        kv[:kv_filled.numel()] = kv_filled.reshape(-1)
+        if data.scales is not None:
+            scales = torch.ones((w.num_blocks + extra, g.num_kv_heads, 2), dtype=torch.float32, device=dev)
+            scales[:w.num_blocks] = torch.from_numpy(data.scales).to(dev)
     q = to_device(w.q_bits(), g.q_dtype, dev)
     out = torch.empty_like(q)
     gen = torch.Generator(device=dev).manual_seed(args.seed)
@@ -567,34 +578,43 @@ def main_loop(args):
         consumed[i].record(compute)
         host_all[0] += time.perf_counter() - h0
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step()
     torch.cuda.synchronize()
     host_s = 0.0
     host_all[0] = 0.0
-    bytes0 = wl.ideal_bytes(w) + R * args.warmup * g.token_bytes
+    bytes0 = wl.ideal_bytes(w) + R * warmup * g.token_bytes
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step()
     torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    ideal = bytes0 + R * g.token_bytes * (args.steps + 1) / 2            # mean over the timed steps: one more token per request and step
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+    ideal = bytes0 + R * g.token_bytes * (steps + 1) / 2            # mean over the timed steps: one more token per request and step
     value = ideal / (ms_per_step * 1e-3) / 1e9
     line = {
         "metric": "decode loop (append + decode attention per step): ideal-byte HBM GB/s + queries/sec",
         "value": value, "unit": "GB/s", "pct_of_peak_hbm": 100.0 * value / PEAK_HBM_GBS,
-        "queries_per_s": R / (ms_per_step * 1e-3), "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "host_ms_per_step": host_s * 1e3 / args.steps,
-        "host_enqueue_ms_per_step": host_all[0] * 1e3 / args.steps,
+        "queries_per_s": R / (ms_per_step * 1e-3), "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": ms_per_step, "host_ms_per_step": host_s * 1e3 / steps,
+        "host_enqueue_ms_per_step": host_all[0] * 1e3 / steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {"bf16": "bf16", "fp8_e4m3": "u8", "f32": "f32"}[g.kv_dtype], "data": "synthetic",
-        "config": {"workload": args.workload, "path": "loop", "requests": R, "mean_ideal_bytes": ideal,
+        "config": {"workload": name, "path": "loop", "requests": R, "mean_ideal_bytes": ideal,
                    "note": "host_ms_per_step = ps_layout_append; the tables go up on a copy stream into two device buffers "
                            "used alternately, so the upload of a step overlaps with the kernels of the step before"},
         "roofline": {"bound": "hbm", "achieved": value, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": value / PEAK_HBM_GBS,
                      "traffic": None, "kernel": "whole step (append store + attention + merge), wall clock"},
     }
-    print(json.dumps(line))
+    torch.cuda.synchronize()
+    B.ps_layout_release(pool, layout)
+    B.ps_pool_destroy(pool)
+    del kv, tabs, wsp
+    torch.cuda.empty_cache()
+    return line
+
+
+def main_loop(args):
+    print(json.dumps(measure_loop(args, args.workload, args.steps, args.warmup)))
 
 
 def read_ceiling_gbs(stream, nbytes=1 << 30):
@@ -823,6 +843,10 @@ def main():
                          "roofline_frac": rf["frac"], "kernel_ms": rf.get("kernel_ms"),
                          "kernel_ms_median": rf.get("kernel_ms_median"),
                          "read_ceiling_frac": (rf.get("read_ceiling") or {}).get("frac_of_it")}
+            # the multi-step decode loop on the same batch (append on the host, table upload, ps_kv_append, the step)
+            lp = measure_loop(args, name, max(args.steps, 50), max(args.warmup, 10), random_kv=True)
+            per[name]["loop"] = {"ms_per_step": lp["ms_per_step"], "value": lp["value"], "unit": "GB/s",
+                                 "host_append_ms_per_step": lp["host_ms_per_step"]}
         line["per_config"] = per
     print(json.dumps(line))
 
