@@ -645,7 +645,10 @@ def main_probe(args):
     patterns = {0: "16 B per lane, 1 KiB contiguous per instruction",
                 1: "16 B per lane, 16 rows x 64 B of 128-byte rows (half lines)",
                 2: "16 B per lane, 16 rows x 64 B of 256-byte rows (half lines)",
-                3: "8 B per lane, 512 B contiguous per instruction"}
+                3: "8 B per lane, 512 B contiguous per instruction",
+                4: "16 B per lane, 1 KiB per instruction, 2 KiB chunks in scrambled order",
+                5: "16 B per lane, 1 KiB per instruction, 4 KiB chunks in scrambled order",
+                6: "16 B per lane, 1 KiB per instruction, 8 KiB chunks in scrambled order"}
     steps = max(1, min(args.steps, 20))
     ev = HipEvents(steps)
     rates = {}

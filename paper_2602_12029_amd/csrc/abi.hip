@@ -275,7 +275,7 @@ int32_t ps_kv_stage_in(const ps_layout* lay, const void* dev_tables, const void*
 }
 
 int32_t ps_probe_read(const void* dev_buf, int64_t bytes, int32_t pattern, int32_t num_workgroups, void* stream) {
-  if (!dev_buf || bytes < 0 || num_workgroups <= 0 || num_workgroups > 65536 || pattern < 0 || pattern > 3 ||
+  if (!dev_buf || bytes < 0 || num_workgroups <= 0 || num_workgroups > 65536 || pattern < 0 || pattern > 6 ||
       reinterpret_cast<uintptr_t>(dev_buf) % 16 != 0)
     return PS_ERR_INVALID_ARG;
   if (int32_t rc = psdev::launch_probe_read(dev_buf, bytes, pattern, num_workgroups, static_cast<hipStream_t>(stream)))

@@ -18,6 +18,9 @@ namespace {
 //      asked for twice) -- lane (n, kg): row 16 r + n, byte 64 s + 16 kg
 //   2: the same over 32 rows of 256 B (an instruction takes 16 rows x 64 B, four instructions per 16 rows)
 //   3: 16 x 8-byte loads, each instruction 512 B contiguous
+//   4, 5, 6: the loads of pattern 0, but the buffer is taken in chunks of 2, 4 or 8 KiB in a scrambled order (chunk
+//      index times an odd constant, modulo the power-of-two chunk count): what block-granular scatter of the KV pool
+//      costs by itself, at the chunk sizes a (block, head) record of K or V has
 template <int PATTERN>
 __global__ __launch_bounds__(256) void probe_read_kernel(const char* __restrict__ buf, int64_t n_units) {
   const int lane = threadIdx.x & 63, n = lane & 15, kg = lane >> 4;
@@ -25,7 +28,19 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const char* __restrict_
   u32x4 acc = {0, 0, 0, 0};
   for (int64_t u = wave; u < n_units; u += n_waves) {
     const char* base = buf + u * 8192;
-    if constexpr (PATTERN == 3) {
+    if constexpr (PATTERN >= 4) {
+      constexpr int kChunk = 2048 << (PATTERN - 4), kPerUnit = 8192 / kChunk;
+      const int64_t mask = n_units * kPerUnit - 1;   // the launcher checks that the chunk count is a power of two
+      u32x4 v[8];
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const int64_t chunk = ((u * kPerUnit + i * 1024 / kChunk) * 0x9E3779B1ll) & mask;
+        v[i] = __builtin_nontemporal_load(
+            reinterpret_cast<const u32x4*>(buf + chunk * kChunk + (i * 1024) % kChunk + lane * 16));
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc ^= v[i];
+    } else if constexpr (PATTERN == 3) {
       u32x2 v[16];
 #pragma unroll
       for (int i = 0; i < 16; ++i)
@@ -65,6 +80,12 @@ int32_t launch_probe_read(const void* buf, int64_t bytes, int pattern, int num_w
     case 1: hipLaunchKernelGGL(probe_read_kernel<1>, grid, block, 0, st, b, n_units); break;
     case 2: hipLaunchKernelGGL(probe_read_kernel<2>, grid, block, 0, st, b, n_units); break;
     case 3: hipLaunchKernelGGL(probe_read_kernel<3>, grid, block, 0, st, b, n_units); break;
+    case 4: case 5: case 6:
+      if (n_units & (n_units - 1)) return PS_ERR_INVALID_ARG;
+      if (pattern == 4) hipLaunchKernelGGL(probe_read_kernel<4>, grid, block, 0, st, b, n_units);
+      else if (pattern == 5) hipLaunchKernelGGL(probe_read_kernel<5>, grid, block, 0, st, b, n_units);
+      else hipLaunchKernelGGL(probe_read_kernel<6>, grid, block, 0, st, b, n_units);
+      break;
     default: return PS_ERR_INVALID_ARG;
   }
   return PS_OK;
