@@ -5,18 +5,24 @@
 // tokens.  With G q heads per KV head a chunk of c new tokens is c * G rows per KV head -- hundreds, where a decode
 // step has a few dozen -- so the work is a dense contraction and the matrix cores, not HBM, are the bound.
 //
-// One workgroup (4 waves) takes one work item: a token range of one context and KV head, and up to 256 query rows
-// that see into it.  The rows are split over the waves, 64 each, and every wave walks the whole token range, so a
-// wave never shares anything with its neighbours: no barrier, no cross-wave merge.  The four waves read the same
-// K/V tiles at nearly the same time, so HBM (and mostly L2) sees each tile once per 256 rows.  A wave's query rows
-// are kept as ready-made MFMA B operands, 16 bytes per lane and piece, in a lane-private corner of LDS (every lane
-// reads back exactly what it wrote, so no synchronisation is involved; registers hold the accumulators, the tile
-// buffers and the scores of two tiles).
+// One workgroup of eight waves takes one work item: a token range of one context and KV head, and up to 256 query
+// rows that see into it.  The rows are split over the waves, 32 each (two 16-row tiles, the query rows resident in
+// registers as MFMA B operands), and every wave walks the token range.  Two waves share a SIMD, so that the vector
+// work of one (exponentials, conversions) runs under the matrix instructions of the other; a wave on its own issues
+// one instruction every four cycles and cannot cover its own matrix instructions.
 //
-// Per wave and 32-token tile the math is that of the decode kernel (S^T = K Q^T, online softmax with a lazily
-// moving reference, O^T += V^T P^T; K straight into the A layout, V transposed in the lane), over four 16-row
-// tiles.  Tiles past what every row of the wave sees are skipped; the per-row limit is applied only to tiles that
-// reach past the shortest row.
+// K and V reach the waves through LDS, as ready-made A operands: per 32-token tile the eight waves fetch one eighth
+// of it each (K straight in operand layout; V as pairs of token rows, transposed inside the lane with one byte
+// permute per operand register; e4m3 codes converted to bf16 once), write it to a three-stage ring, and after one
+// barrier per tile every wave reads the 8 K and 8 V operands of the tile back, 16 bytes per lane and operand, each
+// lane exactly the slot of its own lane index (no bank conflicts).  A tile is thus fetched, transposed and
+// converted once per 256 rows.  Global loads run three tiles ahead of the products (two tiles in registers, one in
+// LDS).
+//
+// Per wave and tile the math is that of the decode kernel (S^T = K Q^T, online softmax with a lazily moving
+// reference, O^T += V^T P^T).  A wave skips the tiles past what its own rows see; the per-row limit is applied only
+// to tiles that reach past the wave's shortest row.  Nothing but the ring is shared between waves: no cross-wave
+// merge, every wave writes the partial states of its own rows.
 #include <type_traits>
 
 #include "device_common.h"
@@ -28,8 +34,11 @@ namespace psdev {
 namespace {
 
 constexpr int kD = kHeadDim;
-constexpr int kNT = 4;            // 16-row tiles per wave
+constexpr int kWaves = 8;         // per workgroup
+constexpr int kNT = 2;            // 16-row tiles per wave
+constexpr int kRowsPerWave = 16 * kNT;
 constexpr int kTile = kTileTokens;
+constexpr int kStages = 3;        // LDS ring: tile k read, tile k + 1 written, tile k - 1 possibly still read
 constexpr float kLazy = kLazyRescale;
 
 __device__ __forceinline__ int wave_max(int x) {
@@ -41,8 +50,10 @@ __device__ __forceinline__ int wave_max(int x) {
 }  // namespace
 
 template <int KVT>
-__global__ __launch_bounds__(256, 1) void prefill_attention_kernel(AttnParams p, const ps_item* __restrict__ items) {
-  __shared__ u32x4 sm_qb[4][kNT * 4][64];   // [wave][row tile * 4 + k-step][lane]: that lane's B operand
+__global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnParams p, const ps_item* __restrict__ items) {
+  __shared__ u32x4 sm_k[kStages][8][64];   // [stage][4 * block + k-step][lane]: K as that lane's A operand
+  __shared__ u32x4 sm_v[kStages][8][64];   // [stage][16-column group][lane]: V^T as that lane's A operand
+  __shared__ int sm_see[kWaves];
   const ps_item* it = items + blockIdx.x;
   const int blk_off = __builtin_amdgcn_readfirstlane(it->blk_off);
   const int tok_begin = __builtin_amdgcn_readfirstlane(it->tok_begin);
@@ -60,101 +71,133 @@ __global__ __launch_bounds__(256, 1) void prefill_attention_kernel(AttnParams p,
   const int kg = lane >> 4;
   const int G = p.group;
   const int rows = n_req * G;
-  const int row_base = 64 * wave;
-  if (row_base >= rows) return;   // nothing shared between waves: a wave without rows simply leaves
-  const int nt_used = min(kNT, (rows - row_base + 15) >> 4);
+  const int row_base = kRowsPerWave * wave;
+  const int nt_used = max(0, min(kNT, (rows - row_base + 15) >> 4));   // 0: a wave without rows only fetches
   const float neg_inf = -__builtin_inff();
 
   // ---- this lane's query rows (row 16 t + n of the wave): request, visible length, and the row itself as the
-  // four B operands of S^T = K Q^T
+  // four B operands of S^T = K Q^T (k-step st, lane group kg: elements 32 st + 8 kg .. + 7)
   int req_of[kNT], lim[kNT];
+  bf16x8 qb[kNT][4];
   int lim_hi = 0, lim_lo = 0x7fffffff;
 #pragma unroll
   for (int t = 0; t < kNT; ++t) {
     const int row = row_base + 16 * t + n;
     req_of[t] = -1;
     lim[t] = 0;   // a padding row sees nothing
-    u32x4 piece[4] = {u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}, u32x4{0, 0, 0, 0}};
+#pragma unroll
+    for (int st = 0; st < 4; ++st) qb[t][st] = as_bf16x8(u32x4{0, 0, 0, 0});
     if (row < rows) {
       const int req = p.req_list[req_off + row / G];
       req_of[t] = req;
       lim[t] = limited ? min(tok_end, p.visible[req]) : tok_end;
       const uint16_t* qrow = static_cast<const uint16_t*>(p.q) + (int64_t(req) * p.num_q_heads + kv_head * G + row % G) * kD;
 #pragma unroll
-      for (int st = 0; st < 4; ++st) piece[st] = *reinterpret_cast<const u32x4*>(qrow + q_chunk_elem<KVT>(st, kg));
+      for (int st = 0; st < 4; ++st) qb[t][st] = as_bf16x8(*reinterpret_cast<const u32x4*>(qrow + 32 * st + 8 * kg));
       lim_hi = max(lim_hi, lim[t]);
       lim_lo = min(lim_lo, lim[t]);
     }
-#pragma unroll
-    for (int st = 0; st < 4; ++st) sm_qb[wave][4 * t + st][lane] = piece[st];
   }
-  const int see_end = wave_max(lim_hi);      // no row of this wave sees a token at or past this one
-  const int see_all = -wave_max(-lim_lo);    // every row of this wave sees every token before this one
-  if (see_end <= tok_begin) return;          // cannot happen for planned items; keeps the loop bounds honest
-  const int n_tiles = (see_end - tok_begin + kTile - 1) / kTile;
+  const int see_end = max(tok_begin, wave_max(lim_hi));   // no row of this wave sees a token at or past this one
+  const int see_all = -wave_max(-lim_lo);                 // every row of this wave sees every token before this one
+  if (lane == 0) sm_see[wave] = see_end;
+  __syncthreads();
+  int see_end_wg = tok_begin;
+#pragma unroll
+  for (int w = 0; w < kWaves; ++w) see_end_wg = max(see_end_wg, sm_see[w]);
+  see_end_wg = __builtin_amdgcn_readfirstlane(see_end_wg);
+  const int n_tiles_wg = (see_end_wg - tok_begin + kTile - 1) / kTile;   // tiles the workgroup fetches
+  const int n_tiles = nt_used > 0 ? (see_end - tok_begin + kTile - 1) / kTile : 0;   // tiles this wave multiplies
+  const int n_whole = min(n_tiles, max(0, (see_all - tok_begin) / kTile));   // ... of which these need no per-row limit
 
-  // ---- addressing (as in the decode kernel): block base in SGPRs, two loop-invariant VGPR offsets
+  // ---- addressing: block base in SGPRs (a buffer descriptor per 16-token block), loop-invariant lane offsets
   const int sub_shift = __builtin_ctz(unsigned(p.block_size >> 4));
   const int sub_mask = (p.block_size >> 4) - 1;
   constexpr int kEsz = KVT == PS_BF16 ? 2 : 1;
   const int tok_bytes = int(p.s_tok) * kEsz;
   const int kv_bytes = int(p.s_kv) * kEsz;
-  const int k_lane_off = n * tok_bytes + kg * 16;
-  const int v_lane_off = 4 * kg * tok_bytes + n * (8 * kEsz);
   const int64_t head_base = reinterpret_cast<int64_t>(p.kv) + int64_t(kv_head) * p.s_head * kEsz;
-  const int64_t blk_bytes = p.s_block * kEsz;
+  const uint32_t blk_bytes = uint32_t(p.s_block * kEsz);
   const int sub_bytes = 16 * tok_bytes;
   const int sub0 = tok_begin >> 4;
-  const int sub_end = (see_end + 15) >> 4;
+  const int sub_end = (see_end_wg + 15) >> 4;
+  // What this wave fetches of every tile, all of it from one 16-token block (fblk) so that one block id and one
+  // buffer descriptor per tile do.  K: operand (block fblk, k-step kst) -- token n of the block, the 8 elements of
+  // lane group kg.  V: the pair of token rows (2 vp, 2 vp + 1) of the eight a lane group owns (rows 4 kg + i of
+  // block 0, then of block 1), column half vh -- 4 of the lane's 8 columns.
+  const int fblk = wave >> 2, kst = wave & 3;
+  const int vp = 2 * fblk + (wave & 1), vh = (wave >> 1) & 1;
+  const int vi = 2 * (wave & 1);
+  const int k_lane_off = n * tok_bytes + (32 * kst + 8 * kg) * kEsz;
+  const int v_lane_off = kv_bytes + (4 * kg + vi) * tok_bytes + (8 * n + 4 * vh) * kEsz;
+  const int32_t* blk_seg = p.blk + blk_off;
 
-  struct TileIds { int id[2]; float ksc[2], lvs[2]; };
-  auto fetch_ids = [&](int k) __attribute__((always_inline)) {    // block ids (and e4m3 scales) of the two 16-token blocks of tile k; wave-uniform
+  struct TileIds { int id; float ksc[2], lvs[2]; };   // id: of this wave's block of the tile
+  auto fetch_ids = [&](int k) __attribute__((always_inline)) {   // block id (and e4m3 scales) of tile k; wave-uniform
+    // no branch around these loads (the index is clamped into the range instead), so that the counting of
+    // outstanding loads in the streaming loop stays exact; a block past the range is never fetched from
     TileIds r;
+    if constexpr (KVT == PS_BF16) {
+      const int sub = max(sub0, min(sub0 + 2 * k + fblk, sub_end - 1));
+      r.id = __builtin_amdgcn_readfirstlane(blk_seg[sub >> sub_shift]);
+      r.ksc[0] = r.ksc[1] = 1.f;
+      r.lvs[0] = r.lvs[1] = 0.f;
+    } else {
+      int id[2];
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      // no branch around these loads (the index is clamped into the range instead), so that the counting of
-      // outstanding loads in the streaming loop stays exact; a block past the range is never fetched from
-      const int sub = min(sub0 + 2 * k + b, sub_end - 1);
-      r.id[b] = __builtin_amdgcn_readfirstlane(p.blk[blk_off + (sub >> sub_shift)]);
-      r.ksc[b] = 1.f;
-      r.lvs[b] = 0.f;
-      if constexpr (KVT == PS_FP8_E4M3) {
-        const float* sc = p.scales + (int64_t(r.id[b]) * p.num_kv_heads + kv_head) * 2;
+      for (int b = 0; b < 2; ++b) {
+        const int sub = max(sub0, min(sub0 + 2 * k + b, sub_end - 1));
+        id[b] = __builtin_amdgcn_readfirstlane(blk_seg[sub >> sub_shift]);
+        const float* sc = p.scales + (int64_t(id[b]) * p.num_kv_heads + kv_head) * 2;
         r.ksc[b] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(sc[0])));
         r.lvs[b] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(__builtin_amdgcn_logf(sc[1]))));
       }
+      r.id = fblk ? id[1] : id[0];
     }
     return r;
   };
-  // K and V of a tile live in separate buffers, because they are needed at different times (see the loop below).
-  // Every call issues the same loads; a block past the range gets a zero-sized descriptor (zeros, no traffic).
-  struct KTile { u32x4 k[2][KVT == PS_BF16 ? 4 : 2]; };
-  struct VTile { std::conditional_t<KVT == PS_BF16, u32x4, u32x2> v[8]; };
-  auto tile_rsrc = [&](const TileIds& ids, int k, int b) __attribute__((always_inline)) {
-    const int sub = sub0 + 2 * k + b;
-    const bool valid = sub < sub_end;
-    const int64_t addr = head_base + int64_t(ids.id[b]) * blk_bytes + (sub & sub_mask) * sub_bytes;
-    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(addr), 0, valid ? 0x7fffffff : 0, 0x00020000);
+  // this wave's share of a tile, as loaded
+  struct Fetched {
+    std::conditional_t<KVT == PS_BF16, u32x4, u32x2> k;         // 8 elements of one token
+    std::conditional_t<KVT == PS_BF16, u32x2, uint32_t> v[2];   // 4 columns of two token rows
   };
-  auto load_k = [&](KTile& kt, const TileIds& ids, int k) __attribute__((always_inline)) {
-#pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      const __amdgpu_buffer_rsrc_t rs = tile_rsrc(ids, k, b);
-#pragma unroll
-      for (int s = 0; s < (KVT == PS_BF16 ? 4 : 2); ++s)
-        kt.k[b][s] = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off + 64 * s, 0, 0);
+  auto fetch = [&](Fetched& f, const TileIds& ids, int k) __attribute__((always_inline)) {
+    const int sub = sub0 + 2 * k + fblk;
+    const bool valid = sub < sub_end;   // a block past the range gets a zero-sized descriptor: zeros, no traffic
+    const uint64_t addr = uint64_t(head_base) + uint64_t(uint32_t(ids.id)) * blk_bytes + uint32_t((sub & sub_mask) * sub_bytes);
+    const __amdgpu_buffer_rsrc_t rs =
+        __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(addr), 0, valid ? 0x7fffffff : 0, 0x00020000);
+    if constexpr (KVT == PS_BF16) {
+      f.k = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off, 0, 0);
+      f.v[0] = __builtin_amdgcn_raw_buffer_load_b64(rs, v_lane_off, 0, 0);
+      f.v[1] = __builtin_amdgcn_raw_buffer_load_b64(rs, v_lane_off, tok_bytes, 0);
+    } else {
+      f.k = __builtin_amdgcn_raw_buffer_load_b64(rs, k_lane_off, 0, 0);
+      f.v[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, v_lane_off, 0, 0);
+      f.v[1] = __builtin_amdgcn_raw_buffer_load_b32(rs, v_lane_off, tok_bytes, 0);
     }
   };
-  auto load_v = [&](VTile& vt, const TileIds& ids, int k) __attribute__((always_inline)) {
+  // ... and its way into the ring: K as it is (e4m3: converted), V transposed -- register vp of the operand of
+  // column group cc holds column 8 n + cc of the token rows (2 vp, 2 vp + 1)
+  auto publish = [&](const Fetched& f, int stage, int k) __attribute__((always_inline)) {
+    if constexpr (KVT == PS_BF16) sm_k[stage][4 * fblk + kst][lane] = f.k;
+    else sm_k[stage][4 * fblk + kst][lane] = e4m3x8_to_bf16x8(f.k.x, f.k.y);
+    // slots of tokens past the item's range may hold anything: zero them (their probabilities are zero)
+    const int tok = tok_begin + kTile * k + 16 * fblk + 4 * kg + vi;
+    auto v0 = f.v[0], v1 = f.v[1];
+    if (tok >= tok_end) v0 = decltype(v0){};
+    if (tok + 1 >= tok_end) v1 = decltype(v1){};
+    uint32_t* dst = reinterpret_cast<uint32_t*>(&sm_v[stage][4 * vh][lane]) + vp;
+    if constexpr (KVT == PS_BF16) {
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      const __amdgpu_buffer_rsrc_t rs = tile_rsrc(ids, k, b);
+      for (int c = 0; c < 4; ++c)   // low (even column) or high (odd column) halves of the two rows: one byte permute
+        dst[c * 64 * 4] = __builtin_amdgcn_perm(v1[c >> 1], v0[c >> 1], (c & 1) ? 0x07060302u : 0x05040100u);
+    } else {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        if constexpr (KVT == PS_BF16)
-          vt.v[4 * b + i] = __builtin_amdgcn_raw_buffer_load_b128(rs, v_lane_off, kv_bytes + i * tok_bytes, 0);
-        else
-          vt.v[4 * b + i] = __builtin_amdgcn_raw_buffer_load_b64(rs, v_lane_off, kv_bytes + i * tok_bytes, 0);
+      for (int cp = 0; cp < 2; ++cp) {   // the codes of columns (2 cp, 2 cp + 1) of the two rows, then converted
+        const uint32_t pair = __builtin_amdgcn_perm(v1, v0, cp ? 0x07030602u : 0x05010400u);
+        dst[(2 * cp) * 64 * 4] = e4m3x2_to_bf16x2(pair, false);
+        dst[(2 * cp + 1) * 64 * 4] = e4m3x2_to_bf16x2(pair, true);
       }
     }
   };
@@ -169,66 +212,37 @@ __global__ __launch_bounds__(256, 1) void prefill_attention_kernel(AttnParams p,
     for (int c = 0; c < 8; ++c) acc[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 
-  struct Scores { f32x4 s[kNT][2]; };
-  struct KOperands { bf16x8 a[2][4]; };
-  auto k_operands = [&](const KTile& kt) __attribute__((always_inline)) {
-    KOperands ka;
-#pragma unroll
-    for (int b = 0; b < 2; ++b) {
-      if constexpr (KVT == PS_BF16) {
-#pragma unroll
-        for (int s = 0; s < 4; ++s) ka.a[b][s] = as_bf16x8(kt.k[b][s]);
-      } else {
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-          ka.a[b][2 * h] = as_bf16x8(e4m3x8_to_bf16x8(kt.k[b][h].x, kt.k[b][h].y));
-          ka.a[b][2 * h + 1] = as_bf16x8(e4m3x8_to_bf16x8(kt.k[b][h].z, kt.k[b][h].w));
-        }
-      }
-    }
-    return ka;
-  };
-  // The query operands of row tile t, read back from LDS.  (The lane index goes through an empty asm so that they
-  // are read tile by tile: hoisted out of the streaming loop they would occupy 64 registers that the accumulators
-  // and tile buffers need.)
-  struct QOperands { bf16x8 b[4]; };
-  auto q_operands = [&](int t) __attribute__((always_inline)) {
-    int q_lane = lane;
-    asm volatile("" : "+v"(q_lane));
-    QOperands q;
-#pragma unroll
-    for (int st = 0; st < 4; ++st) q.b[st] = as_bf16x8(sm_qb[wave][4 * t + st][q_lane]);
-    return q;
-  };
-  // Raw scores S^T = K Q^T of one tile for row tile t: two accumulation chains (one per 16-token block), issued
-  // alternately.
-  auto qk_row_tile = [&](const KOperands& ka, const QOperands& q, Scores& sc, int t) __attribute__((always_inline)) {
-    sc.s[t][0] = f32x4{0.f, 0.f, 0.f, 0.f};
-    sc.s[t][1] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int st = 0; st < 4; ++st)
-#pragma unroll
-      for (int b = 0; b < 2; ++b) sc.s[t][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka.a[b][st], q.b[st], sc.s[t][b], 0, 0, 0);
-  };
-  auto qk_scores = [&](const KTile& kt, Scores& sc) __attribute__((always_inline)) {
-    const KOperands ka = k_operands(kt);
-#pragma unroll
-    for (int t = 0; t < kNT; ++t) qk_row_tile(ka, q_operands(t), sc, t);
-  };
-
-  // Online softmax of a tile's scores and O^T += V^T P^T, with the scores of the next tile (K in kt_next, result
-  // in sc_next) issued row tile by row tile in between: each batch of eight matrix instructions is followed by the
-  // exponentials of one row tile of this tile, which the vector units work off while the matrix cores are busy.
+  // One tile for this wave's rows, operands from the ring.
   // limited_tag: std::true_type applies the per-row limits (and guards rows that have seen nothing yet);
   // std::false_type promises that every row of the wave sees the whole tile.
-  // bf16 KV: the scores of the next tile are issued row tile by row tile between the exponentials (measured 11 %
-  // faster than issuing them first); e4m3 KV: all of them first, then the softmax (the interleaved order measured
-  // 25 % slower there, next to the conversions of the K codes).
-  constexpr bool kInterleave = KVT == PS_BF16;
-  auto softmax_pv = [&](Scores& sc, const VTile& vtile, const TileIds& ids, int k, const KTile& kt_next, Scores& sc_next,
-                        auto limited_tag) __attribute__((always_inline)) {
+  struct KOperands { u32x4 a[2][4]; };
+  auto read_k = [&](int stage) __attribute__((always_inline)) {   // the 8 K operands of a stage, requested in one go
+    KOperands ka;
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int st = 0; st < 4; ++st) ka.a[b][st] = sm_k[stage][4 * b + st][lane];
+    __builtin_amdgcn_sched_barrier(0);
+    return ka;
+  };
+  struct VOperands { u32x4 a[8]; };
+  auto read_v = [&](int stage) __attribute__((always_inline)) {   // the 8 V operands of a stage, requested in one go
+    VOperands vt;
+#pragma unroll
+    for (int cc = 0; cc < 8; ++cc) vt.a[cc] = sm_v[stage][cc][lane];
+    __builtin_amdgcn_sched_barrier(0);
+    return vt;
+  };
+  // O^T += V^T P^T, one 16-column group of V at a time
+  auto pv = [&](const VOperands& vt, const bf16x8 (&pb)[kNT]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int cc = 0; cc < 8; ++cc)
+#pragma unroll
+      for (int t = 0; t < kNT; ++t)
+        acc[t][cc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vt.a[cc]), pb[t], acc[t][cc], 0, 0, 0);
+  };
+  auto multiply = [&](const KOperands& ka, const TileIds& ids, int stage, int k, auto limited_tag) __attribute__((always_inline)) {
     constexpr bool kLimited = decltype(limited_tag)::value;
-    if constexpr (!kInterleave) qk_scores(kt_next, sc_next);
     const int tok0 = tok_begin + kTile * k;
     float sc_k[2], lvs[2], inv_v[2];
 #pragma unroll
@@ -237,6 +251,22 @@ __global__ __launch_bounds__(256, 1) void prefill_attention_kernel(AttnParams p,
       lvs[b] = ids.lvs[b];
       inv_v[b] = KVT == PS_FP8_E4M3 ? fast_exp2(-lvs[b]) : 1.f;
     }
+    // raw scores S^T = K Q^T: per row tile two accumulation chains (one per 16-token block)
+    f32x4 s[kNT][2];
+#pragma unroll
+    for (int t = 0; t < kNT; ++t)
+#pragma unroll
+      for (int b = 0; b < 2; ++b) s[t][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int st = 0; st < 4; ++st)
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int t = 0; t < kNT; ++t)
+          s[t][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka.a[b][st]), qb[t][st], s[t][b], 0, 0, 0);
+    // the V operands are requested now, all eight, so that they arrive under the softmax (left to itself the
+    // compiler requests each one right before its products, and the wave sits out the LDS latency eight times)
+    const VOperands vt = read_v(stage);
     if constexpr (kLimited) {
 #pragma unroll
       for (int t = 0; t < kNT; ++t)
@@ -244,131 +274,148 @@ __global__ __launch_bounds__(256, 1) void prefill_attention_kernel(AttnParams p,
         for (int b = 0; b < 2; ++b)
 #pragma unroll
           for (int j = 0; j < 4; ++j)
-            if (tok0 + 16 * b + 4 * kg + j >= lim[t]) sc.s[t][b][j] = neg_inf;
+            if (tok0 + 16 * b + 4 * kg + j >= lim[t]) s[t][b][j] = neg_inf;
     }
     // The softmax reference m_run follows the row maximum lazily: it moves (and the accumulators are rescaled)
     // only when some score gets more than kLazy ahead of it, so probabilities stay below 2^kLazy instead of below 1
     // -- the same result by shift invariance of softmax.  The test is local to the lane (its own scores, in log2
-    // units; the scales are positive, so a block's maximum scales like its scores) and one vote covers the four
-    // row tiles; only when it fires somewhere in the wave is the maximum of each row put together across the
-    // row's four lanes, which must agree on m_run.  A row that has seen nothing yet has m_run = -inf and stays
-    // there until a score arrives.
-    float mx[kNT];
-    bool ahead = false;
+    // units; the scales are positive, so a block's maximum scales like its scores) and one vote covers the row
+    // tiles; only when it fires somewhere in the wave is the maximum of each row put together across the row's
+    // four lanes, which must agree on m_run.  A row that has seen nothing yet has m_run = -inf and stays there
+    // until a score arrives.
+    // Where no per-row limit applies the test is made on the exponents themselves (score minus reference, which the
+    // probabilities need anyway): one exceeds kLazy exactly when its score is that far ahead, and a row that has
+    // seen nothing yet (reference -inf) gets +inf there and votes too.  Only the rare branch goes back to the raw
+    // scores, and recomputes the exponents against the new reference.
+    auto raw_max = [&](int t) { return fmaxf(max_of4(s[t][0]) * sc_k[0], max_of4(s[t][1]) * sc_k[1]); };
+    auto move_reference = [&](int t, float mx) __attribute__((always_inline)) {
+      float row_mx = fmaxf(mx, lane_xor(mx, 16));
+      row_mx = fmaxf(row_mx, lane_xor(row_mx, 32));
+      const float m_new = (row_mx > m_run[t] + kLazy) ? row_mx : m_run[t];
+      const float alpha = (m_new == m_run[t]) ? 1.f : fast_exp2(m_run[t] - m_new);   // -inf -> finite gives 0
+      l_run[t] *= alpha;
 #pragma unroll
-    for (int t = 0; t < kNT; ++t) {
-      if constexpr (KVT == PS_BF16)   // (the shorter max_of4 form makes this variant spill and run 25 % slower)
-        mx[t] = fmaxf(fmaxf(fmaxf(sc.s[t][0][0], sc.s[t][0][1]), fmaxf(sc.s[t][0][2], sc.s[t][0][3])) * sc_k[0],
-                      fmaxf(fmaxf(sc.s[t][1][0], sc.s[t][1][1]), fmaxf(sc.s[t][1][2], sc.s[t][1][3])) * sc_k[1]);
-      else
-        mx[t] = fmaxf(max_of4(sc.s[t][0]) * sc_k[0], max_of4(sc.s[t][1]) * sc_k[1]);
-      ahead |= mx[t] > m_run[t] + kLazy;
-    }
-    if (__builtin_amdgcn_ballot_w64(ahead) != 0) {
+      for (int cc = 0; cc < 8; ++cc) acc[t][cc] *= alpha;
+      m_run[t] = m_new;
+    };
+    f32x4 e[kNT][2];   // exponents: score in log2 units, plus log2 of the block's V scale, minus the reference
+    if constexpr (kLimited) {
+      float mx[kNT];
+      bool ahead = false;
 #pragma unroll
       for (int t = 0; t < kNT; ++t) {
-        float row_mx = fmaxf(mx[t], lane_xor(mx[t], 16));
-        row_mx = fmaxf(row_mx, lane_xor(row_mx, 32));
-        const float m_new = (row_mx > m_run[t] + kLazy) ? row_mx : m_run[t];
-        const float alpha = (m_new == m_run[t]) ? 1.f : fast_exp2(m_run[t] - m_new);   // -inf -> finite gives 0
-        l_run[t] *= alpha;
-#pragma unroll
-        for (int cc = 0; cc < 8; ++cc) acc[t][cc] *= alpha;
-        m_run[t] = m_new;
+        mx[t] = raw_max(t);
+        ahead |= mx[t] > m_run[t] + kLazy;
       }
-    }
-    KOperands ka_next;
-    QOperands q_cur;
-    if constexpr (kInterleave) {
-      ka_next = k_operands(kt_next);
-      q_cur = q_operands(0);
+      if (__builtin_amdgcn_ballot_w64(ahead) != 0) {
+#pragma unroll
+        for (int t = 0; t < kNT; ++t) move_reference(t, mx[t]);
+      }
+#pragma unroll
+      for (int t = 0; t < kNT; ++t) {
+        const float m_ref = (m_run[t] == neg_inf) ? 0.f : m_run[t];   // keeps (-inf) - (-inf) out of the exponents
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) e[t][b][j] = __builtin_fmaf(s[t][b][j], sc_k[b], lvs[b] - m_ref);
+      }
+    } else {
+      bool ahead = false;
+#pragma unroll
+      for (int t = 0; t < kNT; ++t) {
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) e[t][b][j] = __builtin_fmaf(s[t][b][j], sc_k[b], lvs[b] - m_run[t]);
+        if constexpr (KVT == PS_BF16) {   // no V scale in the exponents: one fold over both blocks
+          const float seed = max_of4(e[t][0]);
+          ahead |= fmaxf(fmaxf(fmaxf(fmaxf(seed, e[t][1][0]), e[t][1][1]), e[t][1][2]), e[t][1][3]) > kLazy;
+        } else {
+          ahead |= (max_of4(e[t][0]) > kLazy + lvs[0]) | (max_of4(e[t][1]) > kLazy + lvs[1]);
+        }
+      }
+      if (__builtin_amdgcn_ballot_w64(ahead) != 0) {
+#pragma unroll
+        for (int t = 0; t < kNT; ++t) {
+          move_reference(t, raw_max(t));
+#pragma unroll
+          for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) e[t][b][j] = __builtin_fmaf(s[t][b][j], sc_k[b], lvs[b] - m_run[t]);
+        }
+      }
     }
     bf16x8 pb[kNT];
 #pragma unroll
     for (int t = 0; t < kNT; ++t) {
-      if constexpr (kInterleave) {
-        // the query operands of the next row tile are requested before this row tile's work (hides the LDS latency)
-        const QOperands q_nxt = q_operands((t + 1) % kNT);
-        qk_row_tile(ka_next, q_cur, sc_next, t);
-        q_cur = q_nxt;
-      }
-      const float m_ref = (kLimited && m_run[t] == neg_inf) ? 0.f : m_run[t];
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
-        const float shift = lvs[b] - m_ref;
         float lsum = 0.f;
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const float pw = fast_exp2(__builtin_fmaf(sc.s[t][b][j], sc_k[b], shift));
+          const float pw = fast_exp2(e[t][b][j]);   // probability times the V scale
           lsum += pw;
           pb[t][4 * b + j] = (__bf16)pw;
         }
         l_run[t] += (KVT == PS_FP8_E4M3) ? lsum * inv_v[b] : lsum;
       }
     }
-    u32x4 vr[8];
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      if constexpr (KVT == PS_BF16) vr[i] = vtile.v[i];
-      else vr[i] = e4m3x8_to_bf16x8(vtile.v[i].x, vtile.v[i].y);
-    }
-    if constexpr (kLimited) {      // slots past the item's range may hold anything: zero them
-#pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int tok = tok0 + 16 * (i >> 2) + 4 * kg + (i & 3);
-        if (tok >= tok_end) vr[i] = u32x4{0, 0, 0, 0};
-      }
-    }
-#pragma unroll
-    for (int cc = 0; cc < 8; ++cc) {
-      uint32_t w[4];
-#pragma unroll
-      for (int i2 = 0; i2 < 4; ++i2) {
-        const uint32_t a = vr[2 * i2][cc >> 1], b = vr[2 * i2 + 1][cc >> 1];
-        w[i2] = __builtin_amdgcn_perm(b, a, (cc & 1) ? 0x07060302u : 0x05040100u);
-      }
-      const bf16x8 vt = as_bf16x8(u32x4{w[0], w[1], w[2], w[3]});
-#pragma unroll
-      for (int t = 0; t < kNT; ++t) acc[t][cc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt, pb[t], acc[t][cc], 0, 0, 0);
-    }
+    pv(vt, pb);
   };
 
-  // ---- stream the token range, software-pipelined across tiles: the scores of tile k + 1 go to the matrix cores
-  // before the softmax of tile k starts, so that the vector work of one tile overlaps with the matrix work of the
-  // next.  K of tile k + 1 is consumed one step before V of tile k + 1, hence the separate buffers: a K buffer is
-  // refilled (tile k + 3) as soon as its scores are issued, a V buffer (tile k + 2) after its P V.  First the tiles
-  // that every row of the wave sees whole (an even number, so the buffers keep their roles), then the rest with the
-  // per-row limits.  No branch surrounds a load, so the counting of outstanding loads stays exact.
-  const int n_whole = max(0, (see_all - tok_begin) / kTile) & ~1;
-  KTile kb[2];
-  VTile vb[2];
-  Scores sc_a, sc_b;
-  TileIds ids_a = fetch_ids(0), ids_b = fetch_ids(1);
-  load_k(kb[0], ids_a, 0);
-  load_v(vb[0], ids_a, 0);
-  load_k(kb[1], ids_b, 1);
-  load_v(vb[1], ids_b, 1);
-  TileIds ids_c = fetch_ids(2), ids_d = fetch_ids(3);
-  qk_scores(kb[0], sc_a);
-  load_k(kb[0], ids_c, 2);
-  auto two_tiles = [&](int k, auto limited_tag) __attribute__((always_inline)) {
-    // tile k: scores in sc_a, V in vb[0]; tile k + 1: K in kb[1], V in vb[1]; tile k + 2: K arriving in kb[0]
-    softmax_pv(sc_a, vb[0], ids_a, k, kb[1], sc_b, limited_tag);
-    load_k(kb[1], ids_d, k + 3);
-    load_v(vb[0], ids_c, k + 2);
-    const TileIds ids_e = fetch_ids(k + 4), ids_f = fetch_ids(k + 5);
-    // tile k + 1, with the scores of tile k + 2 (zeros past the range, never used then)
-    softmax_pv(sc_b, vb[1], ids_b, k + 1, kb[0], sc_a, limited_tag);
-    load_k(kb[0], ids_e, k + 4);
-    load_v(vb[1], ids_d, k + 3);
-    ids_a = ids_c;
-    ids_b = ids_d;
-    ids_c = ids_e;
-    ids_d = ids_f;
+  // ---- stream the token range.  In iteration k the wave publishes its share of tile k + 1 (fetched two iterations
+  // earlier), requests tile k + 3, multiplies tile k, and meets the others at the barrier: after it tile k + 1 is
+  // complete in the ring and nobody reads tile k - 1 any more, whose stage the next iteration overwrites.  No branch
+  // surrounds a load, so the counting of outstanding loads stays exact; every wave runs every iteration (and every
+  // barrier), whether it has rows or not.
+  Fetched fa, fb;
+  TileIds ids_0 = fetch_ids(0), ids_1 = fetch_ids(1), ids_2 = fetch_ids(2), ids_3 = fetch_ids(3);
+  fetch(fa, ids_0, 0);
+  fetch(fb, ids_1, 1);
+  publish(fa, 0, 0);
+  fetch(fa, ids_2, 2);
+  __syncthreads();
+  int st_cur = 0, st_nxt = 1, st_prv = 2;   // ring stages of tiles k, k + 1, k - 1
+  // ids_0: tile k (its scales), ids_1: tile k + 1 (in f_pub), ids_2: tile k + 2 (in flight), ids_3: tile k + 3
+  // what_tag: std::false_type / std::true_type = multiply without / with the per-row limits; void* = only fetch
+  auto one_tile = [&](int k, Fetched& f_pub, auto what_tag) __attribute__((always_inline)) {
+    constexpr bool kMultiply = !std::is_pointer<decltype(what_tag)>::value;
+    KOperands ka;
+    if constexpr (kMultiply) ka = read_k(st_cur);   // on their way while the wave does its share of the fetching
+    publish(f_pub, st_nxt, k + 1);
+    fetch(f_pub, ids_3, k + 3);
+    const TileIds ids_4 = fetch_ids(k + 4);
+    if constexpr (kMultiply) multiply(ka, ids_0, st_cur, k, what_tag);
+    const int st_free = st_prv;
+    st_prv = st_cur;
+    st_cur = st_nxt;
+    st_nxt = st_free;
+    ids_0 = ids_1;
+    ids_1 = ids_2;
+    ids_2 = ids_3;
+    ids_3 = ids_4;
+    __syncthreads();
   };
+  // Two tiles per round, so that the fetch registers keep their roles.  Three loops rather than tests inside one (a
+  // branch around the products would have the accumulators copied where its sides meet): the tiles every row of the
+  // wave sees whole, then the rest of what the wave sees with the per-row limits (a tile past it is masked out
+  // entirely), then the tiles only other waves need.  Every wave passes the same number of barriers.
+  // (Measured and dropped: giving the two waves of a SIMD different orders of the steps of a tile -- P V of the tile
+  // before first, or the fetching after the products instead of before -- so that they would not ask for the matrix
+  // cores at the same time: 5-9 % slower than leaving both in the same order.)
   int k = 0;
-  for (; k < n_whole; k += 2) two_tiles(k, std::false_type{});
-  for (; k < n_tiles; k += 2) two_tiles(k, std::true_type{});
+  for (; k + 2 <= n_whole; k += 2) {
+    one_tile(k, fb, std::false_type{});
+    one_tile(k + 1, fa, std::false_type{});
+  }
+  for (; k < n_tiles; k += 2) {
+    one_tile(k, fb, std::true_type{});
+    one_tile(k + 1, fa, std::true_type{});
+  }
+  for (; k < n_tiles_wg; k += 2) {
+    one_tile(k, fb, static_cast<void*>(nullptr));
+    one_tile(k + 1, fa, static_cast<void*>(nullptr));
+  }
 
   // ---- one partial state per row, straight from the accumulators: lane (n, kg) holds O[row n][32 kg + 8 j + cc]
 #pragma unroll
@@ -403,7 +450,7 @@ int32_t launch_prefill_attention(const AttnParams& p, const ps_geometry& g, cons
   const int spb = g.block_size / 16;
   if (g.head_dim != kD || g.q_dtype != PS_BF16 || g.block_size % 16 != 0 || (spb & (spb - 1)) != 0)
     return PS_ERR_UNSUPPORTED;
-  const dim3 grid(num_items), block(256);
+  const dim3 grid(num_items), block(64 * kWaves);
   if (g.kv_dtype == PS_BF16)
     hipLaunchKernelGGL((prefill_attention_kernel<PS_BF16>), grid, block, 0, st, p, items);
   else if (g.kv_dtype == PS_FP8_E4M3)
