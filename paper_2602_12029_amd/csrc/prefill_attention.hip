@@ -183,10 +183,12 @@ __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnPara
     if constexpr (KVT == PS_BF16) sm_k[stage][4 * fblk + kst][lane] = f.k;
     else sm_k[stage][4 * fblk + kst][lane] = e4m3x8_to_bf16x8(f.k.x, f.k.y);
     // slots of tokens past the item's range may hold anything: zero them (their probabilities are zero)
-    const int tok = tok_begin + kTile * k + 16 * fblk + 4 * kg + vi;
     auto v0 = f.v[0], v1 = f.v[1];
-    if (tok >= tok_end) v0 = decltype(v0){};
-    if (tok + 1 >= tok_end) v1 = decltype(v1){};
+    if (tok_begin + kTile * (k + 1) > tok_end) {   // (only the item's last tile can reach past its range)
+      const int tok = tok_begin + kTile * k + 16 * fblk + 4 * kg + vi;
+      if (tok >= tok_end) v0 = decltype(v0){};
+      if (tok + 1 >= tok_end) v1 = decltype(v1){};
+    }
     uint32_t* dst = reinterpret_cast<uint32_t*>(&sm_v[stage][4 * vh][lane]) + vp;
     if constexpr (KVT == PS_BF16) {
 #pragma unroll
@@ -400,9 +402,12 @@ __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnPara
   // branch around the products would have the accumulators copied where its sides meet): the tiles every row of the
   // wave sees whole, then the rest of what the wave sees with the per-row limits (a tile past it is masked out
   // entirely), then the tiles only other waves need.  Every wave passes the same number of barriers.
-  // (Measured and dropped: giving the two waves of a SIMD different orders of the steps of a tile -- P V of the tile
-  // before first, or the fetching after the products instead of before -- so that they would not ask for the matrix
-  // cores at the same time: 5-9 % slower than leaving both in the same order.)
+  // (Measured and dropped, all with parity green: giving the two waves of a SIMD different orders of the steps of a
+  // tile -- P V of the tile before first, or the fetching after the products instead of before -- so that they would
+  // not ask for the matrix cores at the same time: 5-9 % slower than leaving both in the same order; four-wave
+  // workgroups, two per item and per CU, which do not wait for each other but fetch every tile twice: 4 % slower; a
+  // four-stage ring with the scores of tile k + 1 issued one matrix instruction at a time between the exponentials
+  // of tile k: 9 % slower.)
   int k = 0;
   for (; k + 2 <= n_whole; k += 2) {
     one_tile(k, fb, std::false_type{});
