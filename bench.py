@@ -262,6 +262,7 @@ def main_ingest(args):
         for text in open(summary):
             if text.startswith("traffic_bytes_per_launch:"):
                 roofline["traffic"] = float(text.split(":")[1])
+                roofline["traffic_source"] = os.path.relpath(summary, ROOT) + " (rocprofv3 --pmc runs of this command, not this run)"
     value = moved / (ms_per_step * 1e-3) / 1e9
     line = {
         "metric": "KV hand-off ingest into the paged pool: bytes read + written, GB/s",
@@ -348,6 +349,7 @@ def main_stage(args):
         for text in open(summary):
             if text.startswith("traffic_bytes_per_launch:"):
                 roofline["traffic"] = float(text.split(":")[1])
+                roofline["traffic_source"] = os.path.relpath(summary, ROOT) + " (rocprofv3 --pmc runs of this command, not this run)"
     value = moved / (ms_per_step * 1e-3) / 1e9
     line = {
         "metric": "staging of a batch's KV blocks to an image and back: bytes read + written, GB/s",
@@ -475,6 +477,7 @@ def main_prefill(args):
         for text in open(summary):
             if text.startswith("traffic_bytes_per_launch:"):
                 roofline["traffic"] = float(text.split(":")[1])
+                roofline["traffic_source"] = os.path.relpath(summary, ROOT) + " (rocprofv3 --pmc runs of this command, not this run)"
     value = flops / (ms_per_step * 1e-3) / 1e12
     line = {
         "metric": "partial-prefill attention over the shared cache: algorithmic TFLOP/s + new tokens/sec",
