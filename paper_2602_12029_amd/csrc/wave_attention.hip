@@ -54,7 +54,7 @@ __device__ __forceinline__ void load_elems(const void* base, int64_t elem_off, f
 }
 
 template <int D, int KVT, int QT>
-__global__ __launch_bounds__(256) void wave_attention_kernel(AttnParams p, int item_begin) {
+__global__ __launch_bounds__(256, D <= 64 ? 3 : 2) void wave_attention_kernel(AttnParams p, int item_begin) {
   constexpr int E = D / 16;
   constexpr int kRowTile = D <= 128 ? 8 : 4;  // query rows carried in registers per pass over the tokens
   __shared__ float sm_m[4][kRowTile];
@@ -90,19 +90,35 @@ __global__ __launch_bounds__(256) void wave_attention_kernel(AttnParams p, int i
       }
     }
 
-    for (int t = it.tok_begin + stream; t < it.tok_end; t += 16) {
-      const int blk = p.blk[it.blk_off + t / p.block_size];
-      const int slot = t % p.block_size;
+    // Token loop, two steps deep in flight: while token t is worked on, the K/V rows of token t + 16 are on their way
+    // and the block id of token t + 32 is being looked up (each would otherwise be a memory round trip in front of
+    // every token's arithmetic).  Tokens past the range read token tok_end - 1 again and are not used.
+    auto block_of = [&](int t) { return p.blk[it.blk_off + min(t, it.tok_end - 1) / p.block_size]; };
+    auto fetch = [&](int t, int blk, float (&kf)[E], float (&vf)[E], float& k_scale, float& v_scale) {
+      const int tc = min(t, it.tok_end - 1);
+      const int slot = tc % p.block_size;
       const int64_t off = int64_t(blk) * p.s_block + int64_t(it.kv_head) * p.s_head + int64_t(slot) * p.s_tok + dchunk * E;
-      float kf[E], vf[E];
       load_elems<KVT, E>(p.kv, off, kf);
       load_elems<KVT, E>(p.kv, off + p.s_kv, vf);
-      float k_scale = p.scale_log2, v_scale = 1.f;
+      k_scale = p.scale_log2;
+      v_scale = 1.f;
       if constexpr (KVT == PS_FP8_E4M3) {
         const float* sc = p.scales + (int64_t(blk) * p.num_kv_heads + it.kv_head) * 2;
         k_scale *= sc[0];
         v_scale = sc[1];
       }
+    };
+    const int t_first = it.tok_begin + stream;
+    float kf[E], vf[E], k_scale = 0.f, v_scale = 0.f;
+    int blk_next = 0;
+    if (t_first < it.tok_end) {
+      fetch(t_first, block_of(t_first), kf, vf, k_scale, v_scale);
+      blk_next = block_of(t_first + 16);
+    }
+    for (int t = t_first; t < it.tok_end; t += 16) {
+      float kf_n[E], vf_n[E], k_scale_n, v_scale_n;
+      fetch(t + 16, blk_next, kf_n, vf_n, k_scale_n, v_scale_n);
+      blk_next = block_of(t + 32);
 #pragma unroll
       for (int rr = 0; rr < kRowTile; ++rr) {
         float dot = 0.f;
@@ -120,6 +136,10 @@ __global__ __launch_bounds__(256) void wave_attention_kernel(AttnParams p, int i
         for (int e = 0; e < E; ++e) acc[rr][e] = fmaf(acc[rr][e], alpha, wv * vf[e]);
         m[rr] = m_new;
       }
+#pragma unroll
+      for (int e = 0; e < E; ++e) { kf[e] = kf_n[e]; vf[e] = vf_n[e]; }
+      k_scale = k_scale_n;
+      v_scale = v_scale_n;
     }
 
     // merge the four 16-lane rows of this wave
