@@ -94,6 +94,10 @@ CHUNKS = [
     ("chunk_bf16", wl.Geometry(32, 8, 128, 16, "bf16", "bf16"), [1000, 0, 333], [200, 70, 17]),
     ("chunk_fp8", wl.Geometry(64, 8, 128, 16, "bf16", "fp8_e4m3"), [515, 2048], [100, 33]),
     ("chunk_block32_bf16", wl.Geometry(8, 2, 128, 32, "bf16", "bf16"), [300], [150]),
+    # token ranges of one to four tiles, ending on, just before and just after a tile boundary, with 68 to 260 rows per
+    # KV head: the first and last rounds of the prefill kernel's tile ring, waves without rows, partly filled row tiles
+    ("chunk_edges_bf16", wl.Geometry(32, 8, 128, 16, "bf16", "bf16"), [0, 1, 31, 33, 64, 95], [17, 20, 33, 40, 64, 65]),
+    ("chunk_edges_fp8_block32", wl.Geometry(64, 8, 128, 32, "bf16", "fp8_e4m3"), [0, 30, 63, 97], [9, 34, 33, 31]),
 ]
 
 
