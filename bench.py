@@ -33,7 +33,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="mixed",
                     help="tiny | b8 | long | mixed | fp8_70b; tree_tiny | tree_b8 (a context common to all sessions, stored "
-                         "once as a third sharing level)")
+                         "once as a third sharing level); sessions<S> (S concurrent four-agent sessions, e.g. sessions80: "
+                         "the shape of a sweep over the cap on concurrent sessions)")
     ap.add_argument("--stage-image", default="device", choices=["device", "host"],
                     help="--path stage: where the staging image lives (device memory: the kernels' own rate; pinned "
                          "host memory: the rate across PCIe)")
@@ -786,6 +787,13 @@ def measure_decode(args, name, steps, warmup, cpu_seconds, ceiling):
                    "layout_plan_ms": t_layout_ms},
         "roofline": roofline,
     }
+    if not tree:
+        # KV footprint with the prompts' contexts stored once against once per decode model (Efficiency Analysis, Eq. 9)
+        blk_bytes = g.num_kv_heads * 2 * g.block_size * g.head_dim * wl.generate.ELEM_BYTES[g.kv_dtype]
+        shared = B.ps_blocks_needed(g.block_size, w.prefix_len, w.suffix_len)
+        unshared = B.ps_blocks_needed(g.block_size, [], w.prefix_len[w.req_prompt] + w.suffix_len)
+        res["config"].update(kv_bytes_shared=shared * blk_bytes, kv_bytes_unshared=unshared * blk_bytes,
+                             kv_footprint_ratio=unshared / max(shared, 1))
     if step_stats:
         res["ms_per_step_median"] = step_stats["median"]
         res["ms_per_step_events_mean"] = step_stats["mean"]

@@ -199,9 +199,9 @@ def test_request_without_tokens_gives_zero_and_neg_inf(gpu):
     case.close()
 
 
-@pytest.mark.parametrize("name", ["b8", "fp8_70b", "long", "mixed"])
+@pytest.mark.parametrize("name", ["b8", "fp8_70b", "long", "mixed", "sessions40"])
 def test_full_size_all_outputs(gpu, name):
-    """Full benchmark configurations, default plan (the launch configuration bench.py times), every output of every
+    """Full benchmark configurations (and one point of the concurrent-sessions sweep), default plan (the launch configuration bench.py times), every output of every
     request against the oracle at the literal bars; bitwise repeatable (no float atomics anywhere)."""
     w = wl.named_workload(name)
     case = gpu(w)
@@ -226,8 +226,12 @@ def test_read_probe_runs_every_pattern_and_refuses_bad_arguments(gpu):
         for wgs in (1, 7):
             B.ps_probe_read(buf.data_ptr(), buf.numel(), pattern, wgs, stream)
     B.ps_probe_read(buf.data_ptr(), 100, 0, 4, stream)          # less than one unit: nothing to read
+    pow2 = torch.zeros(4 * 8192, dtype=torch.uint8, device="cuda:0")
+    for pattern in (4, 5, 6):                                   # scrambled chunk order: power-of-two chunk counts only
+        B.ps_probe_read(pow2.data_ptr(), pow2.numel(), pattern, 3, stream)
     torch.cuda.synchronize()
-    for bad in ((0, buf.numel(), 0, 4), (buf.data_ptr(), -1, 0, 4), (buf.data_ptr(), buf.numel(), 4, 4),
+    for bad in ((0, buf.numel(), 0, 4), (buf.data_ptr(), -1, 0, 4), (buf.data_ptr(), buf.numel(), 7, 4),
+                (buf.data_ptr(), buf.numel(), 4, 4),
                 (buf.data_ptr(), buf.numel(), 0, 0), (buf.data_ptr() + 8, buf.numel() - 8, 0, 4)):
         with pytest.raises(B.PsError):
             B.ps_probe_read(*bad, stream)

@@ -40,7 +40,7 @@ def _both(w, geo=None):
     return pool, lay, opool, olay
 
 
-@pytest.mark.parametrize("name", ["tiny", "b8", "long", "mixed", "fp8_70b"])
+@pytest.mark.parametrize("name", ["tiny", "b8", "long", "mixed", "fp8_70b", "sessions40"])
 def test_tables_bit_exact_against_oracle_policy(name):
     w = wl.named_workload(name)
     pool, lay, opool, olay = _both(w)

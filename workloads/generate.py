@@ -437,8 +437,13 @@ def named_workload(name: str, seed: int = 0, models: Optional[int] = None) -> Wo
              suffix U[1,1024], bf16
     fp8_70b  M=4, 64 prompts, prefix 8192, suffix U[1,512], 64/8 heads, bf16 Q, e4m3 KV
 
+    sessionsS  (S a number, e.g. sessions80) S concurrent multi-agent sessions, M=4 agents decoding on each session's
+             context: context lengths uniform in [1024, 6144] (multi-turn agent contexts), suffix U[1,256], 8B-shaped
+             heads, bf16 -- the shape of a sweep over the cap on concurrent sessions (Experiments, impact of max
+             concurrent sessions): the shared KV footprint grows with S, an unshared system's with M S
+
     `models` overrides M for the configurations in which every model decodes on every prompt (b8, long,
-    fp8_70b): same prompts and prefixes, M private suffixes per prompt (for sweeps over M).
+    fp8_70b, sessionsS): same prompts and prefixes, M private suffixes per prompt (for sweeps over M).
     """
     len_rng = _rng(seed, 1)
     mem_rng = _rng(seed, 2)
@@ -469,4 +474,9 @@ def named_workload(name: str, seed: int = 0, models: Optional[int] = None) -> Wo
         m, p = (models or 4), 64
         return make_workload(name, geo, m, [8192] * p, [list(range(m))] * p,
                              len_rng.integers(1, 513, size=p * m), 1.0, seed)
-    raise KeyError(f"unknown workload {name!r}; choose from {CONFIG_NAMES}")
+    if name.startswith("sessions") and name[8:].isdigit() and int(name[8:]) > 0:
+        geo = Geometry(32, 8, 128, 16, "bf16", "bf16")
+        m, p = (models or 4), int(name[8:])
+        return make_workload(name, geo, m, len_rng.integers(1024, 6145, size=p), [list(range(m))] * p,
+                             len_rng.integers(1, 257, size=p * m), 1.0, seed)
+    raise KeyError(f"unknown workload {name!r}; choose from {CONFIG_NAMES} or sessions<S>")
