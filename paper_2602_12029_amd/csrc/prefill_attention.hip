@@ -53,6 +53,7 @@ template <int KVT>
 __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnParams p, const ps_item* __restrict__ items) {
   __shared__ u32x4 sm_k[kStages][8][64];   // [stage][4 * block + k-step][lane]: K as that lane's A operand
   __shared__ u32x4 sm_v[kStages][8][64];   // [stage][16-column group][lane]: V^T as that lane's A operand
+  __shared__ f32x4 sm_sc[kStages][2];      // e4m3: [stage][block] = (score scale in log2 units, log2 of the V scale, 1 / V scale, -)
   __shared__ int sm_see[kWaves];
   const ps_item* it = items + blockIdx.x;
   const int blk_off = __builtin_amdgcn_readfirstlane(it->blk_off);
@@ -132,34 +133,20 @@ __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnPara
   const int v_lane_off = kv_bytes + (4 * kg + vi) * tok_bytes + (8 * n + 4 * vh) * kEsz;
   const int32_t* blk_seg = p.blk + blk_off;
 
-  struct TileIds { int id; float ksc[2], lvs[2]; };   // id: of this wave's block of the tile
-  auto fetch_ids = [&](int k) __attribute__((always_inline)) {   // block id (and e4m3 scales) of tile k; wave-uniform
-    // no branch around these loads (the index is clamped into the range instead), so that the counting of
+  struct TileIds { int id; };   // of this wave's block of the tile
+  auto fetch_ids = [&](int k) __attribute__((always_inline)) {   // wave-uniform
+    // no branch around this load (the index is clamped into the range instead), so that the counting of
     // outstanding loads in the streaming loop stays exact; a block past the range is never fetched from
     TileIds r;
-    if constexpr (KVT == PS_BF16) {
-      const int sub = max(sub0, min(sub0 + 2 * k + fblk, sub_end - 1));
-      r.id = __builtin_amdgcn_readfirstlane(blk_seg[sub >> sub_shift]);
-      r.ksc[0] = r.ksc[1] = 1.f;
-      r.lvs[0] = r.lvs[1] = 0.f;
-    } else {
-      int id[2];
-#pragma unroll
-      for (int b = 0; b < 2; ++b) {
-        const int sub = max(sub0, min(sub0 + 2 * k + b, sub_end - 1));
-        id[b] = __builtin_amdgcn_readfirstlane(blk_seg[sub >> sub_shift]);
-        const float* sc = p.scales + (int64_t(id[b]) * p.num_kv_heads + kv_head) * 2;
-        r.ksc[b] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(sc[0])));
-        r.lvs[b] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(__builtin_amdgcn_logf(sc[1]))));
-      }
-      r.id = fblk ? id[1] : id[0];
-    }
+    const int sub = max(sub0, min(sub0 + 2 * k + fblk, sub_end - 1));
+    r.id = __builtin_amdgcn_readfirstlane(blk_seg[sub >> sub_shift]);
     return r;
   };
   // this wave's share of a tile, as loaded
   struct Fetched {
     std::conditional_t<KVT == PS_BF16, u32x4, u32x2> k;         // 8 elements of one token
     std::conditional_t<KVT == PS_BF16, u32x2, uint32_t> v[2];   // 4 columns of two token rows
+    f32x2 sc;                                                   // e4m3: K and V scale of the block
   };
   auto fetch = [&](Fetched& f, const TileIds& ids, int k) __attribute__((always_inline)) {
     const int sub = sub0 + 2 * k + fblk;
@@ -175,13 +162,24 @@ __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnPara
       f.k = __builtin_amdgcn_raw_buffer_load_b64(rs, k_lane_off, 0, 0);
       f.v[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, v_lane_off, 0, 0);
       f.v[1] = __builtin_amdgcn_raw_buffer_load_b32(rs, v_lane_off, tok_bytes, 0);
+      // (the block id is clamped into the range, so the scales of a tile past it are some block's: never used)
+      f.sc = *reinterpret_cast<const f32x2*>(p.scales + (int64_t(ids.id) * p.num_kv_heads + kv_head) * 2);
     }
   };
   // ... and its way into the ring: K as it is (e4m3: converted), V transposed -- register vp of the operand of
   // column group cc holds column 8 n + cc of the token rows (2 vp, 2 vp + 1)
   auto publish = [&](const Fetched& f, int stage, int k) __attribute__((always_inline)) {
-    if constexpr (KVT == PS_BF16) sm_k[stage][4 * fblk + kst][lane] = f.k;
-    else sm_k[stage][4 * fblk + kst][lane] = e4m3x8_to_bf16x8(f.k.x, f.k.y);
+    if constexpr (KVT == PS_BF16) {
+      sm_k[stage][4 * fblk + kst][lane] = f.k;
+    } else {
+      sm_k[stage][4 * fblk + kst][lane] = e4m3x8_to_bf16x8(f.k.x, f.k.y);
+      // the block's scales, once per workgroup: the K scale folded into the score scale, the V scale as the exponent
+      // offset of the probabilities and as the factor that takes it out of the row sums again
+      if (kst == 0 && lane == 0) {
+        const float lv = __builtin_amdgcn_logf(f.sc.y);
+        sm_sc[stage][fblk] = f32x4{p.scale_log2 * f.sc.x, lv, fast_exp2(-lv), 0.f};
+      }
+    }
     // slots of tokens past the item's range may hold anything: zero them (their probabilities are zero)
     auto v0 = f.v[0], v1 = f.v[1];
     if (tok_begin + kTile * (k + 1) > tok_end) {   // (only the item's last tile can reach past its range)
@@ -243,15 +241,22 @@ __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnPara
       for (int t = 0; t < kNT; ++t)
         acc[t][cc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vt.a[cc]), pb[t], acc[t][cc], 0, 0, 0);
   };
-  auto multiply = [&](const KOperands& ka, const TileIds& ids, int stage, int k, auto limited_tag) __attribute__((always_inline)) {
+  auto multiply = [&](const KOperands& ka, int stage, int k, auto limited_tag) __attribute__((always_inline)) {
     constexpr bool kLimited = decltype(limited_tag)::value;
     const int tok0 = tok_begin + kTile * k;
     float sc_k[2], lvs[2], inv_v[2];
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
-      sc_k[b] = p.scale_log2 * ids.ksc[b];
-      lvs[b] = ids.lvs[b];
-      inv_v[b] = KVT == PS_FP8_E4M3 ? fast_exp2(-lvs[b]) : 1.f;
+      if constexpr (KVT == PS_FP8_E4M3) {
+        const f32x4 q4 = sm_sc[stage][b];
+        sc_k[b] = q4.x;
+        lvs[b] = q4.y;
+        inv_v[b] = q4.z;
+      } else {
+        sc_k[b] = p.scale_log2;
+        lvs[b] = 0.f;
+        inv_v[b] = 1.f;
+      }
     }
     // raw scores S^T = K Q^T: per row tile two accumulation chains (one per 16-token block)
     f32x4 s[kNT][2];
@@ -371,31 +376,28 @@ __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnPara
   // surrounds a load, so the counting of outstanding loads stays exact; every wave runs every iteration (and every
   // barrier), whether it has rows or not.
   Fetched fa, fb;
-  TileIds ids_0 = fetch_ids(0), ids_1 = fetch_ids(1), ids_2 = fetch_ids(2), ids_3 = fetch_ids(3);
-  fetch(fa, ids_0, 0);
-  fetch(fb, ids_1, 1);
+  fetch(fa, fetch_ids(0), 0);
+  fetch(fb, fetch_ids(1), 1);
+  TileIds ids_nxt = fetch_ids(2);
   publish(fa, 0, 0);
-  fetch(fa, ids_2, 2);
+  fetch(fa, ids_nxt, 2);
+  ids_nxt = fetch_ids(3);
   __syncthreads();
   int st_cur = 0, st_nxt = 1, st_prv = 2;   // ring stages of tiles k, k + 1, k - 1
-  // ids_0: tile k (its scales), ids_1: tile k + 1 (in f_pub), ids_2: tile k + 2 (in flight), ids_3: tile k + 3
+  // ids_nxt: the block id of tile k + 3, asked for one iteration ago
   // what_tag: std::false_type / std::true_type = multiply without / with the per-row limits; void* = only fetch
   auto one_tile = [&](int k, Fetched& f_pub, auto what_tag) __attribute__((always_inline)) {
     constexpr bool kMultiply = !std::is_pointer<decltype(what_tag)>::value;
     KOperands ka;
     if constexpr (kMultiply) ka = read_k(st_cur);   // on their way while the wave does its share of the fetching
     publish(f_pub, st_nxt, k + 1);
-    fetch(f_pub, ids_3, k + 3);
-    const TileIds ids_4 = fetch_ids(k + 4);
-    if constexpr (kMultiply) multiply(ka, ids_0, st_cur, k, what_tag);
+    fetch(f_pub, ids_nxt, k + 3);
+    ids_nxt = fetch_ids(k + 4);
+    if constexpr (kMultiply) multiply(ka, st_cur, k, what_tag);
     const int st_free = st_prv;
     st_prv = st_cur;
     st_cur = st_nxt;
     st_nxt = st_free;
-    ids_0 = ids_1;
-    ids_1 = ids_2;
-    ids_2 = ids_3;
-    ids_3 = ids_4;
     __syncthreads();
   };
   // Two tiles per round, so that the fetch registers keep their roles.  Three loops rather than tests inside one (a
