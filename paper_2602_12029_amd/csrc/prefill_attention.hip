@@ -6,23 +6,31 @@
 // step has a few dozen -- so the work is a dense contraction and the matrix cores, not HBM, are the bound.
 //
 // One workgroup of eight waves takes one work item: a token range of one context and KV head, and up to 256 query
-// rows that see into it.  The rows are split over the waves, 32 each (two 16-row tiles, the query rows resident in
-// registers as MFMA B operands), and every wave walks the token range.  Two waves share a SIMD, so that the vector
-// work of one (exponentials, conversions) runs under the matrix instructions of the other; a wave on its own issues
-// one instruction every four cycles and cannot cover its own matrix instructions.
+// rows that see into it.  The rows are split over the waves, 32 each (the query rows resident in registers as MFMA
+// B operands), and every wave walks the token range.  Two waves share a SIMD, so that the vector work of one
+// (exponentials, conversions) runs under the matrix instructions of the other.
+//
+// The products are v_mfma_f32_32x32x16_bf16: 32 tokens x 32 rows per instruction.  On this chip it keeps the matrix
+// core busy for 32 cycles and the SIMD's vector port for 8 of them, so six plain vector instructions fit into its
+// shadow, where the 16x16x32 form (16 cycles, 8 of them on the port) leaves room for two: the same flops take half
+// the issue slots, and issue slots are what this kernel runs out of.
 //
 // K and V reach the waves through LDS, as ready-made A operands: per 32-token tile the eight waves fetch one eighth
 // of it each (K straight in operand layout; V as pairs of token rows, transposed inside the lane with one byte
 // permute per operand register; e4m3 codes converted to bf16 once), write it to a three-stage ring, and after one
 // barrier per tile every wave reads the 8 K and 8 V operands of the tile back, 16 bytes per lane and operand, each
 // lane exactly the slot of its own lane index (no bank conflicts).  A tile is thus fetched, transposed and
-// converted once per 256 rows.  Global loads run three tiles ahead of the products (two tiles in registers, one in
-// LDS).
+// converted once per 256 rows.  Global loads run four tiles ahead of the products (two tiles in registers, two in
+// LDS), and a tile's K operands are requested from the ring while the tile before it is multiplied.
 //
-// Per wave and tile the math is that of the decode kernel (S^T = K Q^T, online softmax with a lazily moving
-// reference, O^T += V^T P^T).  A wave skips the tiles past what its own rows see; the per-row limit is applied only
-// to tiles that reach past the wave's shortest row.  Nothing but the ring is shared between waves: no cross-wave
-// merge, every wave writes the partial states of its own rows.
+// Per wave and tile: S^T = K Q^T (A = K: lane (m, g) holds elements 16 st + 8 g .. + 7 of token m for k-step st; B =
+// Q^T likewise for query row n), whose result leaves lane (n, g) with the scores of row n against tokens
+// 8 (r / 4) + 4 g + r % 4, r = 0 .. 15; online softmax with a lazily moving reference; O^T += V^T P^T with the
+// probabilities as B operand exactly as they lie (registers 8 ks .. 8 ks + 7 for the 16-token step ks), V^T written
+// to the ring so that position j of lane group g in step ks is token 16 ks + 8 (j / 4) + 4 g + j % 4.  A wave skips
+// the tiles past what its own rows see; the per-row limit is applied only to tiles that reach past the wave's
+// shortest row.  Nothing but the ring is shared between waves: no cross-wave merge, every wave writes the partial
+// states of its own rows.
 #include <type_traits>
 
 #include "device_common.h"
@@ -35,11 +43,22 @@ namespace {
 
 constexpr int kD = kHeadDim;
 constexpr int kWaves = 8;         // per workgroup
-constexpr int kNT = 2;            // 16-row tiles per wave
-constexpr int kRowsPerWave = 16 * kNT;
+constexpr int kRowsPerWave = 32;  // one 32-row tile per wave
 constexpr int kTile = kTileTokens;
-constexpr int kStages = 3;        // LDS ring: tile k read, tile k + 1 written, tile k - 1 possibly still read
+constexpr int kStages = 3;        // LDS ring: tile k read (V), tile k + 1 read (K, one tile ahead), tile k + 2 written
 constexpr float kLazy = kLazyRescale;
+constexpr float kLazyTop = 256.f;   // 2^kLazy
+static_assert(kLazyRescale == 8.f, "kLazyTop is 2^kLazyRescale");
+
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+// largest of eight scores, folded from the constant -inf so that three-input maxima do (see max_of4)
+__device__ __forceinline__ float max_of8(const f32x16& s, int first) {
+  float m = -__builtin_inff();
+#pragma unroll
+  for (int i = 0; i < 8; ++i) m = fmaxf(m, s[first + i]);
+  return m;
+}
 
 __device__ __forceinline__ int wave_max(int x) {
 #pragma unroll
@@ -51,8 +70,8 @@ __device__ __forceinline__ int wave_max(int x) {
 
 template <int KVT>
 __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnParams p, const ps_item* __restrict__ items) {
-  __shared__ u32x4 sm_k[kStages][8][64];   // [stage][4 * block + k-step][lane]: K as that lane's A operand
-  __shared__ u32x4 sm_v[kStages][8][64];   // [stage][16-column group][lane]: V^T as that lane's A operand
+  __shared__ u32x4 sm_k[kStages][8][64];   // [stage][k-step][lane]: K as that lane's A operand
+  __shared__ u32x4 sm_v[kStages][8][64];   // [stage][2 * column class + 16-token step][lane]: V^T as that lane's A operand
   __shared__ f32x4 sm_sc[kStages][2];      // e4m3: [stage][block] = (score scale in log2 units, log2 of the V scale, 1 / V scale, -)
   __shared__ int sm_see[kWaves];
   const ps_item* it = items + blockIdx.x;
@@ -68,35 +87,33 @@ __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnPara
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
-  const int n = lane & 15;   // query row within a row tile / token within a block / d-chunk, by role
-  const int kg = lane >> 4;
+  const int n = lane & 15;   // fetching: token within a 16-token block
+  const int kg = lane >> 4;  // fetching: 8-element chunk of a 32-element piece (K), row / column class (V)
+  const int g = lane >> 5;   // products: half of a k-step's 16 contraction indices
   const int G = p.group;
   const int rows = n_req * G;
   const int row_base = kRowsPerWave * wave;
-  const int nt_used = max(0, min(kNT, (rows - row_base + 15) >> 4));   // 0: a wave without rows only fetches
+  const bool has_rows = rows > row_base;   // a wave without rows only fetches
   const float neg_inf = -__builtin_inff();
 
-  // ---- this lane's query rows (row 16 t + n of the wave): request, visible length, and the row itself as the
-  // four B operands of S^T = K Q^T (k-step st, lane group kg: elements 32 st + 8 kg .. + 7)
-  int req_of[kNT], lim[kNT];
-  bf16x8 qb[kNT][4];
+  // ---- this lane's query row (row lane % 32 of the wave): request, visible length, and the row itself as the
+  // eight B operands of S^T = K Q^T (k-step st, lane group g: elements 16 st + 8 g .. + 7)
+  int req_of = -1, lim = 0;   // a padding row sees nothing
+  bf16x8 qb[8];
+#pragma unroll
+  for (int st = 0; st < 8; ++st) qb[st] = as_bf16x8(u32x4{0, 0, 0, 0});
   int lim_hi = 0, lim_lo = 0x7fffffff;
-#pragma unroll
-  for (int t = 0; t < kNT; ++t) {
-    const int row = row_base + 16 * t + n;
-    req_of[t] = -1;
-    lim[t] = 0;   // a padding row sees nothing
-#pragma unroll
-    for (int st = 0; st < 4; ++st) qb[t][st] = as_bf16x8(u32x4{0, 0, 0, 0});
+  {
+    const int row = row_base + (lane & 31);
     if (row < rows) {
       const int req = p.req_list[req_off + row / G];
-      req_of[t] = req;
-      lim[t] = limited ? min(tok_end, p.visible[req]) : tok_end;
+      req_of = req;
+      lim = limited ? min(tok_end, p.visible[req]) : tok_end;
       const uint16_t* qrow = static_cast<const uint16_t*>(p.q) + (int64_t(req) * p.num_q_heads + kv_head * G + row % G) * kD;
 #pragma unroll
-      for (int st = 0; st < 4; ++st) qb[t][st] = as_bf16x8(*reinterpret_cast<const u32x4*>(qrow + 32 * st + 8 * kg));
-      lim_hi = max(lim_hi, lim[t]);
-      lim_lo = min(lim_lo, lim[t]);
+      for (int st = 0; st < 8; ++st) qb[st] = as_bf16x8(*reinterpret_cast<const u32x4*>(qrow + 16 * st + 8 * g));
+      lim_hi = lim;
+      lim_lo = lim;
     }
   }
   const int see_end = max(tok_begin, wave_max(lim_hi));   // no row of this wave sees a token at or past this one
@@ -108,7 +125,7 @@ __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnPara
   for (int w = 0; w < kWaves; ++w) see_end_wg = max(see_end_wg, sm_see[w]);
   see_end_wg = __builtin_amdgcn_readfirstlane(see_end_wg);
   const int n_tiles_wg = (see_end_wg - tok_begin + kTile - 1) / kTile;   // tiles the workgroup fetches
-  const int n_tiles = nt_used > 0 ? (see_end - tok_begin + kTile - 1) / kTile : 0;   // tiles this wave multiplies
+  const int n_tiles = has_rows ? (see_end - tok_begin + kTile - 1) / kTile : 0;   // tiles this wave multiplies
   const int n_whole = min(n_tiles, max(0, (see_all - tok_begin) / kTile));   // ... of which these need no per-row limit
 
   // ---- addressing: block base in SGPRs (a buffer descriptor per 16-token block), loop-invariant lane offsets
@@ -123,14 +140,17 @@ __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnPara
   const int sub0 = tok_begin >> 4;
   const int sub_end = (see_end_wg + 15) >> 4;
   // What this wave fetches of every tile, all of it from one 16-token block (fblk) so that one block id and one
-  // buffer descriptor per tile do.  K: operand (block fblk, k-step kst) -- token n of the block, the 8 elements of
-  // lane group kg.  V: the pair of token rows (2 vp, 2 vp + 1) of the eight a lane group owns (rows 4 kg + i of
-  // block 0, then of block 1), column half vh -- 4 of the lane's 8 columns.
+  // buffer descriptor per tile do.  K: token n of the block, elements 32 kst + 8 kg .. + 7 -- that is lane
+  // (16 fblk + n, kg % 2) of the operand of k-step 2 kst + kg / 2.  V: the pair of token rows (vrow, vrow + 1), columns
+  // 8 n + 4 (kg % 2) + x, x = 0 .. 3 -- the pair is register wave % 4 of lane (n + 16 (kg % 2), kg / 2) = this very
+  // lane in the operand of column class x and step fblk; the operand's row lane % 32 is thus column
+  // 8 (lane % 16) + 4 (lane / 16 % 2) + x, which the epilogue undoes.
   const int fblk = wave >> 2, kst = wave & 3;
-  const int vp = 2 * fblk + (wave & 1), vh = (wave >> 1) & 1;
-  const int vi = 2 * (wave & 1);
+  const int vreg = wave & 3;
+  const int vrow = 4 * (kg >> 1) + 8 * ((wave >> 1) & 1) + 2 * (wave & 1);
   const int k_lane_off = n * tok_bytes + (32 * kst + 8 * kg) * kEsz;
-  const int v_lane_off = kv_bytes + (4 * kg + vi) * tok_bytes + (8 * n + 4 * vh) * kEsz;
+  const int v_lane_off = kv_bytes + vrow * tok_bytes + (8 * n + 4 * (kg & 1)) * kEsz;
+  const int k_op = 2 * kst + (kg >> 1), k_slot = 16 * fblk + n + 32 * (kg & 1);
   const int32_t* blk_seg = p.blk + blk_off;
 
   struct TileIds { int id; };   // of this wave's block of the tile
@@ -166,13 +186,14 @@ __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnPara
       f.sc = *reinterpret_cast<const f32x2*>(p.scales + (int64_t(ids.id) * p.num_kv_heads + kv_head) * 2);
     }
   };
-  // ... and its way into the ring: K as it is (e4m3: converted), V transposed -- register vp of the operand of
-  // column group cc holds column 8 n + cc of the token rows (2 vp, 2 vp + 1)
-  auto publish = [&](const Fetched& f, int stage, int k) __attribute__((always_inline)) {
+  // ... and its way into the ring: K as it is (e4m3: converted), V transposed -- register vreg of this lane's slot
+  // in the operand of column class x holds column 8 n + 4 (kg % 2) + x of the token rows (vrow, vrow + 1)
+  // ragged_tag: std::true_type = the tile may be the item's last, which can reach past its range
+  auto publish = [&](const Fetched& f, int stage, int k, auto ragged_tag) __attribute__((always_inline)) {
     if constexpr (KVT == PS_BF16) {
-      sm_k[stage][4 * fblk + kst][lane] = f.k;
+      sm_k[stage][k_op][k_slot] = f.k;
     } else {
-      sm_k[stage][4 * fblk + kst][lane] = e4m3x8_to_bf16x8(f.k.x, f.k.y);
+      sm_k[stage][k_op][k_slot] = e4m3x8_to_bf16x8(f.k.x, f.k.y);
       // the block's scales, once per workgroup: the K scale folded into the score scale, the V scale as the exponent
       // offset of the probabilities and as the factor that takes it out of the row sums again
       if (kst == 0 && lane == 0) {
@@ -182,46 +203,41 @@ __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnPara
     }
     // slots of tokens past the item's range may hold anything: zero them (their probabilities are zero)
     auto v0 = f.v[0], v1 = f.v[1];
-    if (tok_begin + kTile * (k + 1) > tok_end) {   // (only the item's last tile can reach past its range)
-      const int tok = tok_begin + kTile * k + 16 * fblk + 4 * kg + vi;
+    if (decltype(ragged_tag)::value && tok_begin + kTile * (k + 1) > tok_end) {   // (only the item's last tile can)
+      const int tok = tok_begin + kTile * k + 16 * fblk + vrow;
       if (tok >= tok_end) v0 = decltype(v0){};
       if (tok + 1 >= tok_end) v1 = decltype(v1){};
     }
-    uint32_t* dst = reinterpret_cast<uint32_t*>(&sm_v[stage][4 * vh][lane]) + vp;
+    uint32_t* dst = reinterpret_cast<uint32_t*>(&sm_v[stage][fblk][lane]) + vreg;   // operand 2 x + fblk
     if constexpr (KVT == PS_BF16) {
 #pragma unroll
-      for (int c = 0; c < 4; ++c)   // low (even column) or high (odd column) halves of the two rows: one byte permute
-        dst[c * 64 * 4] = __builtin_amdgcn_perm(v1[c >> 1], v0[c >> 1], (c & 1) ? 0x07060302u : 0x05040100u);
+      for (int x = 0; x < 4; ++x)   // low (even column) or high (odd column) halves of the two rows: one byte permute
+        dst[x * 2 * 64 * 4] = __builtin_amdgcn_perm(v1[x >> 1], v0[x >> 1], (x & 1) ? 0x07060302u : 0x05040100u);
     } else {
 #pragma unroll
       for (int cp = 0; cp < 2; ++cp) {   // the codes of columns (2 cp, 2 cp + 1) of the two rows, then converted
         const uint32_t pair = __builtin_amdgcn_perm(v1, v0, cp ? 0x07030602u : 0x05010400u);
-        dst[(2 * cp) * 64 * 4] = e4m3x2_to_bf16x2(pair, false);
-        dst[(2 * cp + 1) * 64 * 4] = e4m3x2_to_bf16x2(pair, true);
+        dst[(2 * cp) * 2 * 64 * 4] = e4m3x2_to_bf16x2(pair, false);
+        dst[(2 * cp + 1) * 2 * 64 * 4] = e4m3x2_to_bf16x2(pair, true);
       }
     }
   };
 
-  float m_run[kNT], l_run[kNT];
-  f32x4 acc[kNT][8];
+  float m_run = neg_inf, l_run = 0.f;
+  f32x16 acc[4];   // O^T, one block of 32 columns per column class
 #pragma unroll
-  for (int t = 0; t < kNT; ++t) {
-    m_run[t] = neg_inf;
-    l_run[t] = 0.f;
+  for (int x = 0; x < 4; ++x)
 #pragma unroll
-    for (int c = 0; c < 8; ++c) acc[t][c] = f32x4{0.f, 0.f, 0.f, 0.f};
-  }
+    for (int r = 0; r < 16; ++r) acc[x][r] = 0.f;
 
   // One tile for this wave's rows, operands from the ring.
   // limited_tag: std::true_type applies the per-row limits (and guards rows that have seen nothing yet);
   // std::false_type promises that every row of the wave sees the whole tile.
-  struct KOperands { u32x4 a[2][4]; };
+  struct KOperands { u32x4 a[8]; };
   auto read_k = [&](int stage) __attribute__((always_inline)) {   // the 8 K operands of a stage, requested in one go
     KOperands ka;
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int st = 0; st < 4; ++st) ka.a[b][st] = sm_k[stage][4 * b + st][lane];
+    for (int st = 0; st < 8; ++st) ka.a[st] = sm_k[stage][st][lane];
     __builtin_amdgcn_sched_barrier(0);
     return ka;
   };
@@ -229,19 +245,30 @@ __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnPara
   auto read_v = [&](int stage) __attribute__((always_inline)) {   // the 8 V operands of a stage, requested in one go
     VOperands vt;
 #pragma unroll
-    for (int cc = 0; cc < 8; ++cc) vt.a[cc] = sm_v[stage][cc][lane];
+    for (int op = 0; op < 8; ++op) vt.a[op] = sm_v[stage][op][lane];
     __builtin_amdgcn_sched_barrier(0);
     return vt;
   };
-  // O^T += V^T P^T, one 16-column group of V at a time
-  auto pv = [&](const VOperands& vt, const bf16x8 (&pb)[kNT]) __attribute__((always_inline)) {
+  // O^T += V^T P^T: the two 16-token steps of the tile, one column class at a time
+  auto pv = [&](const VOperands& vt, const bf16x8 (&pb)[2]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int cc = 0; cc < 8; ++cc)
+    for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-      for (int t = 0; t < kNT; ++t)
-        acc[t][cc] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(vt.a[cc]), pb[t], acc[t][cc], 0, 0, 0);
+      for (int x = 0; x < 4; ++x)
+        acc[x] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(vt.a[2 * x + ks]), pb[ks], acc[x], 0, 0, 0);
   };
-  auto multiply = [&](const KOperands& ka, int stage, int k, auto limited_tag) __attribute__((always_inline)) {
+  // raw scores S^T = K Q^T: register r of this lane = its row against token 8 (r / 4) + 4 g + r % 4 of the tile
+  // (registers 0 .. 7 the first 16-token block, 8 .. 15 the second)
+  auto scores = [&](const KOperands& ka) __attribute__((always_inline)) {
+    f32x16 s;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+    for (int st = 0; st < 8; ++st) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf16x8(ka.a[st]), qb[st], s, 0, 0, 0);
+    return s;
+  };
+  // softmax of a tile's scores and its P V products
+  auto finish = [&](f32x16 s, const VOperands& vt, int stage, int k, auto limited_tag) __attribute__((always_inline)) {
     constexpr bool kLimited = decltype(limited_tag)::value;
     const int tok0 = tok_begin + kTile * k;
     float sc_k[2], lvs[2], inv_v[2];
@@ -258,196 +285,166 @@ __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnPara
         inv_v[b] = 1.f;
       }
     }
-    // raw scores S^T = K Q^T: per row tile two accumulation chains (one per 16-token block)
-    f32x4 s[kNT][2];
-#pragma unroll
-    for (int t = 0; t < kNT; ++t)
-#pragma unroll
-      for (int b = 0; b < 2; ++b) s[t][b] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int st = 0; st < 4; ++st)
-#pragma unroll
-      for (int b = 0; b < 2; ++b)
-#pragma unroll
-        for (int t = 0; t < kNT; ++t)
-          s[t][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(as_bf16x8(ka.a[b][st]), qb[t][st], s[t][b], 0, 0, 0);
-    // the V operands are requested now, all eight, so that they arrive under the softmax (left to itself the
-    // compiler requests each one right before its products, and the wave sits out the LDS latency eight times)
-    const VOperands vt = read_v(stage);
     if constexpr (kLimited) {
 #pragma unroll
-      for (int t = 0; t < kNT; ++t)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-          for (int j = 0; j < 4; ++j)
-            if (tok0 + 16 * b + 4 * kg + j >= lim[t]) s[t][b][j] = neg_inf;
+      for (int r = 0; r < 16; ++r)
+        if (tok0 + 8 * (r >> 2) + 4 * g + (r & 3) >= lim) s[r] = neg_inf;
     }
     // The softmax reference m_run follows the row maximum lazily: it moves (and the accumulators are rescaled)
-    // only when some score gets more than kLazy ahead of it, so probabilities stay below 2^kLazy instead of below 1
-    // -- the same result by shift invariance of softmax.  The test is local to the lane (its own scores, in log2
-    // units; the scales are positive, so a block's maximum scales like its scores) and one vote covers the row
-    // tiles; only when it fires somewhere in the wave is the maximum of each row put together across the row's
-    // four lanes, which must agree on m_run.  A row that has seen nothing yet has m_run = -inf and stays there
-    // until a score arrives.
-    // Where no per-row limit applies the test is made on the exponents themselves (score minus reference, which the
-    // probabilities need anyway): one exceeds kLazy exactly when its score is that far ahead, and a row that has
-    // seen nothing yet (reference -inf) gets +inf there and votes too.  Only the rare branch goes back to the raw
-    // scores, and recomputes the exponents against the new reference.
-    auto raw_max = [&](int t) { return fmaxf(max_of4(s[t][0]) * sc_k[0], max_of4(s[t][1]) * sc_k[1]); };
-    auto move_reference = [&](int t, float mx) __attribute__((always_inline)) {
-      float row_mx = fmaxf(mx, lane_xor(mx, 16));
-      row_mx = fmaxf(row_mx, lane_xor(row_mx, 32));
-      const float m_new = (row_mx > m_run[t] + kLazy) ? row_mx : m_run[t];
-      const float alpha = (m_new == m_run[t]) ? 1.f : fast_exp2(m_run[t] - m_new);   // -inf -> finite gives 0
-      l_run[t] *= alpha;
+    // only when some score gets far ahead of it, so probabilities stay below 2^kLazy instead of below 1 -- the same
+    // result by shift invariance of softmax.  The test is local to the lane and one wave vote decides; only when it
+    // fires somewhere in the wave is the maximum of the row put together across the row's two lanes, which must
+    // agree on m_run.  A row that has seen nothing yet has m_run = -inf and stays there until a score arrives.
+    auto raw_max = [&]() { return fmaxf(max_of8(s, 0) * sc_k[0], max_of8(s, 8) * sc_k[1]); };
+    auto move_reference = [&](float mx, float ahead_by) __attribute__((always_inline)) {
+      const float row_mx = fmaxf(mx, lane_xor(mx, 32));
+      const float m_new = (row_mx > m_run + ahead_by) ? row_mx : m_run;
+      const float alpha = (m_new == m_run) ? 1.f : fast_exp2(m_run - m_new);   // -inf -> finite gives 0
+      l_run *= alpha;
 #pragma unroll
-      for (int cc = 0; cc < 8; ++cc) acc[t][cc] *= alpha;
-      m_run[t] = m_new;
+      for (int x = 0; x < 4; ++x) acc[x] *= alpha;
+      m_run = m_new;
     };
-    f32x4 e[kNT][2];   // exponents: score in log2 units, plus log2 of the block's V scale, minus the reference
-    if constexpr (kLimited) {
-      float mx[kNT];
-      bool ahead = false;
-#pragma unroll
-      for (int t = 0; t < kNT; ++t) {
-        mx[t] = raw_max(t);
-        ahead |= mx[t] > m_run[t] + kLazy;
-      }
-      if (__builtin_amdgcn_ballot_w64(ahead) != 0) {
-#pragma unroll
-        for (int t = 0; t < kNT; ++t) move_reference(t, mx[t]);
-      }
-#pragma unroll
-      for (int t = 0; t < kNT; ++t) {
-        const float m_ref = (m_run[t] == neg_inf) ? 0.f : m_run[t];   // keeps (-inf) - (-inf) out of the exponents
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) e[t][b][j] = __builtin_fmaf(s[t][b][j], sc_k[b], lvs[b] - m_ref);
-      }
-    } else {
-      bool ahead = false;
-#pragma unroll
-      for (int t = 0; t < kNT; ++t) {
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) e[t][b][j] = __builtin_fmaf(s[t][b][j], sc_k[b], lvs[b] - m_run[t]);
-        if constexpr (KVT == PS_BF16) {   // no V scale in the exponents: one fold over both blocks
-          const float seed = max_of4(e[t][0]);
-          ahead |= fmaxf(fmaxf(fmaxf(fmaxf(seed, e[t][1][0]), e[t][1][1]), e[t][1][2]), e[t][1][3]) > kLazy;
-        } else {
-          ahead |= (max_of4(e[t][0]) > kLazy + lvs[0]) | (max_of4(e[t][1]) > kLazy + lvs[1]);
-        }
-      }
-      if (__builtin_amdgcn_ballot_w64(ahead) != 0) {
-#pragma unroll
-        for (int t = 0; t < kNT; ++t) {
-          move_reference(t, raw_max(t));
-#pragma unroll
-          for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) e[t][b][j] = __builtin_fmaf(s[t][b][j], sc_k[b], lvs[b] - m_run[t]);
-        }
-      }
-    }
-    bf16x8 pb[kNT];
-#pragma unroll
-    for (int t = 0; t < kNT; ++t) {
+    f32x16 e;   // exponents: score in log2 units, plus log2 of the block's V scale, minus the reference
+    float pw[16], lsum[2];   // probabilities times the V scale; their sums per block
+    auto probabilities = [&]() __attribute__((always_inline)) {
 #pragma unroll
       for (int b = 0; b < 2; ++b) {
-        float lsum = 0.f;
+        lsum[b] = 0.f;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const float pw = fast_exp2(e[t][b][j]);   // probability times the V scale
-          lsum += pw;
-          pb[t][4 * b + j] = (__bf16)pw;
+        for (int j = 0; j < 8; ++j) {
+          pw[8 * b + j] = fast_exp2(e[8 * b + j]);
+          lsum[b] += pw[8 * b + j];
         }
-        l_run[t] += (KVT == PS_FP8_E4M3) ? lsum * inv_v[b] : lsum;
+      }
+    };
+    float total;   // this lane's 16 probabilities, summed
+    if constexpr (kLimited) {
+      // per-row limits: the test is made on the raw scores (in log2 units; the scales are positive, so a block's
+      // maximum scales like its scores)
+      const float mx = raw_max();
+      if (__builtin_amdgcn_ballot_w64(mx > m_run + kLazy) != 0) move_reference(mx, kLazy);
+      const float m_ref = (m_run == neg_inf) ? 0.f : m_run;   // keeps (-inf) - (-inf) out of the exponents
+#pragma unroll
+      for (int r = 0; r < 16; ++r) e[r] = __builtin_fmaf(s[r], sc_k[r >> 3], lvs[r >> 3] - m_ref);
+      probabilities();
+      total = (KVT == PS_FP8_E4M3) ? lsum[0] * inv_v[0] + lsum[1] * inv_v[1] : lsum[0] + lsum[1];
+    } else {
+      // Every row sees the whole tile: the test is made on the sum of the lane's probabilities, which the row sum
+      // needs anyway -- a probability above 2^kLazy (or an infinite one: a row that has seen nothing yet has the
+      // reference -inf) shows in it, and a sum above 2^kLazy means that one of its 16 terms is above 2^(kLazy - 4),
+      // so in the rare branch the reference moves for every row that is that far ahead, after which the row's
+      // probabilities are at most 1 and the test is quiet again.  No maximum is taken on the common path.
+#pragma unroll
+      for (int r = 0; r < 16; ++r) e[r] = __builtin_fmaf(s[r], sc_k[r >> 3], lvs[r >> 3] - m_run);
+      probabilities();
+      total = (KVT == PS_FP8_E4M3) ? lsum[0] * inv_v[0] + lsum[1] * inv_v[1] : lsum[0] + lsum[1];
+      if (__builtin_amdgcn_ballot_w64(!(total <= kLazyTop)) != 0) {
+        move_reference(raw_max(), kLazy - 4.f);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) e[r] = __builtin_fmaf(s[r], sc_k[r >> 3], lvs[r >> 3] - m_run);
+        probabilities();
+        total = (KVT == PS_FP8_E4M3) ? lsum[0] * inv_v[0] + lsum[1] * inv_v[1] : lsum[0] + lsum[1];
       }
     }
+    l_run += total;
+    bf16x8 pb[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) pb[b][j] = (__bf16)pw[8 * b + j];
     pv(vt, pb);
   };
 
-  // ---- stream the token range.  In iteration k the wave publishes its share of tile k + 1 (fetched two iterations
-  // earlier), requests tile k + 3, multiplies tile k, and meets the others at the barrier: after it tile k + 1 is
-  // complete in the ring and nobody reads tile k - 1 any more, whose stage the next iteration overwrites.  No branch
-  // surrounds a load, so the counting of outstanding loads stays exact; every wave runs every iteration (and every
-  // barrier), whether it has rows or not.
+  // ---- stream the token range.  The ring holds three tiles: in iteration k the wave multiplies tile k (its K
+  // operands already in registers, requested during iteration k - 1), requests the K operands of tile k + 1 (complete
+  // in the ring since the last barrier), publishes its share of tile k + 2 (fetched two iterations earlier) into the
+  // stage tile k - 1 left, requests tile k + 4 from memory, and meets the others at the barrier.  The products of a
+  // tile thus start right behind the barrier instead of waiting for operands that all eight waves ask for at once.
+  // No branch surrounds a load, so the counting of outstanding loads stays exact; every wave runs every iteration
+  // (and every barrier), whether it has rows or not.
   Fetched fa, fb;
   fetch(fa, fetch_ids(0), 0);
   fetch(fb, fetch_ids(1), 1);
-  TileIds ids_nxt = fetch_ids(2);
-  publish(fa, 0, 0);
-  fetch(fa, ids_nxt, 2);
-  ids_nxt = fetch_ids(3);
+  {
+    const TileIds ids2 = fetch_ids(2), ids3 = fetch_ids(3);
+    publish(fa, 0, 0, std::true_type{});
+    fetch(fa, ids2, 2);
+    publish(fb, 1, 1, std::true_type{});
+    fetch(fb, ids3, 3);
+  }
+  TileIds ids_nxt = fetch_ids(4);   // the block id of tile k + 4, asked for one iteration ahead
   __syncthreads();
-  int st_cur = 0, st_nxt = 1, st_prv = 2;   // ring stages of tiles k, k + 1, k - 1
-  // ids_nxt: the block id of tile k + 3, asked for one iteration ago
+  int st_cur = 0, st_nxt = 1, st_wr = 2;   // ring stages of tiles k, k + 1, k + 2
+  KOperands ka_even, ka_odd;               // K operands of the even / odd tile in flight
+  if (n_tiles > 0) ka_even = read_k(0);
   // what_tag: std::false_type / std::true_type = multiply without / with the per-row limits; void* = only fetch
-  auto one_tile = [&](int k, Fetched& f_pub, auto what_tag) __attribute__((always_inline)) {
+  auto one_tile = [&](int k, Fetched& f_pub, const KOperands& ka, KOperands& ka_next, auto what_tag,
+                      auto ragged_tag) __attribute__((always_inline)) {
     constexpr bool kMultiply = !std::is_pointer<decltype(what_tag)>::value;
-    KOperands ka;
-    if constexpr (kMultiply) ka = read_k(st_cur);   // on their way while the wave does its share of the fetching
-    publish(f_pub, st_nxt, k + 1);
-    fetch(f_pub, ids_nxt, k + 3);
-    ids_nxt = fetch_ids(k + 4);
-    if constexpr (kMultiply) multiply(ka, st_cur, k, what_tag);
-    const int st_free = st_prv;
-    st_prv = st_cur;
+    // (the fetching stands in front of the score products in program order and the compiler weaves it into them:
+    // a wave issues in order, so vector work finds room under matrix instructions only between them -- with the
+    // products first and everything else behind a scheduling barrier the kernel is 3-13 % slower)
+    if constexpr (kMultiply) ka_next = read_k(st_nxt);   // on their way while this tile is multiplied
+    publish(f_pub, st_wr, k + 2, ragged_tag);
+    fetch(f_pub, ids_nxt, k + 4);
+    ids_nxt = fetch_ids(k + 5);
+    if constexpr (kMultiply) {
+      const f32x16 s = scores(ka);
+      // the V operands are requested now, all eight, so that they arrive under the softmax (left to itself the
+      // compiler requests each one right before its products, and the wave sits out the LDS latency eight times)
+      const VOperands vt = read_v(st_cur);
+      finish(s, vt, st_cur, k, what_tag);
+    }
+    const int st_free = st_cur;
     st_cur = st_nxt;
-    st_nxt = st_free;
+    st_nxt = st_wr;
+    st_wr = st_free;
     __syncthreads();
   };
-  // Two tiles per round, so that the fetch registers keep their roles.  Three loops rather than tests inside one (a
-  // branch around the products would have the accumulators copied where its sides meet): the tiles every row of the
-  // wave sees whole, then the rest of what the wave sees with the per-row limits (a tile past it is masked out
-  // entirely), then the tiles only other waves need.  Every wave passes the same number of barriers.
+  // Two tiles per round, so that the fetch and operand registers keep their roles.  Three loops rather than tests
+  // inside one (a branch around the products would have the accumulators copied where its sides meet): the tiles
+  // every row of the wave sees whole, then the rest of what the wave sees with the per-row limits (a tile past it
+  // is masked out entirely), then the tiles only other waves need.  Every wave passes the same number of barriers.
   // (Measured and dropped, all with parity green: giving the two waves of a SIMD different orders of the steps of a
-  // tile -- P V of the tile before first, or the fetching after the products instead of before -- so that they would
-  // not ask for the matrix cores at the same time: 5-9 % slower than leaving both in the same order; four-wave
-  // workgroups, two per item and per CU, which do not wait for each other but fetch every tile twice: 4 % slower; a
-  // four-stage ring with the scores of tile k + 1 issued one matrix instruction at a time between the exponentials
-  // of tile k: 9 % slower; a four-stage ring filled two tiles ahead with a barrier every second tile: 6 % slower
-  // with bf16 KV, 4 % faster with e4m3.)
+  // tile, or different priorities -- whichever phase or wave is favoured, 15-30 % slower than equal priorities;
+  // four-wave workgroups, two per item and per CU, which do not wait for each other but fetch every tile twice: 4 %
+  // slower; the scores of tile k + 1 issued one matrix instruction at a time between the exponentials of tile k: 9 %
+  // slower.)
+  // (the first loop also stops short of the item's last complete tiles, so that the tiles it publishes -- two and
+  // three ahead -- are complete ones and need no zeroing of rows past the range)
+  const int n_fast = min(n_whole, (tok_end - tok_begin) / kTile - 2);
   int k = 0;
-  for (; k + 2 <= n_whole; k += 2) {
-    one_tile(k, fb, std::false_type{});
-    one_tile(k + 1, fa, std::false_type{});
+  for (; k + 2 <= n_fast; k += 2) {
+    one_tile(k, fa, ka_even, ka_odd, std::false_type{}, std::false_type{});
+    one_tile(k + 1, fb, ka_odd, ka_even, std::false_type{}, std::false_type{});
   }
   for (; k < n_tiles; k += 2) {
-    one_tile(k, fb, std::true_type{});
-    one_tile(k + 1, fa, std::true_type{});
+    one_tile(k, fa, ka_even, ka_odd, std::true_type{}, std::true_type{});
+    one_tile(k + 1, fb, ka_odd, ka_even, std::true_type{}, std::true_type{});
   }
   for (; k < n_tiles_wg; k += 2) {
-    one_tile(k, fb, static_cast<void*>(nullptr));
-    one_tile(k + 1, fa, static_cast<void*>(nullptr));
+    one_tile(k, fa, ka_even, ka_odd, static_cast<void*>(nullptr), std::true_type{});
+    one_tile(k + 1, fb, ka_odd, ka_even, static_cast<void*>(nullptr), std::true_type{});
   }
 
-  // ---- one partial state per row, straight from the accumulators: lane (n, kg) holds O[row n][32 kg + 8 j + cc]
+  // ---- one partial state per row, straight from the accumulators: register r of column class x is column
+  // 64 (r / 4 % 2) + 32 g + 8 (r % 4) + 4 (r / 8) + x of this lane's row
+  if (has_rows) {
+    float l = l_run;
+    l += lane_xor(l, 32);
+    if (req_of >= 0) {
+      const float inv = l > 0.f ? 1.f / l : 0.f;
+      const int row = row_base + (lane & 31);
+      const int h = kv_head * G + row % G;
+      const int64_t slot = int64_t(p.slot_base[req_of]) + split_local;
+      float* o = p.ws_o + (slot * p.num_q_heads + h) * kD + 32 * g;
 #pragma unroll
-  for (int t = 0; t < kNT; ++t) {
-    if (t < nt_used) {
-      float l = l_run[t];
-      l += lane_xor(l, 16);
-      l += lane_xor(l, 32);
-      if (req_of[t] >= 0) {
-        const float inv = l > 0.f ? 1.f / l : 0.f;
-        const int row = row_base + 16 * t + n;
-        const int h = kv_head * G + row % G;
-        const int64_t slot = int64_t(p.slot_base[req_of[t]]) + split_local;
-        float* o = p.ws_o + (slot * p.num_q_heads + h) * kD + 32 * kg;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          *reinterpret_cast<f32x4*>(o + 8 * j) =
-              f32x4{acc[t][0][j], acc[t][1][j], acc[t][2][j], acc[t][3][j]} * inv;
-          *reinterpret_cast<f32x4*>(o + 8 * j + 4) =
-              f32x4{acc[t][4][j], acc[t][5][j], acc[t][6][j], acc[t][7][j]} * inv;
-        }
-        if (kg == 0)
-          p.ws_lse[slot * p.num_q_heads + h] = l > 0.f ? (m_run[t] + __builtin_amdgcn_logf(l)) * kLn2 : neg_inf;
-      }
+      for (int r = 0; r < 16; ++r)
+        *reinterpret_cast<f32x4*>(o + 64 * ((r >> 2) & 1) + 8 * (r & 3) + 4 * (r >> 3)) =
+            f32x4{acc[0][r], acc[1][r], acc[2][r], acc[3][r]} * inv;
+      if (g == 0)
+        p.ws_lse[slot * p.num_q_heads + h] = l > 0.f ? (m_run + __builtin_amdgcn_logf(l)) * kLn2 : neg_inf;
     }
   }
 }
