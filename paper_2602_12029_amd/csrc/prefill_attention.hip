@@ -96,6 +96,74 @@ __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnPara
   const bool has_rows = rows > row_base;   // a wave without rows only fetches
   const float neg_inf = -__builtin_inff();
 
+  // ---- addressing: block base in SGPRs (a buffer descriptor per 16-token block), loop-invariant lane offsets
+  const int sub_shift = __builtin_ctz(unsigned(p.block_size >> 4));
+  const int sub_mask = (p.block_size >> 4) - 1;
+  constexpr int kEsz = KVT == PS_BF16 ? 2 : 1;
+  const int tok_bytes = int(p.s_tok) * kEsz;
+  const int kv_bytes = int(p.s_kv) * kEsz;
+  const int64_t head_base = reinterpret_cast<int64_t>(p.kv) + int64_t(kv_head) * p.s_head * kEsz;
+  const uint32_t blk_bytes = uint32_t(p.s_block * kEsz);
+  const int sub_bytes = 16 * tok_bytes;
+  const int sub0 = tok_begin >> 4;
+  int sub_end = (tok_end + 15) >> 4;   // (narrowed below to what some row of the workgroup sees)
+  // What this wave fetches of every tile, all of it from one 16-token block (fblk) so that one block id and one
+  // buffer descriptor per tile do.  K: token n of the block, elements 32 kst + 8 kg .. + 7 -- that is lane
+  // (16 fblk + n, kg % 2) of the operand of k-step 2 kst + kg / 2.  V: the pair of token rows (vrow, vrow + 1), columns
+  // 8 n + 4 (kg % 2) + x, x = 0 .. 3 -- the pair is register wave % 4 of lane (n + 16 (kg % 2), kg / 2) = this very
+  // lane in the operand of column class x and step fblk; the operand's row lane % 32 is thus column
+  // 8 (lane % 16) + 4 (lane / 16 % 2) + x, which the epilogue undoes.
+  const int fblk = wave >> 2, kst = wave & 3;
+  const int vreg = wave & 3;
+  const int vrow = 4 * (kg >> 1) + 8 * ((wave >> 1) & 1) + 2 * (wave & 1);
+  const int k_lane_off = n * tok_bytes + (32 * kst + 8 * kg) * kEsz;
+  const int v_lane_off = kv_bytes + vrow * tok_bytes + (8 * n + 4 * (kg & 1)) * kEsz;
+  const int k_op = 2 * kst + (kg >> 1), k_slot = 16 * fblk + n + 32 * (kg & 1);
+  // (constant address space: the table is read-only for the kernel's lifetime, which keeps the load a scalar one
+  // whatever stands around it)
+  typedef const __attribute__((address_space(4))) int32_t* const_i32_ptr;
+  const const_i32_ptr blk_seg = (const_i32_ptr)(p.blk + blk_off);
+
+  struct TileIds { int id; };   // of this wave's block of the tile
+  auto fetch_ids = [&](int k) __attribute__((always_inline)) {   // wave-uniform
+    // no branch around this load (the index is clamped into the range instead), so that the counting of
+    // outstanding loads in the streaming loop stays exact; a block past the range is never fetched from
+    TileIds r;
+    const int sub = max(sub0, min(sub0 + 2 * k + fblk, sub_end - 1));
+    r.id = blk_seg[sub >> sub_shift];
+    return r;
+  };
+  // this wave's share of a tile, as loaded
+  struct Fetched {
+    std::conditional_t<KVT == PS_BF16, u32x4, u32x2> k;         // 8 elements of one token
+    std::conditional_t<KVT == PS_BF16, u32x2, uint32_t> v[2];   // 4 columns of two token rows
+    f32x2 sc;                                                   // e4m3: K and V scale of the block
+  };
+  auto fetch = [&](Fetched& f, const TileIds& ids, int k) __attribute__((always_inline)) {
+    const int sub = sub0 + 2 * k + fblk;
+    const bool valid = sub < sub_end;   // a block past the range gets a zero-sized descriptor: zeros, no traffic
+    const uint64_t addr = uint64_t(head_base) + uint64_t(uint32_t(ids.id)) * blk_bytes + uint32_t((sub & sub_mask) * sub_bytes);
+    const __amdgpu_buffer_rsrc_t rs =
+        __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(addr), 0, valid ? 0x7fffffff : 0, 0x00020000);
+    if constexpr (KVT == PS_BF16) {
+      f.k = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off, 0, 0);
+      f.v[0] = __builtin_amdgcn_raw_buffer_load_b64(rs, v_lane_off, 0, 0);
+      f.v[1] = __builtin_amdgcn_raw_buffer_load_b64(rs, v_lane_off, tok_bytes, 0);
+    } else {
+      f.k = __builtin_amdgcn_raw_buffer_load_b64(rs, k_lane_off, 0, 0);
+      f.v[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, v_lane_off, 0, 0);
+      f.v[1] = __builtin_amdgcn_raw_buffer_load_b32(rs, v_lane_off, tok_bytes, 0);
+      // (the block id is clamped into the range, so the scales of a tile past it are some block's: never used)
+      f.sc = *reinterpret_cast<const f32x2*>(p.scales + (int64_t(ids.id) * p.num_kv_heads + kv_head) * 2);
+    }
+  };
+  // The first two tiles and the block ids of the next two are requested at once, from the item's header alone: what
+  // the rows see (request list -> visible lengths) is another two round trips to memory, which these need not wait for.
+  Fetched fa, fb;
+  fetch(fa, fetch_ids(0), 0);
+  fetch(fb, fetch_ids(1), 1);
+  const TileIds ids2 = fetch_ids(2), ids3 = fetch_ids(3);
+
   // ---- this lane's query row (row lane % 32 of the wave): request, visible length, and the row itself as the
   // eight B operands of S^T = K Q^T (k-step st, lane group g: elements 16 st + 8 g .. + 7)
   int req_of = -1, lim = 0;   // a padding row sees nothing
@@ -128,64 +196,8 @@ __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnPara
   const int n_tiles = has_rows ? (see_end - tok_begin + kTile - 1) / kTile : 0;   // tiles this wave multiplies
   const int n_whole = min(n_tiles, max(0, (see_all - tok_begin) / kTile));   // ... of which these need no per-row limit
 
-  // ---- addressing: block base in SGPRs (a buffer descriptor per 16-token block), loop-invariant lane offsets
-  const int sub_shift = __builtin_ctz(unsigned(p.block_size >> 4));
-  const int sub_mask = (p.block_size >> 4) - 1;
-  constexpr int kEsz = KVT == PS_BF16 ? 2 : 1;
-  const int tok_bytes = int(p.s_tok) * kEsz;
-  const int kv_bytes = int(p.s_kv) * kEsz;
-  const int64_t head_base = reinterpret_cast<int64_t>(p.kv) + int64_t(kv_head) * p.s_head * kEsz;
-  const uint32_t blk_bytes = uint32_t(p.s_block * kEsz);
-  const int sub_bytes = 16 * tok_bytes;
-  const int sub0 = tok_begin >> 4;
-  const int sub_end = (see_end_wg + 15) >> 4;
-  // What this wave fetches of every tile, all of it from one 16-token block (fblk) so that one block id and one
-  // buffer descriptor per tile do.  K: token n of the block, elements 32 kst + 8 kg .. + 7 -- that is lane
-  // (16 fblk + n, kg % 2) of the operand of k-step 2 kst + kg / 2.  V: the pair of token rows (vrow, vrow + 1), columns
-  // 8 n + 4 (kg % 2) + x, x = 0 .. 3 -- the pair is register wave % 4 of lane (n + 16 (kg % 2), kg / 2) = this very
-  // lane in the operand of column class x and step fblk; the operand's row lane % 32 is thus column
-  // 8 (lane % 16) + 4 (lane / 16 % 2) + x, which the epilogue undoes.
-  const int fblk = wave >> 2, kst = wave & 3;
-  const int vreg = wave & 3;
-  const int vrow = 4 * (kg >> 1) + 8 * ((wave >> 1) & 1) + 2 * (wave & 1);
-  const int k_lane_off = n * tok_bytes + (32 * kst + 8 * kg) * kEsz;
-  const int v_lane_off = kv_bytes + vrow * tok_bytes + (8 * n + 4 * (kg & 1)) * kEsz;
-  const int k_op = 2 * kst + (kg >> 1), k_slot = 16 * fblk + n + 32 * (kg & 1);
-  const int32_t* blk_seg = p.blk + blk_off;
+  sub_end = (see_end_wg + 15) >> 4;   // blocks past it are not fetched: nobody sees them
 
-  struct TileIds { int id; };   // of this wave's block of the tile
-  auto fetch_ids = [&](int k) __attribute__((always_inline)) {   // wave-uniform
-    // no branch around this load (the index is clamped into the range instead), so that the counting of
-    // outstanding loads in the streaming loop stays exact; a block past the range is never fetched from
-    TileIds r;
-    const int sub = max(sub0, min(sub0 + 2 * k + fblk, sub_end - 1));
-    r.id = __builtin_amdgcn_readfirstlane(blk_seg[sub >> sub_shift]);
-    return r;
-  };
-  // this wave's share of a tile, as loaded
-  struct Fetched {
-    std::conditional_t<KVT == PS_BF16, u32x4, u32x2> k;         // 8 elements of one token
-    std::conditional_t<KVT == PS_BF16, u32x2, uint32_t> v[2];   // 4 columns of two token rows
-    f32x2 sc;                                                   // e4m3: K and V scale of the block
-  };
-  auto fetch = [&](Fetched& f, const TileIds& ids, int k) __attribute__((always_inline)) {
-    const int sub = sub0 + 2 * k + fblk;
-    const bool valid = sub < sub_end;   // a block past the range gets a zero-sized descriptor: zeros, no traffic
-    const uint64_t addr = uint64_t(head_base) + uint64_t(uint32_t(ids.id)) * blk_bytes + uint32_t((sub & sub_mask) * sub_bytes);
-    const __amdgpu_buffer_rsrc_t rs =
-        __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void*>(addr), 0, valid ? 0x7fffffff : 0, 0x00020000);
-    if constexpr (KVT == PS_BF16) {
-      f.k = __builtin_amdgcn_raw_buffer_load_b128(rs, k_lane_off, 0, 0);
-      f.v[0] = __builtin_amdgcn_raw_buffer_load_b64(rs, v_lane_off, 0, 0);
-      f.v[1] = __builtin_amdgcn_raw_buffer_load_b64(rs, v_lane_off, tok_bytes, 0);
-    } else {
-      f.k = __builtin_amdgcn_raw_buffer_load_b64(rs, k_lane_off, 0, 0);
-      f.v[0] = __builtin_amdgcn_raw_buffer_load_b32(rs, v_lane_off, 0, 0);
-      f.v[1] = __builtin_amdgcn_raw_buffer_load_b32(rs, v_lane_off, tok_bytes, 0);
-      // (the block id is clamped into the range, so the scales of a tile past it are some block's: never used)
-      f.sc = *reinterpret_cast<const f32x2*>(p.scales + (int64_t(ids.id) * p.num_kv_heads + kv_head) * 2);
-    }
-  };
   // ... and its way into the ring: K as it is (e4m3: converted), V transposed -- register vreg of this lane's slot
   // in the operand of column class x holds column 8 n + 4 (kg % 2) + x of the token rows (vrow, vrow + 1)
   // ragged_tag: std::true_type = the tile may be the item's last, which can reach past its range
@@ -363,16 +375,10 @@ __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnPara
   // tile thus start right behind the barrier instead of waiting for operands that all eight waves ask for at once.
   // No branch surrounds a load, so the counting of outstanding loads stays exact; every wave runs every iteration
   // (and every barrier), whether it has rows or not.
-  Fetched fa, fb;
-  fetch(fa, fetch_ids(0), 0);
-  fetch(fb, fetch_ids(1), 1);
-  {
-    const TileIds ids2 = fetch_ids(2), ids3 = fetch_ids(3);
-    publish(fa, 0, 0, std::true_type{});
-    fetch(fa, ids2, 2);
-    publish(fb, 1, 1, std::true_type{});
-    fetch(fb, ids3, 3);
-  }
+  publish(fa, 0, 0, std::true_type{});
+  fetch(fa, ids2, 2);
+  publish(fb, 1, 1, std::true_type{});
+  fetch(fb, ids3, 3);
   TileIds ids_nxt = fetch_ids(4);   // the block id of tile k + 4, asked for one iteration ahead
   __syncthreads();
   int st_cur = 0, st_nxt = 1, st_wr = 2;   // ring stages of tiles k, k + 1, k + 2
@@ -410,7 +416,9 @@ __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnPara
   // tile, or different priorities -- whichever phase or wave is favoured, 15-30 % slower than equal priorities;
   // four-wave workgroups, two per item and per CU, which do not wait for each other but fetch every tile twice: 4 %
   // slower; the scores of tile k + 1 issued one matrix instruction at a time between the exponentials of tile k: 9 %
-  // slower.)
+  // slower with the 16x16x32 products, and with the 32x32x16 ones, where the compiler weaves the two by itself, 2 %
+  // faster with bf16 KV and 4 % slower with e4m3 than requesting the K operands a tile ahead, which the registers
+  // do not allow next to it.)
   // (the first loop also stops short of the item's last complete tiles, so that the tiles it publishes -- two and
   // three ahead -- are complete ones and need no zeroing of rows past the range)
   const int n_fast = min(n_whole, (tok_end - tok_begin) / kTile - 2);
