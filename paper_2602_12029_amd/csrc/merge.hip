@@ -36,10 +36,14 @@ __global__ __launch_bounds__(256) void merge_states_kernel(const int32_t* __rest
     f32x4 o[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int s = min(b0 + i, s1 - 1);   // slots past the end re-read the last one and get weight zero below
-      lse[i] = ws_lse[int64_t(s) * num_q_heads + h];
-      o[i] = *reinterpret_cast<const f32x4*>(ws_o + (int64_t(s) * num_q_heads + h) * head_dim + 4 * c4);
-      if (b0 + i >= s1) lse[i] = neg_inf;
+      lse[i] = neg_inf;                    // a slot past the end has weight zero and is not read
+      o[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      if (b0 + i < s1) {
+        const int64_t s = b0 + i;
+        lse[i] = ws_lse[s * num_q_heads + h];
+        // the states are read once: non-temporal
+        o[i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(ws_o + (s * num_q_heads + h) * head_dim + 4 * c4));
+      }
     }
     const float bm = fmaxf(fmaxf(fmaxf(lse[0], lse[1]), fmaxf(lse[2], lse[3])), mx);
     if (bm == neg_inf) continue;           // nothing but empty states so far
