@@ -281,7 +281,7 @@ def main_ingest(args):
         opool = ol.BlockPool(w.num_blocks, w.free_order)
         olay = ol.build_layout(opool, g.block_size, w.prefix_len, w.req_prompt, w.req_model, w.suffix_len)
         line["cpu_baseline"] = cpu_ingest_baseline(w, olay, pre, args.cpu_seconds)
-    print(json.dumps(line))
+    return line
 
 
 PEAK_MFMA_BF16_TFLOPS = 2500.0
@@ -379,7 +379,7 @@ def main_stage(args):
         line["cpu_baseline"] = {"value": reps * moved / wall / 1e9, "unit": "GB/s",
                                 "cores": max(1, int(round((time.process_time() - cpu0) / wall))), "kind": "oracle",
                                 "sample": f"numpy oracle, {reps} round trips of the whole batch, {wall:.1f} s wall"}
-    print(json.dumps(line))
+    return line
 
 
 def cpu_prefill_baseline(w, visible, data, seconds):
@@ -498,7 +498,7 @@ def main_prefill(args):
     }
     if args.cpu_seconds > 0:
         line["cpu_baseline"] = cpu_prefill_baseline(w, visible, data, args.cpu_seconds)
-    print(json.dumps(line))
+    return line
 
 
 def measure_loop(args, name, steps, warmup, random_kv=False):
@@ -817,11 +817,11 @@ def main():
         sys.exit("bench.py: this build runs the decode attention of ONE GPU (no collectives, no sharding); "
                  "use --gpus 1")
     if args.path == "ingest":
-        return main_ingest(args)
+        return print(json.dumps(main_ingest(args)))
     if args.path == "prefill":
-        return main_prefill(args)
+        return print(json.dumps(main_prefill(args)))
     if args.path == "stage":
-        return main_stage(args)
+        return print(json.dumps(main_stage(args)))
     if args.path == "loop":
         return main_loop(args)
     if args.path == "probe":
@@ -862,6 +862,26 @@ def main():
             per[name]["loop"] = {"ms_per_step": lp["ms_per_step"], "value": lp["value"], "unit": "GB/s",
                                  "host_append_ms_per_step": lp["host_ms_per_step"]}
         line["per_config"] = per
+        # the paths around the decode step, each a short run of its own `--path` line (no oracle leg): hand-off of
+        # the batch's KV into the pool, partial prefill of newly appended context tokens, staging out and back
+        import copy
+        other = {}
+        for key, fn, over in (("ingest_b8", main_ingest, {"workload": "b8"}),
+                              ("ingest_fp8_70b", main_ingest, {"workload": "fp8_70b"}),
+                              ("prefill_b8", main_prefill, {"workload": "prefill_b8"}),
+                              ("prefill_fp8", main_prefill, {"workload": "prefill_fp8"}),
+                              ("stage_b8", main_stage, {"workload": "b8"})):
+            a = copy.copy(args)
+            a.cpu_seconds, a.steps, a.warmup, a.models, a.no_events = 0.0, 30, 5, 0, False
+            for k, v in over.items():
+                setattr(a, k, v)
+            r = fn(a)
+            rf = r.get("roofline") or {}
+            other[key] = {"metric": r["metric"], "ms_per_step": r["ms_per_step"], "value": r["value"], "unit": r["unit"],
+                          "roofline_bound": rf.get("bound"), "roofline_kernel": rf.get("kernel"),
+                          "roofline_frac": rf.get("frac"), "kernel_ms": rf.get("kernel_ms")}
+            torch.cuda.empty_cache()
+        line["other_paths"] = other
     print(json.dumps(line))
 
 
