@@ -50,6 +50,7 @@ struct KvWriteParams {
   const int32_t* blk;        // concatenated block array
   const int32_t* ent_tok0;   // per entry: its first token in the ragged source of its kind
   const int32_t* ent_valid;  // per entry: tokens stored in the block
+  const int32_t* ent_order;  // per entry position: the entry of its kind an ingest takes there (by physical block)
   const int32_t* dest;       // [R] block * B + slot of the token being appended, -1 = none
   void* kv;
   float* scales;
@@ -80,7 +81,7 @@ __global__ __launch_bounds__(256) void ingest_copy_kernel(KvWriteParams p, const
     const int64_t tile = min(tile0 + i, num_tiles - 1);
     const int which = int(tile & 1);
     const int h = int((tile >> 1) % p.num_kv_heads);
-    const int e = entry0 + int((tile >> 1) / p.num_kv_heads);
+    const int e = entry0 + p.ent_order[entry0 + int((tile >> 1) / p.num_kv_heads)];
     // a block adopted from another layout has no valid tokens here: its contents are already there
     chunks[i] = tile0 + i < num_tiles ? max(0, p.ent_valid[e]) * cpt : 0;
     most = max(most, chunks[i]);
@@ -124,7 +125,7 @@ __global__ __launch_bounds__(256) void ingest_e4m3_kernel(KvWriteParams p, const
   if (tile >= uint32_t(num_entries) * uint32_t(p.num_kv_heads) * 2u) return;
   const int which = int(tile & 1u);
   const int h = int((tile >> 1) % uint32_t(p.num_kv_heads));
-  const int e = entry0 + int((tile >> 1) / uint32_t(p.num_kv_heads));
+  const int e = entry0 + p.ent_order[entry0 + int((tile >> 1) / uint32_t(p.num_kv_heads))];
   const int n_valid = p.ent_valid[e];
   if (n_valid <= 0) return;   // a block adopted from another layout: contents and scale are already there
   const uint16_t* src = (which ? src_v : src_k) + int64_t(p.ent_tok0[e]) * src_s_tok + int64_t(h) * src_s_head;
@@ -332,6 +333,7 @@ KvWriteParams make_write_params(const ps_layout* lay, const void* dev_tables, vo
   p.blk = t + lay->off_blk;
   p.ent_tok0 = t + lay->off_ent_tok0;
   p.ent_valid = t + lay->off_ent_valid;
+  p.ent_order = t + lay->off_ent_order;
   p.dest = t + lay->off_dest;
   p.kv = kv;
   p.scales = scales;

@@ -93,6 +93,8 @@ struct ps_layout {
   }
   // directory entries (first source token, valid tokens) of the shared segments' blocks: prefixes, then roots
   std::vector<int32_t> ent_fixed_tok0, ent_fixed_valid;
+  // ... and the order in which an ingest walks them: by physical block, within each kind
+  std::vector<int32_t> ent_fixed_order;
 
   // where the token of the most recent ps_layout_append went: block * B + slot per request, -1 = none
   std::vector<int32_t> append_dest;
@@ -103,8 +105,9 @@ struct ps_layout {
   int64_t off_visible = 0;           // int32[R]: effective visible prefix length of every request
   // for the cache-writing kernels, per entry of the concatenated block array: index of its first token in the
   // ragged source tensor of its kind (prefixes back to back / suffixes back to back) and its number of valid
-  // tokens; then append_dest
-  int64_t off_ent_tok0 = 0, off_ent_valid = 0, off_dest = 0;
+  // tokens; then append_dest; then, per entry position, the entry (relative to its kind's first) an ingest takes
+  // there
+  int64_t off_ent_tok0 = 0, off_ent_valid = 0, off_dest = 0, off_ent_order = 0;
 };
 
 // Waves per SIMD the MFMA kernel is built for, by the widest row group it must carry.
