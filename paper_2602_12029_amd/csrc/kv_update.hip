@@ -50,7 +50,7 @@ struct KvWriteParams {
   const int32_t* blk;        // concatenated block array
   const int32_t* ent_tok0;   // per entry: its first token in the ragged source of its kind
   const int32_t* ent_valid;  // per entry: tokens stored in the block
-  const int32_t* ent_order;  // per entry position: the entry of its kind an ingest takes there (by physical block)
+  const int32_t* ent_order;  // per entry position: the entry an ingest or stage-in takes there (shared kinds by physical block)
   const int32_t* dest;       // [R] block * B + slot of the token being appended, -1 = none
   void* kv;
   float* scales;
@@ -81,7 +81,7 @@ __global__ __launch_bounds__(256) void ingest_copy_kernel(KvWriteParams p, const
     const int64_t tile = min(tile0 + i, num_tiles - 1);
     const int which = int(tile & 1);
     const int h = int((tile >> 1) % p.num_kv_heads);
-    const int e = entry0 + p.ent_order[entry0 + int((tile >> 1) / p.num_kv_heads)];
+    const int e = p.ent_order[entry0 + int((tile >> 1) / p.num_kv_heads)];
     // a block adopted from another layout has no valid tokens here: its contents are already there
     chunks[i] = tile0 + i < num_tiles ? max(0, p.ent_valid[e]) * cpt : 0;
     most = max(most, chunks[i]);
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(256) void ingest_e4m3_kernel(KvWriteParams p, const
   if (tile >= uint32_t(num_entries) * uint32_t(p.num_kv_heads) * 2u) return;
   const int which = int(tile & 1u);
   const int h = int((tile >> 1) % uint32_t(p.num_kv_heads));
-  const int e = entry0 + p.ent_order[entry0 + int((tile >> 1) / uint32_t(p.num_kv_heads))];
+  const int e = p.ent_order[entry0 + int((tile >> 1) / uint32_t(p.num_kv_heads))];
   const int n_valid = p.ent_valid[e];
   if (n_valid <= 0) return;   // a block adopted from another layout: contents and scale are already there
   const uint16_t* src = (which ? src_v : src_k) + int64_t(p.ent_tok0[e]) * src_s_tok + int64_t(h) * src_s_head;
@@ -287,15 +287,19 @@ __global__ __launch_bounds__(256) void stage_copy_kernel(KvWriteParams p, uint8_
     live[i] = tile0 + i < num_tiles;
     const int which = int(tile & 1);
     const int h = int((tile >> 1) % p.num_kv_heads);
-    const int e = int((tile >> 1) / p.num_kv_heads);
+    // Into the pool the shared blocks are walked in the order of their addresses there, so that the scattered side of
+    // the copy is the read of the image (scattered writes cost more); out of it in table order, for the same reason.
+    const int pos = int((tile >> 1) / p.num_kv_heads);
+    const int e = TO_IMAGE ? pos : p.ent_order[pos];
+    const int64_t image_tile_index = (int64_t(e) * p.num_kv_heads + h) * 2 + which;
     const int id = p.blk[e];
     pool_tile[i] = static_cast<uint8_t*>(p.kv) +
                    (int64_t(id) * p.s_block + int64_t(h) * p.s_head + int64_t(which) * p.s_kv) * elem_bytes;
-    image_tile[i] = image + tile * int64_t(p.block_size) * row_bytes;
+    image_tile[i] = image + image_tile_index * int64_t(p.block_size) * row_bytes;
     if (image_scales && lane == 0 && live[i]) {
       float* pool_scale = p.scales + (int64_t(id) * p.num_kv_heads + h) * 2 + which;
-      if (TO_IMAGE) image_scales[tile] = *pool_scale;
-      else *pool_scale = image_scales[tile];
+      if (TO_IMAGE) image_scales[image_tile_index] = *pool_scale;
+      else *pool_scale = image_scales[image_tile_index];
     }
   }
   // every load of a step (four 16-byte pieces per lane and tile) goes out before the first store

@@ -454,9 +454,11 @@ int32_t ps_blob_build(ps_layout* lay) {
       return PS_ERR_INVALID_ARG;
     lay->append_dest.resize(size_t(R), -1);
     std::copy(lay->append_dest.begin(), lay->append_dest.end(), b + lay->off_dest);
+    // (entries of the concatenated block array: the shared kinds by block, the private segments as stored)
     std::copy(lay->ent_fixed_order.begin(), lay->ent_fixed_order.begin() + total_prefix_blocks, b + lay->off_ent_order);
-    std::copy(lay->ent_fixed_order.begin() + total_prefix_blocks, lay->ent_fixed_order.end(), b + lay->off_ent_order + root_blk0);
-    std::iota(b + lay->off_ent_order + total_prefix_blocks, b + lay->off_ent_order + root_blk0, 0);   // private segments: as stored
+    std::iota(b + lay->off_ent_order + total_prefix_blocks, b + lay->off_ent_order + root_blk0, total_prefix_blocks);
+    for (size_t i = 0; i < lay->root_blk.size(); ++i)
+      b[lay->off_ent_order + root_blk0 + int64_t(i)] = root_blk0 + lay->ent_fixed_order[size_t(total_prefix_blocks) + i];
   }
   auto fill = [&](const ps_layout::schedule& s, const packed& pk) {
     if (pk.items.empty()) return;

@@ -105,8 +105,8 @@ struct ps_layout {
   int64_t off_visible = 0;           // int32[R]: effective visible prefix length of every request
   // for the cache-writing kernels, per entry of the concatenated block array: index of its first token in the
   // ragged source tensor of its kind (prefixes back to back / suffixes back to back) and its number of valid
-  // tokens; then append_dest; then, per entry position, the entry (relative to its kind's first) an ingest takes
-  // there
+  // tokens; then append_dest; then, per entry position, the entry an ingest or a stage-in takes there (every kind
+  // keeps its range of positions)
   int64_t off_ent_tok0 = 0, off_ent_valid = 0, off_dest = 0, off_ent_order = 0;
 };
 
