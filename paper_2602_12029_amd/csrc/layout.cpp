@@ -79,9 +79,10 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   total *= g.num_kv_heads;
   // Aim for about one full-size chunk per compute unit: long items amortise the per-item merge and keep
   // the number of partial states (workspace traffic) low; the many small suffix items fill the gaps.  Where the
-  // kernel runs two workgroups per compute unit the aim is 0.8 of that, 1.6 times a workgroup's share: with
+  // kernel runs two workgroups per compute unit the aim is 0.6 of that, 1.2 times a workgroup's share: with
   // segments of unequal lengths the heaviest workgroups otherwise run on alone at the end of the launch (measured on
-  // 20 to 40 concurrent sessions with contexts of 1024 to 6144 tokens: 7 to 10 % faster, none slower by more than 1 %).
+  // 20 to 60 concurrent sessions with contexts of 1024 to 6144 tokens: 2 to 10 % faster, none slower by more than
+  // 0.5 %; any factor from 0.5 to 0.8 does about as well).
   // Shared segments of (nearly) equal lengths are cut as before: whole segments then pair up evenly on the compute
   // units by themselves, and the 4096-token prefixes of the 8B-shaped configuration are 2-3 % slower in halves.
   int32_t widest = group;   // rows of the widest item per KV head, for the kernel's residency
@@ -96,7 +97,7 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   int32_t shortest = INT32_MAX, longest = 0;   // of the shared segments
   for (int32_t l : lay->prefix_len) { shortest = std::min(shortest, l); longest = std::max(longest, l); }
   const bool unequal = longest > 0 && int64_t(longest) * 10 > int64_t(shortest) * 11;
-  const int64_t ideal = std::max<int64_t>(1, ceil_div(two_per_cu && unequal ? total * 4 / 5 : total, int64_t(num_cus)));
+  const int64_t ideal = std::max<int64_t>(1, ceil_div(two_per_cu && unequal ? total * 3 / 5 : total, int64_t(num_cus)));
   auto pick = [&](int32_t asked) -> int64_t {
     if (asked > 0) return round_up(asked, granule);
     return std::min<int64_t>(std::max<int64_t>(round_up(ideal, granule), round_up(256, granule)), round_up(kPsMfmaMaxChunk, granule));
