@@ -735,3 +735,24 @@ def test_plan_stays_valid_over_many_decode_steps(tree):
             assert key(sch["items"]) == key(plan["items"])
     B.ps_layout_release(pool, lay)
     B.ps_pool_destroy(pool)
+
+
+def test_chunk_aim_follows_the_spread_of_the_shared_segments():
+    """Where two workgroups share a compute unit, shared segments of unequal lengths are cut at 0.6 of a compute
+    unit's share of the batch's token-heads, segments of equal length at a whole share (the split plan is this build's
+    own design: the paper has no kernel; the rule is a measured one, see the planner)."""
+    def prefix_item_tokens(name, num_cus=256):
+        w = wl.named_workload(name)
+        pool, lay, _, _ = _both(w)
+        B.ps_layout_replan(lay, B.plan_options(0, 0, 0, 0, num_cus, 0))
+        items = B.ps_layout_plan(lay, w.num_requests)["items"]
+        shared = items[items[:, 7] & 1 == 0]
+        total = (int(w.prefix_len.astype(np.int64).sum()) + int(w.suffix_len.astype(np.int64).sum())) * w.geometry.num_kv_heads
+        B.ps_layout_release(pool, lay)
+        B.ps_pool_destroy(pool)
+        return (shared[:, 2] - shared[:, 1]), total
+    tok, total = prefix_item_tokens("sessions40")              # contexts of 1024 .. 6144 tokens, 16 rows per group
+    aim = -(-(total * 3 // 5) // 256)
+    assert tok.max() <= -(-aim // 32) * 32 and tok.max() > aim // 2
+    tok, _ = prefix_item_tokens("b8")                          # 32 prefixes of 4096 tokens: stay whole
+    assert set(tok.tolist()) == {4096}
