@@ -418,7 +418,8 @@ __global__ __launch_bounds__(64 * kWaves) void prefill_attention_kernel(AttnPara
   // slower; the scores of tile k + 1 issued one matrix instruction at a time between the exponentials of tile k: 9 %
   // slower with the 16x16x32 products, and with the 32x32x16 ones, where the compiler weaves the two by itself, 2 %
   // faster with bf16 KV and 4 % slower with e4m3 than requesting the K operands a tile ahead, which the registers
-  // do not allow next to it.)
+  // do not allow next to it; four waves of 64 rows, one per SIMD, every operand read feeding two matrix instructions:
+  // 18-29 % slower, a wave alone on its SIMD has nobody to cover its waits.)
   // (the first loop also stops short of the item's last complete tiles, so that the tiles it publishes -- two and
   // three ahead -- are complete ones and need no zeroing of rows past the range)
   const int n_fast = min(n_whole, (tok_end - tok_begin) / kTile - 2);
