@@ -127,13 +127,15 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
   // (by up to a quarter chunk) is not cut once more -- two halves of a context just over the aim cost an item, a
   // partial state per row and a merge more than they balance (partial-prefill batches whose contexts straddle the
   // aim: 7 % faster whole; decode batches of 60-80 sessions 1-2 % slower with the same rule, so they keep the plain
-  // one) -- as long as the pieces stay within what a work item holds.
-  const int64_t prefix_cap = resolve(opt.prefix_variant) == PS_VARIANT_MFMA ? mfma_cap : INT64_MAX;
+  // one).
+  // (the prefill kernel walks a range of any length -- one scalar block id per tile -- so its items are not held to
+  // the persistent kernel's 64 tiles per wave: the aim for them is the uncapped share, at most 32768 tokens)
+  const int64_t wide_chunk = opt.prefix_chunk_tokens > 0 ? prefix_chunk
+                             : std::min<int64_t>(std::max<int64_t>(round_up(ideal, granule), round_up(256, granule)), round_up(32768, granule));
   auto chunking_shared = [&](int64_t len, int64_t chunk, int32_t* n) -> int64_t {
     if (len <= 0) { *n = 0; return chunk; }
     if (opt.prefix_chunk_tokens > 0) return chunking(len, chunk, n);   // a chunk size the caller asked for is taken as it is
-    int64_t count = std::max<int64_t>(1, ceil_div(len - chunk / 4, chunk));
-    if (round_up(ceil_div(len, count), granule) > prefix_cap) count = ceil_div(len, chunk);
+    const int64_t count = std::max<int64_t>(1, ceil_div(len - chunk / 4, chunk));
     const int64_t size = round_up(ceil_div(len, count), granule);
     *n = int32_t(ceil_div(len, size));
     return size;
@@ -173,7 +175,7 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
     int32_t n = 0;
     const int32_t g0 = lay->root_group_indptr[size_t(t)], count = lay->root_group_indptr[size_t(t) + 1] - g0;
     const bool wide = limited && prefix_mfma && int64_t(count) * group > 64;
-    const int64_t size = wide ? chunking_shared(lay->root_len[size_t(t)], prefix_chunk, &n) : chunking(lay->root_len[size_t(t)], prefix_chunk, &n);
+    const int64_t size = wide ? chunking_shared(lay->root_len[size_t(t)], wide_chunk, &n) : chunking(lay->root_len[size_t(t)], prefix_chunk, &n);
     for (int32_t i = 0; i < count; ++i) nsplit_root[size_t(lay->root_group_req[size_t(g0 + i)])] = n;
     const bool row_split = limited && prefix_mfma && int64_t(count) * group > 64;
     const int32_t per_item = row_split ? std::max(1, 256 / group) : max_req;
@@ -201,7 +203,7 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
     int32_t n = 0;
     const int32_t g0 = lay->group_indptr[p], g1 = lay->group_indptr[p + 1];
     const bool wide = limited && prefix_mfma && int64_t(g1 - g0) * group > 64;   // goes to the prefill kernel
-    const int64_t size = wide ? chunking_shared(lay->prefix_len[p], prefix_chunk, &n) : chunking(lay->prefix_len[p], prefix_chunk, &n);
+    const int64_t size = wide ? chunking_shared(lay->prefix_len[p], wide_chunk, &n) : chunking(lay->prefix_len[p], prefix_chunk, &n);
     for (int32_t i = g0; i < g1; ++i) {
       const int32_t r = lay->group_req[size_t(i)];
       nsplit_prefix[size_t(r)] = int32_t(ceil_div(visible_of(r), size));
