@@ -756,3 +756,23 @@ def test_chunk_aim_follows_the_spread_of_the_shared_segments():
     assert tok.max() <= -(-aim // 32) * 32 and tok.max() > aim // 2
     tok, _ = prefix_item_tokens("b8")                          # 32 prefixes of 4096 tokens: stay whole
     assert set(tok.tolist()) == {4096}
+
+
+def test_prefill_items_take_whole_contexts_where_the_share_allows():
+    """Partial-prefill batches: a context a little over the chunk aim is not cut in two, and the prefill kernel's items
+    are not held to the persistent kernel's 8192 tokens (its ranges are walked one scalar block id per tile)."""
+    for name, contexts in (("prefill_b8", 32), ("prefill_fp8", 64)):
+        w, visible = wl.named_chunk_prefill(name)
+        pool, lay, _, _ = _both(w)
+        B.ps_layout_replan(lay, B.plan_options(0, 0, 0, 0, 256, 0))
+        B.ps_layout_set_visible(lay, w.num_requests, visible)
+        plan = B.ps_layout_plan(lay, w.num_requests)
+        _check_plan(w, lay, plan, visible)
+        items = plan["items"]
+        assert np.all(items[:, 7] & 4)                               # every group is wide: row-split items only
+        assert np.all(items[:, 1] == 0)                              # one token range per context
+        assert len(set(items[:, 0].tolist())) == contexts
+        if name == "prefill_fp8":
+            assert (items[:, 2] - items[:, 1]).max() > 8192
+        B.ps_layout_release(pool, lay)
+        B.ps_pool_destroy(pool)
