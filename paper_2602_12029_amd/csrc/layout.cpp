@@ -175,6 +175,7 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
     int32_t n = 0;
     const int32_t g0 = lay->root_group_indptr[size_t(t)], count = lay->root_group_indptr[size_t(t) + 1] - g0;
     const bool wide = limited && prefix_mfma && int64_t(count) * group > 64;
+    // (a root is seen whole by every request below it, so all its chunks go the same way)
     const int64_t size = wide ? chunking_shared(lay->root_len[size_t(t)], wide_chunk, &n) : chunking(lay->root_len[size_t(t)], prefix_chunk, &n);
     for (int32_t i = 0; i < count; ++i) nsplit_root[size_t(lay->root_group_req[size_t(g0 + i)])] = n;
     const bool row_split = limited && prefix_mfma && int64_t(count) * group > 64;
@@ -203,7 +204,16 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
     int32_t n = 0;
     const int32_t g0 = lay->group_indptr[p], g1 = lay->group_indptr[p + 1];
     const bool wide = limited && prefix_mfma && int64_t(g1 - g0) * group > 64;   // goes to the prefill kernel
-    const int64_t size = wide ? chunking_shared(lay->prefix_len[p], wide_chunk, &n) : chunking(lay->prefix_len[p], prefix_chunk, &n);
+    int64_t size = wide ? chunking_shared(lay->prefix_len[p], wide_chunk, &n) : chunking(lay->prefix_len[p], prefix_chunk, &n);
+    if (size > mfma_cap && prefix_mfma) {
+      // chunks longer than the persistent kernel's items hold are fine only while every one of them goes to the
+      // prefill kernel: a chunk that too few requests see into (64 rows or fewer) would be an ordinary item
+      for (int32_t c = 0; c < n && size > mfma_cap; ++c) {
+        int64_t seen_by = 0;
+        for (int32_t i = g0; i < g1; ++i) seen_by += visible_of(lay->group_req[size_t(i)]) > c * size;
+        if (seen_by * group <= 64) size = chunking(lay->prefix_len[p], prefix_chunk, &n);
+      }
+    }
     for (int32_t i = g0; i < g1; ++i) {
       const int32_t r = lay->group_req[size_t(i)];
       nsplit_prefix[size_t(r)] = int32_t(ceil_div(visible_of(r), size));
@@ -313,6 +323,10 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
       for (size_t c = 0; c < 8; ++c)
         if (row < column[c].size()) prefix_items[size_t(out++)] = column[c][row];
   }
+  // (what the persistent kernel is given must fit its per-wave tile directory; the cuts above see to it)
+  if (prefix_mfma)
+    for (const ps_item& it : prefix_items)
+      if (!(it.kind & kPsItemRowSplit) && it.tok_end - it.tok_begin > mfma_cap) return PS_ERR_INVALID_ARG;
   lay->num_prefix_items = int32_t(prefix_items.size());
   lay->items = std::move(prefix_items);
   lay->items.insert(lay->items.end(), suffix_items.begin(), suffix_items.end());

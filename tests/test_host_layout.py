@@ -776,3 +776,31 @@ def test_prefill_items_take_whole_contexts_where_the_share_allows():
             assert (items[:, 2] - items[:, 1]).max() > 8192
         B.ps_layout_release(pool, lay)
         B.ps_pool_destroy(pool)
+
+
+def test_long_prefill_chunks_fall_back_where_few_requests_see_far():
+    """A chunk longer than the persistent kernel's items hold is kept only if every chunk of the context goes to the
+    prefill kernel; here two of forty requests see past the first 100 tokens, so the far chunk would be an ordinary
+    8-row item and the context is cut at the ordinary size instead."""
+    geo = wl.Geometry(32, 8, 128, 16, "bf16", "bf16")
+    n, length = 40, 60000
+    w = wl.make_workload("far", geo, n, [length], [list(range(n))], [0] * n, seed=0)
+    pool, lay, _, _ = _both(w)
+    visible = np.full(n, 100, np.int32)
+    visible[-2:] = length
+    B.ps_layout_replan(lay, B.plan_options(0, 0, 0, 0, 4, 0))       # four compute units: a share of 120 k token-heads
+    B.ps_layout_set_visible(lay, n, visible)
+    plan = B.ps_layout_plan(lay, n)
+    _check_plan(w, lay, plan, visible)
+    items = plan["items"]
+    ordinary = items[(items[:, 7] & 4) == 0]
+    assert len(ordinary) and (ordinary[:, 2] - ordinary[:, 1]).max() <= 8192
+    assert (items[:, 2] - items[:, 1]).max() <= 8192
+    # all forty seeing everything: one row-split range, longer than an ordinary item may be
+    B.ps_layout_set_visible(lay, n, np.full(n, length, np.int32))
+    plan = B.ps_layout_plan(lay, n)
+    _check_plan(w, lay, plan, np.full(n, length, np.int32))
+    items = plan["items"]
+    assert np.all(items[:, 7] & 4) and (items[:, 2] - items[:, 1]).max() > 8192
+    B.ps_layout_release(pool, lay)
+    B.ps_pool_destroy(pool)
