@@ -199,12 +199,62 @@ int32_t ps_plan_build(ps_layout* lay, const ps_plan_options* user) {
           prefix_items.push_back(it);
         }
   }
+  // The prefill kernel runs one workgroup per item, one item per compute unit at a time, and its items are long: with
+  // a few items per compute unit the last round of the launch is badly filled (704 items of 132 tiles on 256 compute
+  // units: three rounds for the work of 2.75).  The contexts whose items come last -- the shortest, the launch goes
+  // heaviest first -- are therefore cut into more pieces, as many as fill the last round best; the others stay whole
+  // (one partial state per row).
+  std::vector<int32_t> tail_cut(size_t(P), 1);
+  if (limited && prefix_mfma && opt.prefix_chunk_tokens == 0) {
+    struct wide_prompt { int32_t p; int64_t items, tiles; };
+    std::vector<wide_prompt> wp;
+    int64_t n_items = 0, work = 0;
+    for (int32_t p = 0; p < P; ++p) {
+      const int64_t reqs = lay->group_indptr[p + 1] - lay->group_indptr[p];
+      if (reqs * group <= 64 || lay->prefix_len[p] <= 0) continue;
+      int32_t n0 = 0;
+      const int64_t size0 = chunking_shared(lay->prefix_len[p], wide_chunk, &n0);
+      const int64_t per_item = std::max(1, 256 / group);
+      const wide_prompt e{p, ceil_div(reqs, per_item) * g.num_kv_heads * n0, ceil_div(std::min<int64_t>(size0, lay->prefix_len[p]), 32)};
+      wp.push_back(e);
+      n_items += e.items;
+      work += e.items * e.tiles;
+    }
+    if (n_items > 0) {
+      const int64_t mean_tiles = std::max<int64_t>(1, work / n_items);
+      const int64_t rounds = work / num_cus / mean_tiles;          // rounds the whole items fill completely
+      const int64_t rest = n_items - rounds * num_cus;             // items of the last, partly filled round
+      // time of the last round in tiles, an item costing about twelve tiles beyond its own (launch, the dependent
+      // reads of its start, filling the ring, its stores; measured: pieces of 33 tiles gained nothing on 132-tile items)
+      constexpr int64_t kItemOverheadTiles = 12;
+      int64_t best_cut = 1, best_cost = INT64_MAX, whole_cost = 0;
+      for (int64_t cut : {1, 2, 3, 4, 6, 8}) {
+        if (mean_tiles / cut < 16) break;                          // pieces of at least 512 tokens
+        const int64_t cost = ceil_div(rest * cut, int64_t(num_cus)) * (ceil_div(mean_tiles, cut) + kItemOverheadTiles);
+        if (cut == 1) whole_cost = cost;
+        if (cost < best_cost) { best_cost = cost; best_cut = cut; }
+      }
+      // (worth it from 3 % of a compute unit's work on: the pieces cost their rows a partial state and a merge each)
+      if (rest > 0 && best_cut > 1 && (whole_cost - best_cost) * 100 >= 3 * (work / num_cus)) {
+        std::stable_sort(wp.begin(), wp.end(), [](const wide_prompt& x, const wide_prompt& y) { return x.tiles < y.tiles; });
+        int64_t taken = 0;
+        for (size_t i = 0; i < wp.size() && taken < rest; ++i) {
+          tail_cut[size_t(wp[i].p)] = int32_t(best_cut);
+          taken += wp[i].items;
+        }
+      }
+    }
+  }
   std::vector<int32_t> members;
   for (int32_t p = 0; p < P; ++p) {
     int32_t n = 0;
     const int32_t g0 = lay->group_indptr[p], g1 = lay->group_indptr[p + 1];
     const bool wide = limited && prefix_mfma && int64_t(g1 - g0) * group > 64;   // goes to the prefill kernel
     int64_t size = wide ? chunking_shared(lay->prefix_len[p], wide_chunk, &n) : chunking(lay->prefix_len[p], prefix_chunk, &n);
+    if (wide && tail_cut[size_t(p)] > 1 && n > 0) {
+      size = round_up(ceil_div(int64_t(lay->prefix_len[p]), int64_t(n) * tail_cut[size_t(p)]), granule);
+      n = int32_t(ceil_div(int64_t(lay->prefix_len[p]), size));
+    }
     if (size > mfma_cap && prefix_mfma) {
       // chunks longer than the persistent kernel's items hold are fine only while every one of them goes to the
       // prefill kernel: a chunk that too few requests see into (64 rows or fewer) would be an ordinary item

@@ -770,8 +770,12 @@ def test_prefill_items_take_whole_contexts_where_the_share_allows():
         _check_plan(w, lay, plan, visible)
         items = plan["items"]
         assert np.all(items[:, 7] & 4)                               # every group is wide: row-split items only
-        assert np.all(items[:, 1] == 0)                              # one token range per context
-        assert len(set(items[:, 0].tolist())) == contexts
+        # one token range per context, except the shortest contexts, whose items fill the launch's last round in pieces
+        whole = {blk for blk in set(items[:, 0].tolist()) if np.all(items[items[:, 0] == blk][:, 1] == 0)}
+        assert len(set(items[:, 0].tolist())) == contexts and len(whole) >= contexts // 2
+        cut = items[~np.isin(items[:, 0], list(whole))]
+        longest_cut = (cut[:, 2] - cut[:, 1]).max() if len(cut) else 0
+        assert longest_cut < (items[:, 2] - items[:, 1]).max()
         if name == "prefill_fp8":
             assert (items[:, 2] - items[:, 1]).max() > 8192
         B.ps_layout_release(pool, lay)
